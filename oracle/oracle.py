@@ -1,0 +1,292 @@
+"""ctypes front end of the CPU oracle (oracle/sun_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu-baseline leg.  The GPU library never imports this module and
+this module never imports the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sun_oracle.c")
+_LIB = os.path.join(_HERE, "libsun_oracle.so")
+
+F32, BF16, F64, W4 = 0, 1, 2, 3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP across independent rows/requests)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class Cfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
+                ("vocab", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double)]
+
+
+class Mat(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("rows", C.c_int32), ("cols", C.c_int32), ("group", C.c_int32),
+                ("data", C.c_void_p), ("q", C.c_void_p), ("s", C.c_void_p), ("z", C.c_void_p)]
+
+
+class Pool(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("n_pages", C.c_int64), ("page_tokens", C.c_int32), ("pad_", C.c_int32),
+                ("k_off", C.c_int64), ("k_layer", C.c_int64), ("k_page", C.c_int64), ("k_head", C.c_int64),
+                ("k_token", C.c_int64), ("k_dim", C.c_int64),
+                ("v_off", C.c_int64), ("v_layer", C.c_int64), ("v_page", C.c_int64), ("v_head", C.c_int64),
+                ("v_token", C.c_int64), ("v_dim", C.c_int64)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_silu.restype = C.c_double
+        _lib.orc_silu.argtypes = [C.c_double]
+        _lib.orc_bf16_to_double.restype = C.c_double
+        _lib.orc_bf16_to_double.argtypes = [C.c_uint16]
+        _lib.orc_double_to_bf16.restype = C.c_uint16
+        _lib.orc_double_to_bf16.argtypes = [C.c_double]
+        _lib.orc_float_to_half.restype = C.c_uint16
+        _lib.orc_float_to_half.argtypes = [C.c_float]
+        _lib.orc_half_to_float.restype = C.c_float
+        _lib.orc_half_to_float.argtypes = [C.c_uint16]
+        _lib.orc_argmax.restype = C.c_int32
+    return _lib
+
+
+def threads() -> int:
+    return int(lib().orc_threads())
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def make_cfg(shape) -> Cfg:
+    """shape: any object with the Shape fields (n_layers, hidden, ...)."""
+    return Cfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+               shape.ffn, shape.vocab, float(shape.rms_eps), float(shape.rope_base))
+
+
+_KIND = {np.dtype(np.float32): F32, np.dtype(np.uint16): BF16, np.dtype(np.float64): F64}
+
+
+def dense_mat(a: np.ndarray) -> Mat:
+    """Dense parameter; a uint16 array is read as bfloat16 bit patterns."""
+    assert a.flags["C_CONTIGUOUS"]
+    if a.ndim == 1:
+        rows, cols = 1, a.shape[0]
+    else:
+        rows, cols = a.shape
+    return Mat(_KIND[a.dtype], rows, cols, 0, _ptr(a), None, None, None)
+
+
+def w4_mat(q: np.ndarray, s: np.ndarray, z: np.ndarray, cols: int, group: int) -> Mat:
+    """Quantised parameter: q uint8 [rows, cols/2], s/z uint16 (fp16 bits) [rows, groups]."""
+    assert q.dtype == np.uint8 and s.dtype == np.uint16 and z.dtype == np.uint16
+    assert q.flags["C_CONTIGUOUS"] and s.flags["C_CONTIGUOUS"] and z.flags["C_CONTIGUOUS"]
+    return Mat(W4, q.shape[0], cols, group, None, _ptr(q), _ptr(s), _ptr(z))
+
+
+class Params:
+    """Parameter table in the order the C side expects; keeps the arrays alive."""
+
+    def __init__(self, n_layers: int):
+        self.n_layers = n_layers
+        self.mats = (Mat * (3 + 9 * n_layers))()
+        self.keep: List[object] = []
+
+    def set(self, idx: int, m: Mat, *arrays):
+        self.mats[idx] = m
+        self.keep.extend(arrays)
+
+
+LAYER_KEYS = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
+QUANT_KEYS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd")
+
+
+def params_from_arrays(w: Dict[str, object], quant: Optional[Dict[str, list]] = None,
+                       group: int = 128) -> Params:
+    """w: dict of numpy arrays (float32 / float64 / uint16-as-bf16): 'embed', 'gf', 'wlm'
+    and per-layer lists under LAYER_KEYS.  quant: optional dict key -> list of (q, s, z)
+    per layer replacing the dense matrices of QUANT_KEYS (QSUN, Appendix A.1)."""
+    nl = len(w["wq"])
+    p = Params(nl)
+    p.set(0, dense_mat(w["embed"]), w["embed"])
+    for l in range(nl):
+        for j, k in enumerate(LAYER_KEYS):
+            if quant is not None and k in quant:
+                q, s, z = quant[k][l]
+                cols = w[k][l].shape[1]
+                p.set(1 + 9 * l + j, w4_mat(q, s, z, cols, group), q, s, z)
+            else:
+                p.set(1 + 9 * l + j, dense_mat(w[k][l]), w[k][l])
+    p.set(1 + 9 * nl, dense_mat(w["gf"]), w["gf"])
+    p.set(2 + 9 * nl, dense_mat(w["wlm"]), w["wlm"])
+    return p
+
+
+def make_pool(base: np.ndarray, n_pages: int, page_tokens: int, strides: Dict[str, int]) -> Pool:
+    """base: uint16 array holding the bf16 pool.  strides: element strides with keys
+    k_off,k_layer,k_page,k_head,k_token,k_dim and the same for v_."""
+    assert base.dtype == np.uint16 and base.flags["C_CONTIGUOUS"]
+    p = Pool()
+    p.base = _ptr(base)
+    p.n_pages = n_pages
+    p.page_tokens = page_tokens
+    for k, v in strides.items():
+        setattr(p, k, int(v))
+    p._keep = base
+    return p
+
+
+def default_strides(shape, n_pages: int, page_tokens: int = 16) -> Dict[str, int]:
+    """A plain layout for CPU-only tests: [layer][page][k|v][head][token][dim]."""
+    d, hkv = shape.head_dim, shape.n_kv_heads
+    blk = page_tokens * d
+    page = 2 * hkv * blk
+    return dict(k_off=0, k_layer=n_pages * page, k_page=page, k_head=blk, k_token=d, k_dim=1,
+                v_off=hkv * blk, v_layer=n_pages * page, v_page=page, v_head=blk, v_token=d, v_dim=1)
+
+
+def pool_elems(shape, n_pages: int, page_tokens: int = 16) -> int:
+    return shape.n_layers * n_pages * 2 * shape.n_kv_heads * page_tokens * shape.head_dim
+
+
+def decode_step(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_lens, model_ids,
+                mode: int = 0, want_rowsums: bool = False, want_attn: bool = False):
+    """Runs one decode step; mutates the pool (appends the new K/V).  Returns a dict."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    page_tables = np.ascontiguousarray(page_tables, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    model_ids = np.ascontiguousarray(model_ids, dtype=np.int32)
+    B = tokens.shape[0]
+    logits = np.empty((B, cfg.vocab), dtype=np.float64)
+    nxt = np.empty(B, dtype=np.int32)
+    rows = np.empty((B, cfg.n_layers, cfg.n_q_heads), dtype=np.float64) if want_rowsums else None
+    attn = np.empty((B, cfg.n_layers, cfg.n_q_heads * cfg.head_dim), dtype=np.float64) if want_attn else None
+    rc = lib().orc_decode_step(C.byref(cfg), params.mats, C.byref(pool), C.c_int(B), _ptr(tokens),
+                               _ptr(page_tables), C.c_int(page_tables.shape[1]), _ptr(seq_lens),
+                               _ptr(model_ids), C.c_int(mode), _ptr(logits), _ptr(nxt), _ptr(rows), _ptr(attn))
+    if rc != 0:
+        raise ValueError(f"orc_decode_step failed with status {rc}")
+    return {"logits": logits, "next": nxt, "rowsums": rows, "attn": attn}
+
+
+def decode_contig_f64(cfg: Cfg, params: Params, token: int, L: int, Kc: np.ndarray, Vc: np.ndarray,
+                      round_kv: bool = False):
+    """Kc, Vc: float64 [NL, cap, Hkv, d]; writes position L.  Returns (logits, next)."""
+    assert Kc.dtype == np.float64 and Kc.flags["C_CONTIGUOUS"] and Vc.flags["C_CONTIGUOUS"]
+    logits = np.empty(cfg.vocab, dtype=np.float64)
+    nxt = C.c_int32(0)
+    rc = lib().orc_decode_contig_f64(C.byref(cfg), params.mats, C.c_int32(token), C.c_int64(L),
+                                     C.c_int64(Kc.shape[1]), _ptr(Kc), _ptr(Vc), C.c_int(int(round_kv)),
+                                     _ptr(logits), C.byref(nxt))
+    if rc != 0:
+        raise ValueError(f"orc_decode_contig_f64 failed with status {rc}")
+    return logits, int(nxt.value)
+
+
+def full_forward(cfg: Cfg, params: Params, tokens, round_kv: bool = False, want_kv: bool = False):
+    """Causal forward over the whole sequence (no cache). Returns logits [T,V] (and K,V)."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    T = tokens.shape[0]
+    logits = np.empty((T, cfg.vocab), dtype=np.float64)
+    K = V = None
+    if want_kv:
+        K = np.empty((cfg.n_layers, T, cfg.n_kv_heads, cfg.head_dim), dtype=np.float64)
+        V = np.empty_like(K)
+    rc = lib().orc_full_forward(C.byref(cfg), params.mats, C.c_int(T), _ptr(tokens), C.c_int(int(round_kv)),
+                                _ptr(logits), _ptr(K), _ptr(V))
+    if rc != 0:
+        raise ValueError(f"orc_full_forward failed with status {rc}")
+    return (logits, K, V) if want_kv else logits
+
+
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    h = np.empty_like(x)
+    lib().orc_rmsnorm(_ptr(x), _ptr(g), C.c_int(x.shape[0]), C.c_double(eps), _ptr(h))
+    return h
+
+
+def rope(u: np.ndarray, pos: int, base: float) -> np.ndarray:
+    out = np.array(u, dtype=np.float64, copy=True)
+    lib().orc_rope(_ptr(out), C.c_int(out.shape[0]), C.c_int64(pos), C.c_double(base))
+    return out
+
+
+def silu(z: float) -> float:
+    return float(lib().orc_silu(z))
+
+
+def linear(m: Mat, X: np.ndarray) -> np.ndarray:
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    Y = np.empty((X.shape[0], m.rows), dtype=np.float64)
+    lib().orc_linear(C.byref(m), _ptr(X), C.c_int(X.shape[0]), _ptr(Y))
+    return Y
+
+
+def argmax(v: np.ndarray) -> int:
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    return int(lib().orc_argmax(_ptr(v), C.c_int(v.shape[0])))
+
+
+def attention_paged(cfg: Cfg, pool: Pool, layer: int, page_table: np.ndarray, q: np.ndarray, n: int):
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    a = np.empty(cfg.n_q_heads * cfg.head_dim, dtype=np.float64)
+    rs = np.empty(cfg.n_q_heads, dtype=np.float64)
+    rc = lib().orc_attention_paged(C.byref(cfg), C.byref(pool), C.c_int(layer), _ptr(page_table), _ptr(q),
+                                   C.c_int64(n), _ptr(a), _ptr(rs))
+    assert rc == 0
+    return a, rs
+
+
+def quantize_w4(w: np.ndarray, group: int = 128, mode: str = "asym"):
+    """Returns (q uint8 [rows, cols/2], s uint16 [rows, groups], z uint16 [rows, groups])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    rows, cols = w.shape
+    ng = (cols + group - 1) // group
+    q = np.empty((rows, cols // 2), dtype=np.uint8)
+    s = np.empty((rows, ng), dtype=np.uint16)
+    z = np.empty((rows, ng), dtype=np.uint16)
+    rc = lib().orc_quantize_w4(_ptr(w), C.c_int(rows), C.c_int(cols), C.c_int(group),
+                               C.c_int({"asym": 0, "sym": 1}[mode]), _ptr(q), _ptr(s), _ptr(z))
+    if rc != 0:
+        raise ValueError(f"orc_quantize_w4 failed with status {rc}")
+    return q, s, z
+
+
+def dequantize_w4(q: np.ndarray, s: np.ndarray, z: np.ndarray, cols: int, group: int = 128) -> np.ndarray:
+    m = w4_mat(q, s, z, cols, group)
+    out = np.empty((q.shape[0], cols), dtype=np.float32)
+    lib().orc_dequantize_w4(C.byref(m), _ptr(out))
+    return out
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float64 values to bf16 (nearest even) and return the bit patterns."""
+    f = lib().orc_double_to_bf16
+    flat = np.asarray(x, dtype=np.float64).ravel()
+    return np.array([f(float(v)) for v in flat], dtype=np.uint16).reshape(np.shape(x))
+
+
+def bf16_values(bits: np.ndarray) -> np.ndarray:
+    b = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16
+    return b.view(np.float32).astype(np.float64)
