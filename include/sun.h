@@ -1,0 +1,281 @@
+/*
+ * libsun — one decode step of SUN's frozen, shared decode module on one MI355X.
+ *
+ * The library evaluates D_theta_d of Section 3.1, Eq. 3: for every request of a
+ * batch it consumes the most recent token and the request's KV cache, appends
+ * the KV entry of the new position (Eq. 4) and returns next-token logits and
+ * the greedy next token.  The requests of one batch may come from different
+ * task-specific prefill models; because all tasks decode with the same
+ * parameters (Section 3.2.1) and decode routing ignores task identity
+ * (Section 3.2.3), the source-model id of a request is a tag that is validated
+ * and otherwise ignored, and all caches live in one paged pool addressed only
+ * through per-request page tables.  sun_qdecode_step is the QSUN variant
+ * (Section 3.3, Eq. 8): the same step with 4-bit, group-128 weight-only
+ * quantised projections; lm_head, embedding and norm gains stay dense
+ * (Appendix A.1, "Quantization Configurations").
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) addresses owned by the caller; "host"
+ *    pointers are ordinary host memory.  The library never allocates or frees
+ *    device memory and never synchronises unless stated; work is enqueued on the
+ *    caller's hipStream_t (passed as void*; NULL = the null stream).
+ *  - Every function returns a status (SUN_OK = 0).  On error nothing has been
+ *    enqueued and sun_last_error() describes the problem (thread-local).
+ *  - All matrices are row-major [out_features, in_features].
+ *  - A process uses the library from one thread per stream; calls that share a
+ *    workspace or a pool must not overlap.
+ */
+#ifndef SUN_H_
+#define SUN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SUN_OK = 0,
+    SUN_ERR_NULL = 1,       /* a required pointer is NULL */
+    SUN_ERR_SHAPE = 2,      /* unsupported or inconsistent model shape / batch */
+    SUN_ERR_POOL_SIZE = 3,  /* pool memory too small for the requested pages */
+    SUN_ERR_WORKSPACE = 4,  /* workspace too small */
+    SUN_ERR_PAGE_RANGE = 5, /* page table entry outside [0, n_pages) or table too short */
+    SUN_ERR_SEQ_LEN = 6,    /* negative length or length beyond the page table */
+    SUN_ERR_MODEL_ID = 7,   /* source-model id outside [0, n_source_models) */
+    SUN_ERR_HIP = 8,        /* a HIP runtime call failed */
+    SUN_ERR_TOKEN = 9       /* token id outside [0, vocab) */
+};
+
+enum { SUN_F32 = 0, SUN_BF16 = 1 };
+
+/* step flags */
+enum {
+    SUN_VALIDATE = 1u, /* copy token ids, lengths, page tables and model ids to the host
+                          (synchronises the stream) and check them before enqueueing */
+    SUN_PROFILE = 2u   /* record HIP events around each kernel class; see sun_profile_read */
+};
+
+/*
+ * Decoder shape (pre-norm Llama-style block: RMSNorm, GQA attention with rotary
+ * embedding in half-split pairing, SwiGLU, untied lm_head).  act_dtype selects the
+ * arithmetic: SUN_F32 = fp32 weights and activations on the vector ALUs (parity
+ * configuration), SUN_BF16 = bf16 weights, bf16 matrix-core inputs, fp32
+ * accumulators / residual stream / softmax.  The KV pool is bf16 in both.
+ * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with ratio
+ * <= 8; SUN_BF16 additionally needs hidden, ffn and n_q_heads*head_dim multiples
+ * of 128 and vocab a multiple of 32.
+ */
+typedef struct sun_model_cfg {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    float rms_eps, rope_base;
+    int32_t act_dtype;
+} sun_model_cfg;
+
+/* ------------------------------------------------------------------ KV pool */
+
+/*
+ * Element (bf16) offsets into the pool:
+ *   K(layer,page,head,token,dim) = k_off + layer*k_layer + page*k_page + head*k_head + token*k_token + dim*k_dim
+ * and the same with v_.  K is stored [token][dim], V transposed [dim][token] inside
+ * a (layer, page, head) block, so that both are matrix-core operands after a
+ * 16-byte load.  A prefill producer writes through these strides.
+ */
+typedef struct sun_kv_layout {
+    int64_t n_pages;
+    int32_t page_tokens, reserved;
+    int64_t k_off, k_layer, k_page, k_head, k_token, k_dim;
+    int64_t v_off, v_layer, v_page, v_head, v_token, v_dim;
+    int64_t total_elems;
+} sun_kv_layout;
+
+typedef struct sun_kv_pool sun_kv_pool;
+
+/* Bytes of device memory a pool of n_pages pages needs. */
+size_t sun_kv_pool_bytes(const sun_model_cfg* cfg, int64_t n_pages, int page_tokens);
+
+/*
+ * Wraps caller-owned device memory as ONE paged KV pool shared by the caches of
+ * all source models (Section 3.2.3: decode requests are pooled whatever model
+ * prefilled them).  dev_mem: device, 256-byte aligned, borrowed until destroy
+ * and never freed by the library.  bytes / page size gives n_pages.
+ * page_tokens must be 16.  n_source_models bounds the model ids accepted by
+ * SUN_VALIDATE.  Errors: SUN_ERR_NULL, SUN_ERR_SHAPE, SUN_ERR_POOL_SIZE (no page fits).
+ */
+int sun_kv_pool_create(const sun_model_cfg* cfg, void* dev_mem, size_t bytes, int page_tokens,
+                       int n_source_models, sun_kv_pool** out);
+int sun_kv_pool_layout(const sun_kv_pool* pool, sun_kv_layout* out);
+void sun_kv_pool_destroy(sun_kv_pool* pool);
+
+/* ------------------------------------------------------------------ weights */
+
+/*
+ * Dense decode parameters theta_d (Eq. 3).  embed [vocab, hidden]; per layer
+ * (host arrays of n_layers device pointers) g1 [hidden], wq [Hq*d, hidden],
+ * wk, wv [Hkv*d, hidden], wo [hidden, Hq*d], g2 [hidden], wg, wu [ffn, hidden],
+ * wd [hidden, ffn]; gf [hidden]; wlm [vocab, hidden].  Element type is fp32
+ * (SUN_F32) or bf16 (SUN_BF16) for every tensor.
+ */
+typedef struct sun_weight_ptrs {
+    const void* embed;
+    const void* const* g1;
+    const void* const* wq;
+    const void* const* wk;
+    const void* const* wv;
+    const void* const* wo;
+    const void* const* g2;
+    const void* const* wg;
+    const void* const* wu;
+    const void* const* wd;
+    const void* gf;
+    const void* wlm;
+} sun_weight_ptrs;
+
+typedef struct sun_weights sun_weights;
+
+/*
+ * SUN_BF16: projection matrices are re-tiled into the matrix-core operand order
+ * inside pack_mem (device, 256-byte aligned, at least sun_weights_pack_bytes(cfg)
+ * bytes, borrowed until destroy); the packing kernels run on `stream` and the call
+ * returns after synchronising it, after which the caller may free the row-major
+ * matrices (embed, gains are still referenced).  SUN_F32: pack_mem may be NULL,
+ * the row-major arrays are used in place.
+ */
+size_t sun_weights_pack_bytes(const sun_model_cfg* cfg);
+int sun_weights_create(const sun_model_cfg* cfg, const sun_weight_ptrs* dev, void* pack_mem,
+                       size_t pack_bytes, void* stream, sun_weights** out);
+void sun_weights_destroy(sun_weights* w);
+
+/*
+ * QSUN parameters q(theta_d) (Eq. 8; Appendix A.1): every projection of the block is
+ * W_hat[n,k] = (Q[n,k] - Z[n,k/128]) * S[n,k/128] with Q 4-bit codes packed two per
+ * byte along k (low nibble = even k) [out, in/2], S and Z fp16 [out, in/128], Z
+ * holding an integer in [0,15].  embed, gains and wlm are dense as in
+ * sun_weight_ptrs (lm_head is not quantised).
+ */
+typedef struct sun_qmat {
+    const void* q;
+    const void* s;
+    const void* z;
+} sun_qmat;
+
+typedef struct sun_qweight_ptrs {
+    const void* embed;
+    const void* const* g1;
+    const sun_qmat* wq; /* host arrays of n_layers entries */
+    const sun_qmat* wk;
+    const sun_qmat* wv;
+    const sun_qmat* wo;
+    const void* const* g2;
+    const sun_qmat* wg;
+    const sun_qmat* wu;
+    const sun_qmat* wd;
+    const void* gf;
+    const void* wlm;
+} sun_qweight_ptrs;
+
+size_t sun_qweights_pack_bytes(const sun_model_cfg* cfg, int group);
+/* group must be 128.  Packing as in sun_weights_create (codes, scales and lm_head
+ * are re-tiled into pack_mem under SUN_BF16). */
+int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* dev, int group,
+                        void* pack_mem, size_t pack_bytes, void* stream, sun_weights** out);
+
+/*
+ * Round-to-nearest group quantiser producing the QSUN format from a dense matrix
+ * (device; dtype SUN_F32 or SUN_BF16; [rows, cols], cols a multiple of `group`,
+ * group a multiple of 8).  mode 0 (affine): S = fp16((max-min)/15) (1 if 0),
+ * Z = clamp(rne(-min/S),0,15), Q = clamp(rne(w/S)+Z,0,15).  mode 1 (symmetric,
+ * the wording of Appendix A.1): S = fp16(max|w|/7) (1 if 0), Z = 8,
+ * Q = clamp(rne(w/S)+8,0,15).  Divisions use the stored fp16 S, in fp32.
+ * Outputs (device): q [rows, cols/2] bytes, s and z fp16 [rows, cols/group].
+ */
+int sun_quantize_w4(const void* w, int dtype, int rows, int cols, int group, int mode, void* q,
+                    void* s, void* z, void* stream);
+
+/* ------------------------------------------------------------------ decode step */
+
+/* Bytes of device workspace a step with up to max_batch requests and max_pages
+ * page-table columns needs. */
+size_t sun_workspace_bytes(const sun_model_cfg* cfg, int max_batch, int max_pages);
+
+/*
+ * One decode step (Eq. 3) for `batch` requests, enqueued on `stream`.
+ *   token_ids   dev int32 [batch]             y_{t-1} of each request
+ *   page_tables dev int32 [batch, max_pages]  physical page per 16 tokens, -1 = unused
+ *   seq_lens    dev int32 [batch]             L_i = tokens cached BEFORE the step; the new
+ *                                             token takes position L_i and attention spans
+ *                                             positions 0..L_i
+ *   seq_lens_host host int32 [batch] or NULL  optional copy, used only to size the launch
+ *   model_ids   dev int32 [batch]             source-model tag (checked under SUN_VALIDATE,
+ *                                             never read by a kernel)
+ *   logits_out  dev fp32 [batch, vocab] or NULL
+ *   next_tokens_out dev int32 [batch]         greedy argmax, lowest index on ties
+ *   workspace   dev, 256-byte aligned, >= sun_workspace_bytes(cfg, batch, max_pages)
+ * The step writes K/V of the new position into slot L_i % 16 of page
+ * page_tables[i][L_i / 16] in every layer (Eq. 4) and does not change seq_lens.
+ * Preconditions: the table of request i has ceil((L_i+1)/16) valid entries; the page
+ * written this step is not referenced by any other request of the batch (history
+ * pages may be shared read-only).  Outputs are valid after the stream is
+ * synchronised.  With flags = 0 device array contents are not checked.
+ * Errors: SUN_ERR_NULL, SUN_ERR_SHAPE (batch < 1, or a pool / weights pair of
+ * different shape), SUN_ERR_WORKSPACE; under SUN_VALIDATE also SUN_ERR_TOKEN,
+ * SUN_ERR_SEQ_LEN, SUN_ERR_PAGE_RANGE, SUN_ERR_MODEL_ID.
+ */
+int sun_decode_step(sun_kv_pool* pool, const sun_weights* weights, int batch,
+                    const int32_t* token_ids, const int32_t* page_tables, int max_pages,
+                    const int32_t* seq_lens, const int32_t* seq_lens_host, const int32_t* model_ids,
+                    float* logits_out, int32_t* next_tokens_out, void* workspace,
+                    size_t workspace_bytes, void* stream, unsigned flags);
+
+/* QSUN step (Eq. 8): identical arguments; `weights` must come from sun_qweights_create. */
+int sun_qdecode_step(sun_kv_pool* pool, const sun_weights* weights, int batch,
+                     const int32_t* token_ids, const int32_t* page_tables, int max_pages,
+                     const int32_t* seq_lens, const int32_t* seq_lens_host, const int32_t* model_ids,
+                     float* logits_out, int32_t* next_tokens_out, void* workspace,
+                     size_t workspace_bytes, void* stream, unsigned flags);
+
+/* ------------------------------------------------------------------ single operations */
+
+/*
+ * The attention sub-step of the decode step on its own (same kernels, same launch
+ * shape): for each request, softmax(q K^T / sqrt(d)) V over the first n_tokens[i]
+ * cached positions of `layer`, GQA mapping q-head h -> kv-head h / (Hq/Hkv).
+ *   q dev fp32 [batch, Hq*d] (already rotated); out dev fp32 [batch, Hq*d];
+ *   n_tokens dev int32 [batch], each >= 1; n_tokens_host optional as above.
+ * Reads the pool only.  Workspace as for a step.
+ */
+int sun_paged_attention(sun_kv_pool* pool, int layer, int batch, const float* q,
+                        const int32_t* page_tables, int max_pages, const int32_t* n_tokens,
+                        const int32_t* n_tokens_host, float* out, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
+ * out[b, n] = sum_k W[n, k] x[b, k]  through the projection kernels of the step.
+ *   mat: index into the projection list of layer `layer`: 0 = [Wq;Wk;Wv] stacked,
+ *        1 = Wo, 2 = fused silu(Wg x) * (Wu x) (out has ffn columns), 3 = Wd, 4 = lm_head
+ *        (layer ignored).  x dev fp32 [batch, in]; out dev fp32 [batch, out].
+ * Under SUN_BF16 x is rounded to bf16 first, as in the step.
+ */
+int sun_linear(const sun_weights* weights, int layer, int mat, int batch, const float* x, float* out,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ misc */
+
+/*
+ * With SUN_PROFILE the step brackets each kernel class with HIP events.  After the
+ * stream is synchronised, sun_profile_read returns, for class `kind`, the summed
+ * elapsed milliseconds and the number of launches since sun_profile_reset().
+ * kinds: 0 attention split kernel, 1 attention combine, 2 qkv proj, 3 o proj,
+ * 4 gate/up proj, 5 down proj, 6 lm_head, 7 everything else.
+ */
+int sun_profile_read(int kind, double* ms, int64_t* launches);
+void sun_profile_reset(void);
+
+const char* sun_last_error(void);
+const char* sun_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUN_H_ */

@@ -575,6 +575,7 @@ int orc_quantize_w4(const float *w, int rows, int cols, int group, int mode,
             float S = half_to_float(sh);
             if (S == 0.0f) { S = 1.0f; sh = float_to_half(1.0f); }
             float Z = (mode == 0) ? clampf(nearbyintf(-mn / S), 0.0f, 15.0f) : 8.0f;
+            if (Z == 0.0f) Z = 0.0f; /* the zero point is an integer code: store +0, never -0 */
             s[(size_t)r * ng + g] = sh;
             z[(size_t)r * ng + g] = float_to_half(Z);
             for (int cc = c0; cc < c1; ++cc) {

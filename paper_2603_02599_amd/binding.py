@@ -1,0 +1,324 @@
+"""Thin ctypes binding of libsun (argument marshalling only; every step of the decode path
+runs in the HIP kernels).  Function names follow include/sun.h.  PyTorch tensors are used
+as device-memory owners; their data_ptr() is what crosses the boundary.
+
+There is no CPU fallback: if the HIP library is missing the import of a function fails."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsun.so")
+
+SUN_F32, SUN_BF16 = 0, 1
+SUN_VALIDATE, SUN_PROFILE = 1, 2
+STATUS = {0: "SUN_OK", 1: "SUN_ERR_NULL", 2: "SUN_ERR_SHAPE", 3: "SUN_ERR_POOL_SIZE", 4: "SUN_ERR_WORKSPACE",
+          5: "SUN_ERR_PAGE_RANGE", 6: "SUN_ERR_SEQ_LEN", 7: "SUN_ERR_MODEL_ID", 8: "SUN_ERR_HIP", 9: "SUN_ERR_TOKEN"}
+PROFILE_KINDS = ("attn_split", "attn_combine", "qkv_proj", "o_proj", "gate_up_proj", "down_proj", "lm_head", "other")
+
+EXPORTS = [
+    "sun_kv_pool_bytes", "sun_kv_pool_create", "sun_kv_pool_layout", "sun_kv_pool_destroy",
+    "sun_weights_pack_bytes", "sun_weights_create", "sun_weights_destroy",
+    "sun_qweights_pack_bytes", "sun_qweights_create", "sun_quantize_w4",
+    "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step",
+    "sun_paged_attention", "sun_linear",
+    "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
+]
+
+
+class SunError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_base", C.c_float), ("act_dtype", C.c_int32)]
+
+
+class KvLayout(C.Structure):
+    _fields_ = [("n_pages", C.c_int64), ("page_tokens", C.c_int32), ("reserved", C.c_int32),
+                ("k_off", C.c_int64), ("k_layer", C.c_int64), ("k_page", C.c_int64), ("k_head", C.c_int64),
+                ("k_token", C.c_int64), ("k_dim", C.c_int64),
+                ("v_off", C.c_int64), ("v_layer", C.c_int64), ("v_page", C.c_int64), ("v_head", C.c_int64),
+                ("v_token", C.c_int64), ("v_dim", C.c_int64), ("total_elems", C.c_int64)]
+
+
+class WeightPtrs(C.Structure):
+    _fields_ = [("embed", C.c_void_p)] + [(k, C.POINTER(C.c_void_p)) for k in
+                                          ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")] + \
+               [("gf", C.c_void_p), ("wlm", C.c_void_p)]
+
+
+class QMat(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("s", C.c_void_p), ("z", C.c_void_p)]
+
+
+class QWeightPtrs(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("g1", C.POINTER(C.c_void_p)),
+                ("wq", C.POINTER(QMat)), ("wk", C.POINTER(QMat)), ("wv", C.POINTER(QMat)), ("wo", C.POINTER(QMat)),
+                ("g2", C.POINTER(C.c_void_p)),
+                ("wg", C.POINTER(QMat)), ("wu", C.POINTER(QMat)), ("wd", C.POINTER(QMat)),
+                ("gf", C.c_void_p), ("wlm", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_02599_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.sun_last_error.restype = C.c_char_p
+        L.sun_version.restype = C.c_char_p
+        for f in ("sun_kv_pool_bytes", "sun_weights_pack_bytes", "sun_qweights_pack_bytes", "sun_workspace_bytes"):
+            getattr(L, f).restype = C.c_size_t
+        L.sun_kv_pool_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int64, C.c_int]
+        L.sun_kv_pool_create.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_size_t, C.c_int, C.c_int,
+                                         C.POINTER(C.c_void_p)]
+        L.sun_kv_pool_layout.argtypes = [C.c_void_p, C.POINTER(KvLayout)]
+        L.sun_kv_pool_destroy.argtypes = [C.c_void_p]
+        L.sun_kv_pool_destroy.restype = None
+        L.sun_weights_pack_bytes.argtypes = [C.POINTER(ModelCfg)]
+        L.sun_weights_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(WeightPtrs), C.c_void_p, C.c_size_t,
+                                         C.c_void_p, C.POINTER(C.c_void_p)]
+        L.sun_weights_destroy.argtypes = [C.c_void_p]
+        L.sun_weights_destroy.restype = None
+        L.sun_qweights_pack_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int]
+        L.sun_qweights_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(QWeightPtrs), C.c_int, C.c_void_p,
+                                          C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.sun_quantize_w4.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sun_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
+        step_args = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
+                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
+        L.sun_decode_step.argtypes = step_args
+        L.sun_qdecode_step.argtypes = step_args
+        L.sun_paged_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sun_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+        L.sun_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.sun_profile_reset.restype = None
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SunError(rc, lib().sun_last_error().decode())
+
+
+def _p(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous()
+        return t.data_ptr()
+    return int(t)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def make_cfg(shape, act_dtype: str) -> ModelCfg:
+    """shape: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base."""
+    return ModelCfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
+                    shape.vocab, float(shape.rms_eps), float(shape.rope_base),
+                    {"f32": SUN_F32, "bf16": SUN_BF16}[act_dtype])
+
+
+# ------------------------------------------------------------------ pool
+def sun_kv_pool_bytes(cfg: ModelCfg, n_pages: int, page_tokens: int = 16) -> int:
+    return int(lib().sun_kv_pool_bytes(C.byref(cfg), n_pages, page_tokens))
+
+
+class KvPool:
+    """Owner of the pool handle; `mem` (a torch uint8/bf16 CUDA tensor) is borrowed and kept alive."""
+
+    def __init__(self, handle: int, mem: torch.Tensor):
+        self.handle, self.mem = handle, mem
+
+    def layout(self) -> KvLayout:
+        return sun_kv_pool_layout(self)
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().sun_kv_pool_destroy(self.handle)
+            self.handle = None
+
+
+def sun_kv_pool_create(cfg: ModelCfg, mem: torch.Tensor, page_tokens: int = 16, n_source_models: int = 1) -> KvPool:
+    out = C.c_void_p()
+    nbytes = mem.numel() * mem.element_size() if isinstance(mem, torch.Tensor) else 0
+    _check(lib().sun_kv_pool_create(C.byref(cfg), _p(mem), nbytes, page_tokens, n_source_models, C.byref(out)))
+    return KvPool(out.value, mem)
+
+
+def sun_kv_pool_layout(pool: KvPool) -> KvLayout:
+    lay = KvLayout()
+    _check(lib().sun_kv_pool_layout(pool.handle, C.byref(lay)))
+    return lay
+
+
+# ------------------------------------------------------------------ weights
+LAYER_KEYS = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
+QUANT_KEYS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd")
+
+
+class Weights:
+    def __init__(self, handle: int, keep: list, quant: bool):
+        self.handle, self.keep, self.quant = handle, keep, quant
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib().sun_weights_destroy(self.handle)
+            self.handle = None
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    arr = (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+    return arr
+
+
+def sun_weights_pack_bytes(cfg: ModelCfg) -> int:
+    return int(lib().sun_weights_pack_bytes(C.byref(cfg)))
+
+
+def sun_weights_create(cfg: ModelCfg, w: Dict[str, object], stream=None, keep_sources: bool = True) -> Weights:
+    """w: dict from workloads.make_weights (torch CUDA tensors).  Allocates the pack buffer with torch."""
+    ptrs = WeightPtrs()
+    keep: List[object] = []
+    ptrs.embed = w["embed"].data_ptr()
+    for k in LAYER_KEYS:
+        arr = _ptr_array(w[k])
+        keep.append(arr)
+        setattr(ptrs, k, C.cast(arr, C.POINTER(C.c_void_p)))
+    ptrs.gf, ptrs.wlm = w["gf"].data_ptr(), w["wlm"].data_ptr()
+    nbytes = sun_weights_pack_bytes(cfg)
+    pack = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=w["embed"].device) if cfg.act_dtype == SUN_BF16 else None
+    out = C.c_void_p()
+    _check(lib().sun_weights_create(C.byref(cfg), C.byref(ptrs), _p(pack), nbytes, _stream(stream), C.byref(out)))
+    keep.append(pack)
+    if keep_sources or cfg.act_dtype == SUN_F32:
+        keep.append(w)
+    else:
+        keep.extend([w["embed"], w["g1"], w["g2"], w["gf"]])
+    return Weights(out.value, keep, False)
+
+
+def sun_qweights_pack_bytes(cfg: ModelCfg, group: int = 128) -> int:
+    return int(lib().sun_qweights_pack_bytes(C.byref(cfg), group))
+
+
+def sun_qweights_create(cfg: ModelCfg, w: Dict[str, object], quant: Dict[str, list], group: int = 128,
+                        stream=None) -> Weights:
+    """quant[key][layer] = (q uint8 [out, in/2], s fp16 [out, in/128], z fp16 [out, in/128]) CUDA tensors;
+    w supplies embed, g1, g2, gf, wlm."""
+    ptrs = QWeightPtrs()
+    keep: List[object] = [w["embed"], w["g1"], w["g2"], w["gf"], w["wlm"], quant]
+    ptrs.embed = w["embed"].data_ptr()
+    for k in ("g1", "g2"):
+        arr = _ptr_array(w[k])
+        keep.append(arr)
+        setattr(ptrs, k, C.cast(arr, C.POINTER(C.c_void_p)))
+    for k in QUANT_KEYS:
+        arr = (QMat * len(quant[k]))(*[QMat(q.data_ptr(), s.data_ptr(), z.data_ptr()) for (q, s, z) in quant[k]])
+        keep.append(arr)
+        setattr(ptrs, k, C.cast(arr, C.POINTER(QMat)))
+    ptrs.gf, ptrs.wlm = w["gf"].data_ptr(), w["wlm"].data_ptr()
+    nbytes = sun_qweights_pack_bytes(cfg, group)
+    pack = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=w["embed"].device) if cfg.act_dtype == SUN_BF16 else None
+    out = C.c_void_p()
+    _check(lib().sun_qweights_create(C.byref(cfg), C.byref(ptrs), group, _p(pack), nbytes, _stream(stream), C.byref(out)))
+    keep.append(pack)
+    return Weights(out.value, keep, True)
+
+
+def sun_quantize_w4(w: torch.Tensor, group: int = 128, mode: str = "asym", stream=None):
+    """Returns (q uint8 [rows, cols/2], s fp16 [rows, cols/group], z fp16 [rows, cols/group])."""
+    rows, cols = w.shape
+    dt = {torch.float32: SUN_F32, torch.bfloat16: SUN_BF16}[w.dtype]
+    q = torch.empty((rows, cols // 2), dtype=torch.uint8, device=w.device)
+    s = torch.empty((rows, cols // group), dtype=torch.float16, device=w.device)
+    z = torch.empty_like(s)
+    _check(lib().sun_quantize_w4(_p(w), dt, rows, cols, group, {"asym": 0, "sym": 1}[mode], _p(q), _p(s), _p(z),
+                                 _stream(stream)))
+    return q, s, z
+
+
+# ------------------------------------------------------------------ step
+def sun_workspace_bytes(cfg: ModelCfg, max_batch: int, max_pages: int) -> int:
+    return int(lib().sun_workspace_bytes(C.byref(cfg), max_batch, max_pages))
+
+
+def _host_i32(a):
+    if a is None:
+        return None, None
+    import numpy as np
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data
+
+
+def _step(fn, pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out, next_tokens_out, workspace,
+          seq_lens_host, stream, flags):
+    batch, max_pages = page_tables.shape
+    keep, host_ptr = _host_i32(seq_lens_host)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(fn(pool.handle if pool is not None else None, weights.handle if weights is not None else None, batch,
+              _p(token_ids), _p(page_tables), max_pages, _p(seq_lens), host_ptr, _p(model_ids), _p(logits_out),
+              _p(next_tokens_out), _p(workspace), ws_bytes, _stream(stream), flags))
+
+
+def sun_decode_step(pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out, next_tokens_out,
+                    workspace, seq_lens_host=None, stream=None, flags: int = 0):
+    _step(lib().sun_decode_step, pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out,
+          next_tokens_out, workspace, seq_lens_host, stream, flags)
+
+
+def sun_qdecode_step(pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out, next_tokens_out,
+                     workspace, seq_lens_host=None, stream=None, flags: int = 0):
+    _step(lib().sun_qdecode_step, pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out,
+          next_tokens_out, workspace, seq_lens_host, stream, flags)
+
+
+def sun_paged_attention(pool, layer: int, q, page_tables, n_tokens, out, workspace, n_tokens_host=None, stream=None):
+    batch, max_pages = page_tables.shape
+    keep, host_ptr = _host_i32(n_tokens_host)
+    _check(lib().sun_paged_attention(pool.handle, layer, batch, _p(q), _p(page_tables), max_pages, _p(n_tokens),
+                                     host_ptr, _p(out), _p(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)))
+
+
+def sun_linear(weights, layer: int, mat: int, x, out, workspace, stream=None):
+    _check(lib().sun_linear(weights.handle, layer, mat, x.shape[0], _p(x), _p(out), _p(workspace),
+                            workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def sun_profile_reset():
+    lib().sun_profile_reset()
+
+
+def sun_profile_read() -> Dict[str, Dict[str, float]]:
+    out = {}
+    for k, name in enumerate(PROFILE_KINDS):
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib().sun_profile_read(k, C.byref(ms), C.byref(n)))
+        out[name] = {"ms": ms.value, "launches": int(n.value)}
+    return out
+
+
+def sun_version() -> str:
+    return lib().sun_version().decode()

@@ -1,0 +1,445 @@
+// Paged GQA decode attention over the shared KV pool (the cache-reading part of
+// Eq. 3; the cache is prompt KV from any task's prefill module followed by
+// decode-generated KV, Eq. 4).  One query position per request attends to all
+// n_i cached positions of that request; requests of different source models are
+// handled identically, the pool is addressed through the page table only.
+//
+// Work decomposition: a work item is (request, kv head, chunk of 256 positions).
+// The chunk grid of a request depends on its own length only, so a request's
+// result does not depend on its batch-mates.  One wave per item streams the
+// item's K and V^T pages with 16-byte loads straight into matrix-core operand
+// registers:
+//   S^T[token, head] = K[token, :] . q[head, :]      (16x16x32 MFMA, q split hi+lo bf16)
+//   O[head, dim]    += P[head, token] V^T[dim, token] (16x16x32 MFMA, P split hi+lo bf16)
+// The group's q heads occupy the first G of the 16 MFMA columns.  Softmax runs in
+// fp32 in the log2 domain with a running maximum; partial (O, m, l) per item are
+// merged by a second kernel in chunk order.  The matrix cores are used because at
+// ~13 HBM bytes per CU-clock the vector ALUs cannot also convert, multiply and
+// reduce 256 bf16 values per token for several query heads; the kernel stays HBM
+// bound.  An fp32 vector-ALU variant serves the fp32 parity configuration.
+#include "kernels.hpp"
+
+namespace sun {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int CH = kAttnChunk;
+constexpr float kLog2e = 1.4426950408889634f;
+
+size_t attn_max_chunks(int batch, int max_pages) {
+    const size_t per_req = ((size_t)max_pages * kPageTokens + CH - 1) / CH;
+    return (size_t)batch * (per_req > 0 ? per_req : 1);
+}
+
+// ---------------------------------------------------------------------------------
+// plan: chunk list from the lengths (one block)
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t* __restrict__ n_or_len, int len_plus, int batch,
+                                                         int32_t* __restrict__ chunk_off, int32_t* __restrict__ item_req,
+                                                         int32_t* __restrict__ item_chunk, int max_chunks, int max_tokens) {
+    __shared__ int scan[1024];
+    const int t = threadIdx.x;
+    int mine = 0;
+    if (t < batch) {
+        const int n = min(max(n_or_len[t] + len_plus, 1), max_tokens);
+        mine = (n + CH - 1) / CH;
+    }
+    scan[t] = mine;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int v = t >= o ? scan[t - o] : 0;
+        __syncthreads();
+        scan[t] += v;
+        __syncthreads();
+    }
+    const int end = scan[t], begin = end - mine;
+    if (t < batch) {
+        chunk_off[t + 1] = min(end, max_chunks);
+        if (t == 0) chunk_off[0] = 0;
+        for (int j = 0; j < mine; ++j)
+            if (begin + j < max_chunks) {
+                item_req[begin + j] = t;
+                item_chunk[begin + j] = j;
+            }
+    }
+}
+
+hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch, int max_pages,
+                            hipStream_t st) {
+    if (batch > 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_or_len, len_plus, batch, plan.chunk_off,
+                       plan.item_req, plan.item_chunk, plan.max_chunks, max_pages * kPageTokens);
+    return hipGetLastError();
+}
+
+struct AttnArgs {
+    const uint16_t* kbase;  // pool base + k_off + layer * k_layer
+    const uint16_t* vbase;
+    int64_t k_page, k_head, v_page, v_head;
+    const float* q;         // [batch, Hq*D]
+    const int32_t* page_tables;
+    const int32_t* n_or_len;
+    const int32_t* chunk_off;
+    const int32_t* item_req;
+    const int32_t* item_chunk;
+    float* partial;
+    int len_plus, max_pages, batch, Hq, Hkv, n_pages;
+    float qscale;           // log2(e) / sqrt(D)
+};
+
+__device__ __forceinline__ uint32_t bf16_pair_hi(float a, float b, float& ra, float& rb) {
+    const uint32_t ha = f32_to_bf16_bits(a), hb = f32_to_bf16_bits(b);
+    ra = a - __uint_as_float(ha << 16);
+    rb = b - __uint_as_float(hb << 16);
+    return ha | (hb << 16);
+}
+
+// ---------------------------------------------------------------------------------
+// split kernel, matrix-core variant
+// ---------------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
+    constexpr int NS = D / 32;  // dim slices of a QK MFMA
+    constexpr int NB = D / 16;  // dim blocks of a PV MFMA
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c16 = lane & 15, kq = lane >> 4;
+    const int total_items = a.chunk_off[a.batch] * a.Hkv;
+
+    for (int item = blockIdx.x * 4 + wave; item < total_items; item += gridDim.x * 4) {
+        const int chunk_idx = item / a.Hkv, head = item % a.Hkv;
+        const int req = __builtin_amdgcn_readfirstlane(a.item_req[chunk_idx]);
+        const int cj = __builtin_amdgcn_readfirstlane(a.item_chunk[chunk_idx]);
+        const int n = __builtin_amdgcn_readfirstlane(min(max(a.n_or_len[req] + a.len_plus, 1), a.max_pages * kPageTokens));
+        const int t0 = cj * CH, t1 = min(n, t0 + CH);
+        const int npages = (t1 - t0 + kPageTokens - 1) / kPageTokens;
+        const int npairs = (npages + 1) / 2;
+
+        // page ids of this chunk, one per lane
+        int ptv = -1;
+        if (lane < npages)  // ids are validated on the host under SUN_VALIDATE; clamp so a bad table cannot fault
+            ptv = min(max(a.page_tables[(size_t)req * a.max_pages + t0 / kPageTokens + lane], 0), a.n_pages - 1);
+
+        // q as MFMA B operand: lane (head g = c16, dim octet kq) per 32-dim slice, hi + lo bf16
+        bf16x8 qhi[NS], qlo[NS];
+        {
+            const float* qp = a.q + ((size_t)req * a.Hq + head * G + (c16 < G ? c16 : 0)) * D;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                u32x4 h, l;
+                const f32x4 v0 = *reinterpret_cast<const f32x4*>(qp + s * 32 + kq * 8);
+                const f32x4 v1 = *reinterpret_cast<const f32x4*>(qp + s * 32 + kq * 8 + 4);
+                float x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const float xa = c16 < G ? x[2 * p] * a.qscale : 0.f;
+                    const float xb = c16 < G ? x[2 * p + 1] * a.qscale : 0.f;
+                    float ra, rb;
+                    h[p] = bf16_pair_hi(xa, xb, ra, rb);
+                    l[p] = pack_bf16(ra, rb);
+                }
+                qhi[s] = __builtin_bit_cast(bf16x8, h);
+                qlo[s] = __builtin_bit_cast(bf16x8, l);
+            }
+        }
+
+        const uint16_t* kb = a.kbase + head * a.k_head;
+        const uint16_t* vb = a.vbase + head * a.v_head;
+        // K operand rows: MFMA row i of tile 0 <-> page (i>>3), token 8*((i>>2)&1) + (i&3); tile 1: +4
+        const int k_psel = c16 >> 3, k_tok = 8 * ((c16 >> 2) & 1) + (c16 & 3);
+        const int64_t k_lane_off = (int64_t)k_tok * D + kq * 8;
+        // V^T operand: lane (dim c16 of a 16-dim block, token octet kq): page (kq>>1), tokens 8*(kq&1)..+7
+        const int v_psel = kq >> 1;
+        const int64_t v_lane_off = (int64_t)c16 * kPageTokens + 8 * (kq & 1);
+
+        u32x4 kc[2][NS], kn[2][NS], vc[NB], vn[NB];
+        auto load_pair = [&](int pp, u32x4(&k)[2][NS], u32x4(&v)[NB]) {
+            const int pA = __builtin_amdgcn_readlane(ptv, 2 * pp);
+            int pB = __builtin_amdgcn_readlane(ptv, 2 * pp + 1);
+            if (pB < 0) pB = pA;
+            const uint16_t* kp = kb + (int64_t)(k_psel ? pB : pA) * a.k_page + k_lane_off;
+            const uint16_t* vp = vb + (int64_t)(v_psel ? pB : pA) * a.v_page + v_lane_off;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                k[0][s] = *reinterpret_cast<const u32x4*>(kp + s * 32);
+                k[1][s] = *reinterpret_cast<const u32x4*>(kp + 4 * D + s * 32);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) v[b] = *reinterpret_cast<const u32x4*>(vp + b * 16 * kPageTokens);
+        };
+
+        f32x4 O[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) O[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float m_run = -INFINITY, l_run = 0.f;
+
+        auto process = [&](int pp, u32x4(&k)[2][NS], u32x4(&v)[NB]) {
+            f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const bf16x8 kx = __builtin_bit_cast(bf16x8, k[0][s]), ky = __builtin_bit_cast(bf16x8, k[1][s]);
+                sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qhi[s], sx, 0, 0, 0);
+                sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ky, qhi[s], sy, 0, 0, 0);
+                sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qlo[s], sx, 0, 0, 0);
+                sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ky, qlo[s], sy, 0, 0, 0);
+            }
+            // this lane: head c16, tokens tb + r (tile X) and tb + 4 + r (tile Y)
+            const int tb = t0 + pp * 32 + (kq >> 1) * 16 + 8 * (kq & 1);
+            float mloc = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                sx[r] = (tb + r < t1) ? sx[r] : -INFINITY;
+                sy[r] = (tb + 4 + r < t1) ? sy[r] : -INFINITY;
+                mloc = fmaxf(mloc, fmaxf(sx[r], sy[r]));
+            }
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+            const float m_new = fmaxf(m_run, mloc);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            float p[8], psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(sx[r] - m_new);
+                p[4 + r] = __builtin_amdgcn_exp2f(sy[r] - m_new);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) psum += p[e];
+            l_run = l_run * alpha + psum;
+            u32x4 ph, pl;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float ra, rb;
+                ph[e] = bf16_pair_hi(p[2 * e], p[2 * e + 1], ra, rb);
+                pl[e] = pack_bf16(ra, rb);
+            }
+            const bf16x8 phi = __builtin_bit_cast(bf16x8, ph), plo = __builtin_bit_cast(bf16x8, pl);
+            // rescale O: row (head) 4*kq + r of the output tile needs alpha of lane (head)
+            float al[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) al[r] = __shfl(alpha, 4 * kq + r);
+            // pool slots past the end of the cache may hold anything: zero their V
+            if (t0 + pp * 32 + 32 > t1) {
+                const int vt = t0 + pp * 32 + (kq >> 1) * 16 + 8 * (kq & 1);
+                uint32_t msk[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    msk[w] = (vt + 2 * w < t1 ? 0x0000ffffu : 0u) | (vt + 2 * w + 1 < t1 ? 0xffff0000u : 0u);
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) v[b][w] &= msk[w];
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) O[b][r] *= al[r];
+                const bf16x8 vt8 = __builtin_bit_cast(bf16x8, v[b]);
+                O[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, vt8, O[b], 0, 0, 0);
+                O[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, vt8, O[b], 0, 0, 0);
+            }
+        };
+
+        load_pair(0, kc, vc);
+        for (int pp = 0; pp < npairs; pp += 2) {
+            if (pp + 1 < npairs) load_pair(pp + 1, kn, vn);
+            process(pp, kc, vc);
+            if (pp + 1 >= npairs) break;
+            if (pp + 2 < npairs) load_pair(pp + 2, kc, vc);
+            process(pp + 1, kn, vn);
+        }
+
+        float l_tot = l_run + __shfl_xor(l_run, 16);
+        l_tot += __shfl_xor(l_tot, 32);
+        float* pbase = a.partial + ((size_t)chunk_idx * a.Hq + head * G) * (D + 2);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int g = 4 * kq + r;
+            if (g < G) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) pbase[(size_t)g * (D + 2) + b * 16 + c16] = O[b][r];
+            }
+        }
+        if (kq == 0 && c16 < G) {
+            pbase[(size_t)c16 * (D + 2) + D] = m_run;
+            pbase[(size_t)c16 * (D + 2) + D + 1] = l_tot;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// split kernel, fp32 vector-ALU variant (parity configuration); one wave per item
+// ---------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attn_split_f32_kernel(AttnArgs a, int G) {
+    __shared__ float sc[8][CH];
+    const int lane = threadIdx.x;
+    const int total_items = a.chunk_off[a.batch] * a.Hkv;
+    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
+        const int chunk_idx = item / a.Hkv, head = item % a.Hkv;
+        const int req = a.item_req[chunk_idx], cj = a.item_chunk[chunk_idx];
+        const int n = min(max(a.n_or_len[req] + a.len_plus, 1), a.max_pages * kPageTokens);
+        const int t0 = cj * CH, t1 = min(n, t0 + CH), cnt = t1 - t0;
+        const int32_t* pt = a.page_tables + (size_t)req * a.max_pages;
+        const uint16_t* kb = a.kbase + head * a.k_head;
+        const uint16_t* vb = a.vbase + head * a.v_head;
+        __syncthreads();
+        // scores: lane <-> token
+        for (int g = 0; g < G; ++g) {
+            const float* qp = a.q + ((size_t)req * a.Hq + head * G + g) * D;
+            for (int tt = lane; tt < cnt; tt += 64) {
+                const int t = t0 + tt;
+                const uint16_t* kr = kb + (int64_t)min(max(pt[t / kPageTokens], 0), a.n_pages - 1) * a.k_page + (t % kPageTokens) * D;
+                float acc = 0.f;
+                for (int j = 0; j < D; ++j) acc = fmaf(qp[j], bf16_bits_to_f32(kr[j]), acc);
+                sc[g][tt] = acc * a.qscale;
+            }
+        }
+        __syncthreads();
+        float* pbase = a.partial + ((size_t)chunk_idx * a.Hq + head * G) * (D + 2);
+        for (int g = 0; g < G; ++g) {
+            float mx = -INFINITY;
+            for (int tt = lane; tt < cnt; tt += 64) mx = fmaxf(mx, sc[g][tt]);
+            mx = wave_max(mx);
+            float sum = 0.f;
+            for (int tt = lane; tt < cnt; tt += 64) {
+                const float p = exp2f(sc[g][tt] - mx);
+                sc[g][tt] = p;
+                sum += p;
+            }
+            sum = wave_sum(sum);
+            __syncthreads();
+            // output: lane <-> dim
+            for (int j = lane; j < D; j += 64) {
+                float acc = 0.f;
+                for (int tt = 0; tt < cnt; ++tt) {
+                    const int t = t0 + tt;
+                    const uint16_t* vr = vb + (int64_t)min(max(pt[t / kPageTokens], 0), a.n_pages - 1) * a.v_page + j * kPageTokens + (t % kPageTokens);
+                    acc = fmaf(sc[g][tt], bf16_bits_to_f32(*vr), acc);
+                }
+                pbase[(size_t)g * (D + 2) + j] = acc;
+            }
+            if (lane == 0) {
+                pbase[(size_t)g * (D + 2) + D] = mx;
+                pbase[(size_t)g * (D + 2) + D + 1] = sum;
+            }
+        }
+    }
+}
+
+template <int D>
+static hipError_t launch_split_d(const AttnArgs& a, int G, int grid, hipStream_t st) {
+    switch (G) {
+#define SUN_CASE(g) \
+    case g: hipLaunchKernelGGL((attn_split_kernel<D, g>), dim3(grid), dim3(256), 0, st, a); break;
+        SUN_CASE(1) SUN_CASE(2) SUN_CASE(3) SUN_CASE(4) SUN_CASE(5) SUN_CASE(6) SUN_CASE(7) SUN_CASE(8)
+#undef SUN_CASE
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan, const float* q,
+                             const int32_t* page_tables, int max_pages, const int32_t* n_or_len, int len_plus,
+                             int batch, int total_chunks_hint, bool f32_exact, hipStream_t st) {
+    const sun_model_cfg& c = pool.cfg;
+    const sun_kv_layout& L = pool.lay;
+    const int D = c.head_dim, G = c.n_q_heads / c.n_kv_heads;
+    if (L.k_dim != 1 || L.k_token != D || L.v_token != 1 || L.v_dim != kPageTokens) return hipErrorInvalidValue;
+    AttnArgs a{};
+    a.kbase = pool.base + L.k_off + (int64_t)layer * L.k_layer;
+    a.vbase = pool.base + L.v_off + (int64_t)layer * L.v_layer;
+    a.k_page = L.k_page;
+    a.k_head = L.k_head;
+    a.v_page = L.v_page;
+    a.v_head = L.v_head;
+    a.q = q;
+    a.page_tables = page_tables;
+    a.n_or_len = n_or_len;
+    a.chunk_off = plan.chunk_off;
+    a.item_req = plan.item_req;
+    a.item_chunk = plan.item_chunk;
+    a.partial = plan.partial;
+    a.len_plus = len_plus;
+    a.max_pages = max_pages;
+    a.batch = batch;
+    a.Hq = c.n_q_heads;
+    a.Hkv = c.n_kv_heads;
+    a.n_pages = (int)L.n_pages;
+    a.qscale = kLog2e / sqrtf((float)D);
+    const long long chunks = total_chunks_hint >= 0 ? total_chunks_hint : plan.max_chunks;
+    const long long items = chunks * c.n_kv_heads;
+    if (f32_exact) {
+        if (G > 8) return hipErrorInvalidValue;
+        const int grid = (int)max(1LL, min(items, 4096LL));
+        if (D == 64) hipLaunchKernelGGL(attn_split_f32_kernel<64>, dim3(grid), dim3(64), 0, st, a, G);
+        else if (D == 128) hipLaunchKernelGGL(attn_split_f32_kernel<128>, dim3(grid), dim3(64), 0, st, a, G);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
+    // persistent waves: 2 workgroups of 4 waves per CU at most
+    const int grid = (int)max(1LL, min((items + 3) / 4, 512LL));
+    if (D == 64) return launch_split_d<64>(a, G, grid, st);
+    if (D == 128) return launch_split_d<128>(a, G, grid, st);
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------
+// combine: merge the chunk partials of a request in chunk order
+// ---------------------------------------------------------------------------------
+struct CombineArgs {
+    const int32_t* chunk_off;
+    const float* partial;
+    float* out_f32;
+    uint16_t* out_tiled;
+    float* hsum;
+    int Hq, D, batch, out_mb;
+};
+
+__global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
+    __shared__ float red[2];
+    const int b = blockIdx.y, col = blockIdx.x * 128 + threadIdx.x;
+    const int h = col / a.D, j = col % a.D;
+    const int c0 = a.chunk_off[b], c1 = a.chunk_off[b + 1];
+    const size_t stride = (size_t)a.Hq * (a.D + 2);
+    const float* p = a.partial + (size_t)c0 * stride + (size_t)h * (a.D + 2);
+    float M = -INFINITY;
+    for (int c = 0; c < c1 - c0; ++c) M = fmaxf(M, p[c * stride + a.D]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < c1 - c0; ++c) {
+        const float w = exp2f(p[c * stride + a.D] - M);
+        den = fmaf(w, p[c * stride + a.D + 1], den);
+        num = fmaf(w, p[c * stride + j], num);
+    }
+    const float v = num / den;
+    if (a.out_f32) a.out_f32[(size_t)b * a.Hq * a.D + col] = v;
+    if (a.out_tiled) {
+        const uint16_t bits = f32_to_bf16_bits(v);
+        a.out_tiled[atile_elem(ATile{a.out_mb}, b, col)] = bits;
+        if (a.hsum) {
+            const float s = wave_sum(bf16_bits_to_f32(bits));
+            if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+            __syncthreads();
+            if (threadIdx.x == 0) a.hsum[(size_t)blockIdx.x * (a.out_mb * 32) + b] = red[0] + red[1];
+        }
+    }
+}
+
+hipError_t launch_attn_combine(const sun_model_cfg& cfg, const AttnPlan& plan, int batch, float* out_f32,
+                               void* out_tiled, float* hsum, hipStream_t st) {
+    CombineArgs a{};
+    a.chunk_off = plan.chunk_off;
+    a.partial = plan.partial;
+    a.out_f32 = out_f32;
+    a.out_tiled = (uint16_t*)out_tiled;
+    a.hsum = hsum;
+    a.Hq = cfg.n_q_heads;
+    a.D = cfg.head_dim;
+    a.batch = batch;
+    a.out_mb = atile_for_rows(batch).MB;
+    const int cols = cfg.n_q_heads * cfg.head_dim;
+    if (cols % 128) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(cols / 128, batch), dim3(128), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace sun

@@ -1,0 +1,122 @@
+// Shared device/host helpers of the SUN shared-decode library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sun.h"
+
+namespace sun {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kWave = 64;
+constexpr int kPageTokens = 16;     // tokens per KV page
+constexpr int kAttnChunk = 256;     // tokens per split-K work item; a request's chunking depends on its own length only
+constexpr int kGroup = 128;         // quantisation group along K (Appendix A.1)
+constexpr int kMaxBatchTile = 256;  // rows one projection launch covers
+
+// ---- bf16 <-> f32 (round to nearest even) ----
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+}
+
+// ---- projection activations: "fragment-tiled" bf16 layout ----
+// A [rows, K] is stored so that one staging step of the MFMA projection kernels is a
+// linear copy into LDS and each 16-byte unit (8 consecutive k of one row) is one
+// lane's A operand of a 32x32x16 MFMA:
+//   unit(b, k/8) = ((chunk * 8 + kk) * MB + b/32) * 64 + half * 32 + b%32
+// with chunk = k / 128, g = (k % 128) / 8, half = g / 8, kk = g % 8.  Lane-half `half`
+// of k-step kk of a 128-wide chunk therefore carries k = chunk*128 + half*64 + kk*8 .. +7;
+// the packed weights use the same assignment, and any bijection is valid because the
+// MFMA sums over k.  MB = number of 32-row blocks (1, 2, 4 or 8).
+struct ATile {
+    int MB;
+};
+__host__ __device__ __forceinline__ ATile atile_for_rows(int rows) {
+    return ATile{rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 128 ? 4 : 8};
+}
+__host__ __device__ __forceinline__ size_t atile_unit(ATile t, int b, int k8) {
+    const int chunk = k8 >> 4, g = k8 & 15;
+    const int half = g >> 3, kk = g & 7;
+    return ((size_t)(chunk * 8 + kk) * t.MB + (b >> 5)) * 64 + half * 32 + (b & 31);
+}
+__host__ __device__ __forceinline__ size_t atile_elem(ATile t, int b, int k) {
+    return atile_unit(t, b, k >> 3) * 8 + (k & 7);
+}
+__host__ __device__ __forceinline__ size_t atile_bytes(ATile t, int K) { return (size_t)t.MB * 32 * K * 2; }
+
+// ---- wave reductions (all lanes receive the result; fixed order => deterministic) ----
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// ---- handles ----
+struct KvPool {
+    sun_model_cfg cfg;
+    uint16_t* base;
+    sun_kv_layout lay;
+    int n_source_models;
+};
+
+enum MatKind { MAT_NONE = 0, MAT_F32 = 1, MAT_BF16_PACKED = 2, MAT_W4_PACKED = 3, MAT_W4_LOGICAL = 4 };
+
+// One projection matrix as the kernels consume it.
+struct Mat {
+    int kind = MAT_NONE;
+    int N = 0, K = 0;          // logical out/in features (N counts gate+up rows for the fused pair)
+    const void* w = nullptr;   // F32: row-major fp32; BF16_PACKED / W4_PACKED: packed codes
+    const void* sz = nullptr;  // W4_PACKED: half2 (scale, zero) per (32-row block, group, row)
+    // W4_LOGICAL (fp32 activations): logical arrays, up to two stacked sources (gate, up)
+    const uint8_t* q[3] = {nullptr, nullptr, nullptr};
+    const uint16_t* s[3] = {nullptr, nullptr, nullptr};
+    const uint16_t* z[3] = {nullptr, nullptr, nullptr};
+    const void* wsrc[3] = {nullptr, nullptr, nullptr};  // F32: separate row-major sources
+    int nsrc = 0;
+    int src_rows[3] = {0, 0, 0};
+};
+
+struct LayerW {
+    const void* g1;
+    const void* g2;
+    Mat qkv, o, gu, down;
+};
+
+struct Weights {
+    sun_model_cfg cfg;
+    bool quant;
+    const void* embed;
+    const void* gf;
+    Mat lm;
+    LayerW* layers;
+};
+
+void set_error(const char* fmt, ...);
+
+}  // namespace sun
+
+#define SUN_HIP_CHECK(expr)                                                              \
+    do {                                                                                 \
+        hipError_t e_ = (expr);                                                          \
+        if (e_ != hipSuccess) {                                                          \
+            sun::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return SUN_ERR_HIP;                                                          \
+        }                                                                                \
+    } while (0)

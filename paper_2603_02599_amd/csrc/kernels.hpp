@@ -1,0 +1,91 @@
+// Host-side launchers of the HIP kernels (one translation unit per kernel family).
+#pragma once
+#include "common.hpp"
+
+namespace sun {
+
+// ---------------- projections (proj.hip) ----------------
+
+enum ProjEpilogue {
+    EPI_STORE = 0,   // fp32 partial sums: out[(split * ld_rows + b) * ldo + n]
+    EPI_SWIGLU = 1   // rows of W interleave 16 gate / 16 up; writes silu(g)*u as tiled bf16
+};
+
+struct ProjLaunch {
+    const Mat* W;
+    const void* A;         // tiled bf16 activations [rows, K]
+    const float* hsum;     // W4 only: [K/128][MB*32] sums of the (rounded) activations per group
+    int rows;              // valid rows (<= 256)
+    int epilogue;
+    int splits;            // split-K factor (EPI_STORE only); partial s is written at out + s*ld_rows*ldo
+    float* out;
+    int ldo;               // leading dimension of out (>= N)
+    int ld_rows;           // rows per split slab
+    void* out_tiled;       // EPI_SWIGLU: tiled bf16 [rows, N/2]
+};
+// Chooses the split-K factor the step uses for this matrix and row count.
+int proj_pick_splits(const Mat& W, int rows, int max_splits);
+hipError_t launch_proj(const ProjLaunch& p, hipStream_t st);
+
+// fp32 activations path (vector ALU): out[b][n] = sum_k W[n][k] x[b][k], out row-major [rows, N].
+hipError_t launch_proj_f32(const Mat& W, const float* x, int rows, float* out, hipStream_t st);
+
+// packing (weights load time)
+size_t packed_bf16_bytes(int N, int K);
+size_t packed_w4_bytes(int N, int K);     // codes
+size_t packed_w4_sz_bytes(int N, int K);  // scales / zero points
+// mode 0: rows of up to three sources stacked; mode 1: two sources interleaved in blocks of 16 rows.
+hipError_t launch_pack_bf16(const void* const src[3], const int src_rows[3], int nsrc, int mode, int K,
+                            void* dst, hipStream_t st);
+hipError_t launch_pack_w4(const sun_qmat src[3], const int src_rows[3], int nsrc, int mode, int K,
+                          void* dst_codes, void* dst_sz, hipStream_t st);
+hipError_t launch_quantize_w4(const void* w, int dtype, int rows, int cols, int group, int mode, void* q,
+                              void* s, void* z, hipStream_t st);
+
+// ---------------- attention (attention.hip) ----------------
+
+struct AttnPlan {           // device arrays inside the workspace
+    int32_t* chunk_off;     // [batch+1] prefix sum of chunks per request
+    int32_t* item_req;      // [max_chunks]
+    int32_t* item_chunk;    // [max_chunks]
+    float* partial;         // [max_chunks][Hq][d+2]  (o[d], m, l)
+    int max_chunks;
+};
+size_t attn_max_chunks(int batch, int max_pages);
+hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch, int max_pages,
+                            hipStream_t st);
+// n_tokens(i) = n_or_len[i] + len_plus.  q fp32 [batch, Hq*d].  total_chunks_hint < 0 if unknown.
+hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan, const float* q,
+                             const int32_t* page_tables, int max_pages, const int32_t* n_or_len, int len_plus,
+                             int batch, int total_chunks_hint, bool f32_exact, hipStream_t st);
+// out: fp32 row-major [batch, Hq*d] (out_f32) and/or tiled bf16 (+ per-128 group sums for W4).
+hipError_t launch_attn_combine(const sun_model_cfg& cfg, const AttnPlan& plan, int batch, float* out_f32,
+                               void* out_tiled, float* hsum, hipStream_t st);
+
+// ---------------- everything else (misc.hip) ----------------
+
+hipError_t launch_embed(const sun_model_cfg& cfg, const void* embed, const int32_t* tokens, int batch, float* x,
+                        hipStream_t st);
+// x[b] += sum_s partial[s][b] (s ascending; nparts may be 0); then h = rmsnorm(x; g).
+// h_f32: row-major fp32 or NULL; h_tiled: tiled bf16 or NULL; hsum: group sums or NULL.
+hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float* partial, int nparts, int ld_rows,
+                                const void* gain, int batch, float* h_f32, void* h_tiled, float* hsum, hipStream_t st);
+hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, int batch, float* table,
+                             hipStream_t st);
+// qkv partial sums [nparts][ld_rows][Nqkv] -> rotated q fp32 [batch, Hq*d]; K,V (bf16) appended to the pool.
+hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, int nparts, int ld_rows,
+                              const float* table, const int32_t* seq_lens, const int32_t* page_tables, int max_pages,
+                              int batch, float* q_out, hipStream_t st);
+hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipStream_t st);
+hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next, hipStream_t st);
+// fp32 [rows, K] -> tiled bf16 (+ group sums)
+hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st);
+// group sums of an already tiled bf16 activation matrix
+hipError_t launch_group_sums(const void* tiled, int rows, int K, float* hsum, hipStream_t st);
+// out[b][n] = sum_s partial[s][b][n]
+hipError_t launch_reduce_partials(const float* partial, int nparts, int ld_rows, int rows, int N, float* out,
+                                  hipStream_t st);
+// tiled bf16 [rows, K] -> fp32 row-major
+hipError_t launch_untile_rows(const void* tiled, int rows, int K, float* out, hipStream_t st);
+
+}  // namespace sun

@@ -1,0 +1,381 @@
+// Small kernels of the decode step (Eq. 3): embedding gather, residual + RMSNorm,
+// rotary embedding + KV append (Eq. 4), SwiGLU (fp32 path), greedy argmax, and the
+// layout helpers around the projection kernels.
+#include "kernels.hpp"
+
+namespace sun {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------- embedding: x[b] = E[token_b] ----------------
+__global__ __launch_bounds__(256) void embed_kernel(const void* __restrict__ E, int is_bf16, int H, int V,
+                                                    const int32_t* __restrict__ tokens, float* __restrict__ x) {
+    const int b = blockIdx.x;
+    int tok = tokens[b];
+    tok = min(max(tok, 0), V - 1);  // ids are validated on the host under SUN_VALIDATE; never fault here
+    for (int j = threadIdx.x; j < H; j += 256)
+        x[(size_t)b * H + j] = is_bf16 ? bf16_bits_to_f32(((const uint16_t*)E)[(size_t)tok * H + j])
+                                       : ((const float*)E)[(size_t)tok * H + j];
+}
+
+hipError_t launch_embed(const sun_model_cfg& cfg, const void* embed, const int32_t* tokens, int batch, float* x,
+                        hipStream_t st) {
+    hipLaunchKernelGGL(embed_kernel, dim3(batch), dim3(256), 0, st, embed, cfg.act_dtype == SUN_BF16, cfg.hidden,
+                       cfg.vocab, tokens, x);
+    return hipGetLastError();
+}
+
+// ---------------- residual add + RMSNorm ----------------
+// One block per row.  x += sum_s partial[s] (s ascending), h = x * rsqrt(mean(x^2) + eps) * g.
+struct NormArgs {
+    float* x;
+    const float* partial;
+    const void* gain;
+    float* h_f32;
+    uint16_t* h_tiled;
+    float* hsum;
+    int nparts, ld_rows, H, gain_bf16, mb;
+    float eps;
+};
+
+__global__ __launch_bounds__(256) void residual_norm_kernel(NormArgs a) {
+    __shared__ float red[4];
+    const int b = blockIdx.x, tid = threadIdx.x, H = a.H;
+    float* xr = a.x + (size_t)b * H;
+    float ss = 0.f;
+    for (int u = tid; u < H / 8; u += 256) {
+        float v[8];
+        *reinterpret_cast<f32x4*>(v) = *reinterpret_cast<const f32x4*>(xr + u * 8);
+        *reinterpret_cast<f32x4*>(v + 4) = *reinterpret_cast<const f32x4*>(xr + u * 8 + 4);
+        for (int s = 0; s < a.nparts; ++s) {
+            const float* p = a.partial + ((size_t)s * a.ld_rows + b) * H + u * 8;
+            const f32x4 p0 = *reinterpret_cast<const f32x4*>(p), p1 = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] += p0[e];
+                v[4 + e] += p1[e];
+            }
+        }
+        if (a.nparts > 0) {
+            *reinterpret_cast<f32x4*>(xr + u * 8) = *reinterpret_cast<f32x4*>(v);
+            *reinterpret_cast<f32x4*>(xr + u * 8 + 4) = *reinterpret_cast<f32x4*>(v + 4);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(v[e], v[e], ss);
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    const float rinv = 1.0f / sqrtf(tot / (float)H + a.eps);
+    for (int u0 = 0; u0 < H / 8; u0 += 256) {
+        const int u = u0 + tid;
+        float gsum = 0.f;
+        if (u < H / 8) {
+            float v[8], g[8];
+            *reinterpret_cast<f32x4*>(v) = *reinterpret_cast<const f32x4*>(xr + u * 8);
+            *reinterpret_cast<f32x4*>(v + 4) = *reinterpret_cast<const f32x4*>(xr + u * 8 + 4);
+            if (a.gain_bf16) {
+                const u32x4 gw = *reinterpret_cast<const u32x4*>((const uint16_t*)a.gain + u * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    g[2 * e] = bf16_lo(gw[e]);
+                    g[2 * e + 1] = bf16_hi(gw[e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) g[e] = ((const float*)a.gain)[u * 8 + e];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] * rinv * g[e];
+            if (a.h_f32) {
+                *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8) = *reinterpret_cast<f32x4*>(v);
+                *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8 + 4) = *reinterpret_cast<f32x4*>(v + 4);
+            }
+            if (a.h_tiled) {
+                u32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    o[e] = pack_bf16(v[2 * e], v[2 * e + 1]);
+                    gsum += bf16_lo(o[e]) + bf16_hi(o[e]);
+                }
+                reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, b, u)] = o;
+            }
+        }
+        if (a.hsum) {  // 16 consecutive units (lanes) form one 128-wide group
+            gsum += __shfl_xor(gsum, 1);
+            gsum += __shfl_xor(gsum, 2);
+            gsum += __shfl_xor(gsum, 4);
+            gsum += __shfl_xor(gsum, 8);
+            if (u < H / 8 && (tid & 15) == 0) a.hsum[(size_t)(u >> 4) * (a.mb * 32) + b] = gsum;
+        }
+    }
+}
+
+hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float* partial, int nparts, int ld_rows,
+                                const void* gain, int batch, float* h_f32, void* h_tiled, float* hsum, hipStream_t st) {
+    NormArgs a{};
+    a.x = x;
+    a.partial = partial;
+    a.gain = gain;
+    a.h_f32 = h_f32;
+    a.h_tiled = (uint16_t*)h_tiled;
+    a.hsum = hsum;
+    a.nparts = nparts;
+    a.ld_rows = ld_rows;
+    a.H = cfg.hidden;
+    a.gain_bf16 = cfg.act_dtype == SUN_BF16;
+    a.mb = atile_for_rows(batch).MB;
+    a.eps = cfg.rms_eps;
+    if (cfg.hidden % 8) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(residual_norm_kernel, dim3(batch), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ---------------- rotary table: cos/sin of pos * base^(-2j/d), angle in double ----------------
+__global__ __launch_bounds__(64) void rope_table_kernel(const int32_t* __restrict__ seq_lens, int d, double base,
+                                                        float* __restrict__ table) {
+    const int b = blockIdx.x;
+    const double pos = (double)seq_lens[b];
+    for (int j = threadIdx.x; j < d / 2; j += 64) {
+        const double theta = pow(base, -2.0 * (double)j / (double)d);
+        const double ang = pos * theta;
+        table[((size_t)b * (d / 2) + j) * 2] = (float)cos(ang);
+        table[((size_t)b * (d / 2) + j) * 2 + 1] = (float)sin(ang);
+    }
+}
+
+hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, int batch, float* table,
+                             hipStream_t st) {
+    hipLaunchKernelGGL(rope_table_kernel, dim3(batch), dim3(64), 0, st, seq_lens, cfg.head_dim, (double)cfg.rope_base,
+                       table);
+    return hipGetLastError();
+}
+
+// ---------------- rotary embedding + KV append ----------------
+// grid (Hq + 2*Hkv, batch): head index < Hq -> q head; next Hkv -> k head; last Hkv -> v head.
+struct RopeArgs {
+    const float* qkv;
+    const float* table;
+    const int32_t* seq_lens;
+    const int32_t* page_tables;
+    float* q_out;
+    uint16_t* pool;
+    int64_t k_base, k_page, k_head, k_token, k_dim, v_base, v_page, v_head, v_token, v_dim;
+    int nparts, ld_rows, Hq, Hkv, D, max_pages, n_pages;
+};
+
+__global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
+    const int b = blockIdx.y, hh = blockIdx.x, D = a.D, half = D / 2;
+    const int Nqkv = (a.Hq + 2 * a.Hkv) * D;
+    // lengths and page ids are validated on the host under SUN_VALIDATE; clamp so bad input cannot fault
+    const int L = min(max(a.seq_lens[b], 0), a.max_pages * kPageTokens - 1);
+    const int page = min(max(a.page_tables[(size_t)b * a.max_pages + L / kPageTokens], 0), a.n_pages - 1);
+    const int slot = L % kPageTokens;
+    const float* src = a.qkv + (size_t)b * Nqkv + (size_t)hh * D;
+    const size_t pstride = (size_t)a.ld_rows * Nqkv;
+    for (int j = threadIdx.x; j < half; j += 64) {
+        float lo = 0.f, hi = 0.f;
+        for (int s = 0; s < a.nparts; ++s) {
+            lo += src[s * pstride + j];
+            hi += src[s * pstride + j + half];
+        }
+        if (hh < a.Hq + a.Hkv) {
+            const float c = a.table[((size_t)b * half + j) * 2], sn = a.table[((size_t)b * half + j) * 2 + 1];
+            const float rl = lo * c - hi * sn, rh = hi * c + lo * sn;
+            lo = rl;
+            hi = rh;
+        }
+        if (hh < a.Hq) {
+            a.q_out[((size_t)b * a.Hq + hh) * D + j] = lo;
+            a.q_out[((size_t)b * a.Hq + hh) * D + j + half] = hi;
+        } else if (hh < a.Hq + a.Hkv) {
+            uint16_t* kd = a.pool + a.k_base + (int64_t)page * a.k_page + (int64_t)(hh - a.Hq) * a.k_head + slot * a.k_token;
+            kd[j * a.k_dim] = f32_to_bf16_bits(lo);
+            kd[(j + half) * a.k_dim] = f32_to_bf16_bits(hi);
+        } else {
+            uint16_t* vd = a.pool + a.v_base + (int64_t)page * a.v_page + (int64_t)(hh - a.Hq - a.Hkv) * a.v_head + slot * a.v_token;
+            vd[j * a.v_dim] = f32_to_bf16_bits(lo);
+            vd[(j + half) * a.v_dim] = f32_to_bf16_bits(hi);
+        }
+    }
+}
+
+hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, int nparts, int ld_rows,
+                              const float* table, const int32_t* seq_lens, const int32_t* page_tables, int max_pages,
+                              int batch, float* q_out, hipStream_t st) {
+    const sun_model_cfg& c = pool.cfg;
+    const sun_kv_layout& L = pool.lay;
+    RopeArgs a{};
+    a.qkv = qkv;
+    a.table = table;
+    a.seq_lens = seq_lens;
+    a.page_tables = page_tables;
+    a.q_out = q_out;
+    a.pool = pool.base;
+    a.k_base = L.k_off + (int64_t)layer * L.k_layer;
+    a.k_page = L.k_page;
+    a.k_head = L.k_head;
+    a.k_token = L.k_token;
+    a.k_dim = L.k_dim;
+    a.v_base = L.v_off + (int64_t)layer * L.v_layer;
+    a.v_page = L.v_page;
+    a.v_head = L.v_head;
+    a.v_token = L.v_token;
+    a.v_dim = L.v_dim;
+    a.nparts = nparts;
+    a.ld_rows = ld_rows;
+    a.Hq = c.n_q_heads;
+    a.Hkv = c.n_kv_heads;
+    a.D = c.head_dim;
+    a.max_pages = max_pages;
+    a.n_pages = (int)L.n_pages;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(c.n_q_heads + 2 * c.n_kv_heads, batch), dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+
+// ---------------- SwiGLU on fp32 [batch, 2*ffn] (gate columns first) ----------------
+__global__ __launch_bounds__(256) void swiglu_f32_kernel(const float* __restrict__ gu, int ffn, float* __restrict__ u) {
+    const int b = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= ffn) return;
+    const float g = gu[(size_t)b * 2 * ffn + j], up = gu[(size_t)b * 2 * ffn + ffn + j];
+    u[(size_t)b * ffn + j] = g / (1.0f + expf(-g)) * up;
+}
+
+hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipStream_t st) {
+    hipLaunchKernelGGL(swiglu_f32_kernel, dim3((ffn + 255) / 256, batch), dim3(256), 0, st, gu, ffn, u);
+    return hipGetLastError();
+}
+
+// ---------------- greedy argmax, lowest index on ties ----------------
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ next) {
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float* row = logits + (size_t)b * V;
+    float best = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int j = tid; j < V; j += 1024) {
+        const float v = row[j];
+        if (v > best || (v == best && j < idx)) {
+            best = v;
+            idx = j;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(idx, o);
+        if (ov > best || (ov == best && oi < idx)) {
+            best = ov;
+            idx = oi;
+        }
+    }
+    if ((tid & 63) == 0) {
+        bv[tid >> 6] = best;
+        bi[tid >> 6] = idx;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < idx)) {
+                best = bv[w];
+                idx = bi[w];
+            }
+        next[b] = idx == 0x7fffffff ? 0 : idx;
+    }
+}
+
+hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_kernel, dim3(batch), dim3(1024), 0, st, logits, vocab, next);
+    return hipGetLastError();
+}
+
+// ---------------- layout helpers ----------------
+__global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict__ x, int rows, int K, int mb,
+                                                        u32x4* __restrict__ tiled, float* __restrict__ hsum) {
+    const int b = blockIdx.y;
+    const int u = blockIdx.x * 256 + threadIdx.x;
+    float gsum = 0.f;
+    if (u < K / 8) {
+        const float* p = x + (size_t)b * K + u * 8;
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = pack_bf16(p[2 * e], p[2 * e + 1]);
+            gsum += bf16_lo(o[e]) + bf16_hi(o[e]);
+        }
+        tiled[atile_unit(ATile{mb}, b, u)] = o;
+    }
+    if (hsum) {
+        gsum += __shfl_xor(gsum, 1);
+        gsum += __shfl_xor(gsum, 2);
+        gsum += __shfl_xor(gsum, 4);
+        gsum += __shfl_xor(gsum, 8);
+        if (u < K / 8 && (threadIdx.x & 15) == 0) hsum[(size_t)(u >> 4) * (mb * 32) + b] = gsum;
+    }
+}
+
+hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st) {
+    if (K % 128) return hipErrorInvalidValue;
+    const int mb = atile_for_rows(rows).MB;
+    hipLaunchKernelGGL(tile_rows_kernel, dim3((K / 8 + 255) / 256, rows), dim3(256), 0, st, x, rows, K, mb,
+                       (u32x4*)tiled, hsum);
+    return hipGetLastError();
+}
+
+// one thread per (row, group): sums the 128 bf16 values of the group
+__global__ __launch_bounds__(256) void group_sums_kernel(const u32x4* __restrict__ tiled, int rows, int K, int mb,
+                                                         float* __restrict__ hsum) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int ng = K / 128;
+    if (idx >= rows * ng) return;
+    const int b = idx % rows, g = idx / rows;
+    float s = 0.f;
+    for (int u = 0; u < 16; ++u) {
+        const u32x4 w = tiled[atile_unit(ATile{mb}, b, g * 16 + u)];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += bf16_lo(w[e]) + bf16_hi(w[e]);
+    }
+    hsum[(size_t)g * (mb * 32) + b] = s;
+}
+
+hipError_t launch_group_sums(const void* tiled, int rows, int K, float* hsum, hipStream_t st) {
+    const int mb = atile_for_rows(rows).MB;
+    const int total = rows * (K / 128);
+    hipLaunchKernelGGL(group_sums_kernel, dim3((total + 255) / 256), dim3(256), 0, st, (const u32x4*)tiled, rows, K, mb,
+                       hsum);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts,
+                                                              int ld_rows, int N, float* __restrict__ out) {
+    const int b = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float v = 0.f;
+    for (int s = 0; s < nparts; ++s) v += partial[((size_t)s * ld_rows + b) * N + n];
+    out[(size_t)b * N + n] = v;
+}
+
+hipError_t launch_reduce_partials(const float* partial, int nparts, int ld_rows, int rows, int N, float* out,
+                                  hipStream_t st) {
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 255) / 256, rows), dim3(256), 0, st, partial, nparts, ld_rows,
+                       N, out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void untile_rows_kernel(const uint16_t* __restrict__ tiled, int K, int mb,
+                                                          float* __restrict__ out) {
+    const int b = blockIdx.y, k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    out[(size_t)b * K + k] = bf16_bits_to_f32(tiled[atile_elem(ATile{mb}, b, k)]);
+}
+
+hipError_t launch_untile_rows(const void* tiled, int rows, int K, float* out, hipStream_t st) {
+    const int mb = atile_for_rows(rows).MB;
+    hipLaunchKernelGGL(untile_rows_kernel, dim3((K + 255) / 256, rows), dim3(256), 0, st, (const uint16_t*)tiled, K, mb,
+                       out);
+    return hipGetLastError();
+}
+
+}  // namespace sun

@@ -1,0 +1,516 @@
+// Projections of the decode step: out[b, n] = sum_k W[n, k] x[b, k] for the skinny
+// batch (b <= 256) against the shared decode weights (Section 3.1, Eq. 3), and the
+// QSUN variant with W_hat = (Q - Z) * S, 4-bit codes in groups of 128 along k
+// (Section 3.3, Eq. 8; Appendix A.1).
+//
+// bf16 path: each weight byte is read from HBM once.  Weights are pre-tiled so that a
+// wave's 16-byte-per-lane load is 1 KiB contiguous and already is the B operand of a
+// 32x32x16 MFMA (lane n%32 <-> weight row, lane half <-> k octet).  Activations are
+// pre-tiled by their producer, staged through LDS (double buffered) and shared by the
+// waves of a workgroup; wave w owns 32 output columns and all batch rows.
+//
+// W4 path: codes are widened in registers to the bf16 value 128+q (a shift and an
+// and-or per pair), fed to the MFMA per 128-wide group, and the group's partial sum is
+// corrected and scaled in fp32:  acc += S * (sum_k (128+q_k) x_k - (128+Z) * sum_k x_k),
+// which equals sum_k (q_k - Z) S x_k up to fp32 rounding; the integer grid is never
+// rounded.  sum_k x_k per group comes from the activation producer.
+#include <hip/hip_fp16.h>
+
+#include "kernels.hpp"
+
+namespace sun {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct ProjArgs {
+    const u32x4* W;
+    const uint32_t* SZ;
+    const u32x4* A;
+    const float* hsum;
+    float* out;
+    uint16_t* out_tiled;
+    int rows, N, K;
+    int n_stages, stages_per_split;
+    int ldo, ld_rows;
+    int mb_total;  // 32-row blocks in the activation tiling
+    int out_mb;    // tiling of out_tiled
+};
+
+template <int MB, int KS, int NW, int EPI, bool W4>
+__global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
+    constexpr int KK = KS / 16;                // MFMA k-steps per stage
+    constexpr int STAGE_UNITS = KK * MB * 64;  // 16-byte units of activations per stage
+    constexpr int NT = NW * 64;
+    constexpr int UPT = STAGE_UNITS / NT;
+    static_assert(STAGE_UNITS % NT == 0, "stage must divide evenly over the workgroup");
+    constexpr int WREGS = W4 ? KK / 4 : KK;    // 16-byte weight loads per lane per stage
+
+    __shared__ u32x4 lds[2][STAGE_UNITS];
+    float* hs_lds = nullptr;  // W4: [2][MB*32] group sums of the activations, double buffered per chunk
+    if constexpr (W4) {
+        __shared__ __attribute__((aligned(16))) float hs_store[2 * MB * 32];
+        hs_lds = hs_store;
+    }
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5;
+    const int nb = blockIdx.x * NW + wave;
+    const bool active = nb < a.N / 32;
+    const int split = blockIdx.y;
+    const int mb_off = blockIdx.z * MB;
+    const int s0 = split * a.stages_per_split;
+    const int s1 = min(a.n_stages, s0 + a.stages_per_split);
+    const int kch = a.K / 128;
+
+    const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * (W4 ? 2 : 8) * 64 + lane;
+    const uint32_t* SZl = W4 ? a.SZ + ((size_t)(active ? nb : 0) * kch) * 32 + (lane & 31) : nullptr;
+
+    f32x16 acc[MB];
+    f32x16 accg[W4 ? MB : 1];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+
+    u32x4 w0[WREGS], w1[WREGS], areg[UPT];
+    uint32_t sz0 = 0, sz1 = 0;
+    float hreg = 0.f;
+
+    auto load_w = [&](u32x4(&w)[WREGS], uint32_t& sz, int st) {
+        if (active) {
+#pragma unroll
+            for (int j = 0; j < WREGS; ++j) w[j] = Wl[((size_t)st * WREGS + j) * 64];
+            if (W4) sz = SZl[(size_t)((st * KK) >> 3) * 32];
+        }
+    };
+    auto load_a = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            const int u = i * NT + tid;
+            const int kk = u / (MB * 64), rem = u % (MB * 64);
+            areg[i] = a.A[((size_t)(st * KK + kk) * a.mb_total + mb_off) * 64 + rem];
+        }
+        if (W4 && ((st * KK) & 7) == 0 && tid < MB * 32)
+            hreg = a.hsum[(size_t)((st * KK) >> 3) * (a.mb_total * 32) + mb_off * 32 + tid];
+    };
+    auto store_a = [&](int buf, int st) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) lds[buf][i * NT + tid] = areg[i];
+        if (W4 && ((st * KK) & 7) == 0 && tid < MB * 32) hs_lds[(((st * KK) >> 3) & 1) * MB * 32 + tid] = hreg;
+    };
+    auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
+        if (!active) return;
+        const bool first = (KS == 128) || ((st & 1) == 0);
+        const bool last = (KS == 128) || ((st & 1) == 1);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            bf16x8 bfrag;
+            if (W4) {
+                const uint32_t word = w[kk >> 2][kk & 3];
+                u32x4 t;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) t[p] = ((word >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
+                bfrag = __builtin_bit_cast(bf16x8, t);
+            } else {
+                bfrag = __builtin_bit_cast(bf16x8, w[kk]);
+            }
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                const bf16x8 afrag = __builtin_bit_cast(bf16x8, lds[buf][(kk * MB + m) * 64 + lane]);
+                if (W4) {
+                    if (first && kk == 0) {
+                        f32x16 zero;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                        accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, zero, 0, 0, 0);
+                    } else {
+                        accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, accg[m], 0, 0, 0);
+                    }
+                } else {
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[m], 0, 0, 0);
+                }
+            }
+        }
+        if (W4 && last) {
+            const __half2 h2 = __builtin_bit_cast(__half2, sz);
+            const float s = __low2float(h2), nzz = -(128.f + __high2float(h2));
+            const float* hs = hs_lds + (((st * KK) >> 3) & 1) * MB * 32;
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs + m * 32 + 8 * rr + 4 * half);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[m][rr * 4 + q] = fmaf(s, fmaf(nzz, h4[q], accg[m][rr * 4 + q]), acc[m][rr * 4 + q]);
+                }
+        }
+    };
+
+    if (s0 < s1) {
+        load_w(w0, sz0, s0);
+        load_a(s0);
+        store_a(0, s0);
+        __syncthreads();
+        for (int st = s0; st < s1; st += 2) {
+            const bool more1 = st + 1 < s1;
+            if (more1) {
+                load_w(w1, sz1, st + 1);
+                load_a(st + 1);
+            }
+            compute(0, w0, sz0, st);
+            if (more1) store_a(1, st + 1);
+            __syncthreads();
+            if (!more1) break;
+            const bool more2 = st + 2 < s1;
+            if (more2) {
+                load_w(w0, sz0, st + 2);
+                load_a(st + 2);
+            }
+            compute(1, w1, sz1, st + 1);
+            if (more2) store_a(0, st + 2);
+            __syncthreads();
+        }
+    }
+    if (!active) return;
+
+    const int col = lane & 31;
+    if (EPI == EPI_STORE) {
+        float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (b < a.rows) o[(size_t)b * a.ldo] = acc[m][r];
+            }
+    } else {
+        const ATile ot{a.out_mb};
+        const int ucol = nb * 16 + (lane & 15);
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v = acc[m][r];
+                const float other = __shfl_xor(v, 16);
+                const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if ((lane & 16) == 0 && b < a.rows) {
+                    const float y = v / (1.f + __expf(-v)) * other;
+                    a.out_tiled[atile_elem(ot, b, ucol)] = f32_to_bf16_bits(y);
+                }
+            }
+    }
+}
+
+template <int MB, int KS, bool W4>
+static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
+    constexpr int NW = 4;
+    dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
+    if (epilogue == EPI_STORE)
+        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4>), grid, block, 0, st, a);
+    else
+        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, W4>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / splits; }
+
+int proj_pick_splits(const Mat& W, int rows, int max_splits) {
+    const int tiles = (W.N / 32 + 3) / 4, kch = W.K / 128;
+    const int target = rows <= 64 ? 512 : 256;
+    int s = (target + tiles - 1) / tiles;
+    s = min(s, max_splits);
+    s = min(s, max(1, kch / 2));
+    s = max(s, 1);
+    const int cps = chunks_per_split(kch, s);
+    return (kch + cps - 1) / cps;
+}
+
+hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
+    const Mat& W = *p.W;
+    const bool w4 = W.kind == MAT_W4_PACKED;
+    if (!w4 && W.kind != MAT_BF16_PACKED) return hipErrorInvalidValue;
+    if (p.rows < 1 || p.rows > kMaxBatchTile || W.N % 32 || W.K % 128) return hipErrorInvalidValue;
+    const ATile at = atile_for_rows(p.rows);
+    ProjArgs a{};
+    a.W = (const u32x4*)W.w;
+    a.SZ = (const uint32_t*)W.sz;
+    a.A = (const u32x4*)p.A;
+    a.hsum = p.hsum;
+    a.out = p.out;
+    a.out_tiled = (uint16_t*)p.out_tiled;
+    a.rows = p.rows;
+    a.N = W.N;
+    a.K = W.K;
+    a.ldo = p.ldo;
+    a.ld_rows = p.ld_rows;
+    a.mb_total = at.MB;
+    a.out_mb = at.MB;
+    const int kch = W.K / 128;
+    int splits = p.epilogue == EPI_STORE ? max(1, p.splits) : 1;
+    const int cps = chunks_per_split(kch, splits);
+    splits = (kch + cps - 1) / cps;
+    const int mb = at.MB;
+    if (w4 && p.hsum == nullptr) return hipErrorInvalidValue;
+    // stage width: 128 for up to 64 rows, 64 above (LDS budget)
+    if (mb <= 2) {
+        a.n_stages = kch;
+        a.stages_per_split = cps;
+        if (mb == 1) return w4 ? launch_proj_t<1, 128, true>(a, p.epilogue, splits, 1, st)
+                               : launch_proj_t<1, 128, false>(a, p.epilogue, splits, 1, st);
+        return w4 ? launch_proj_t<2, 128, true>(a, p.epilogue, splits, 1, st)
+                  : launch_proj_t<2, 128, false>(a, p.epilogue, splits, 1, st);
+    }
+    a.n_stages = kch * 2;
+    a.stages_per_split = cps * 2;
+    if (mb == 4) return w4 ? launch_proj_t<4, 64, true>(a, p.epilogue, splits, 1, st)
+                           : launch_proj_t<4, 64, false>(a, p.epilogue, splits, 1, st);
+    // 256 rows: bf16 covers them in one pass; W4 runs two 128-row tiles (accumulator budget)
+    return w4 ? launch_proj_t<4, 64, true>(a, p.epilogue, splits, 2, st)
+              : launch_proj_t<8, 64, false>(a, p.epilogue, splits, 1, st);
+}
+
+// ---------------------------------------------------------------------------------
+// fp32 path (parity configuration): plain vector-ALU dot products, one wave per column
+// ---------------------------------------------------------------------------------
+
+struct F32Mat {
+    const float* w[3];
+    const uint8_t* q[3];
+    const uint16_t* s[3];
+    const uint16_t* z[3];
+    int rows[3];
+    int nsrc, N, K, quant;
+};
+
+template <int BT>
+__global__ __launch_bounds__(256) void proj_f32_kernel(F32Mat m, const float* __restrict__ x, int nrows,
+                                                       float* __restrict__ out) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + wave;
+    if (n >= m.N) return;
+    const int b0 = blockIdx.y * BT;
+    int src = 0, r = n;
+    while (src + 1 < m.nsrc && r >= m.rows[src]) {
+        r -= m.rows[src];
+        ++src;
+    }
+    float acc[BT];
+#pragma unroll
+    for (int j = 0; j < BT; ++j) acc[j] = 0.f;
+    const int ng = m.K / kGroup;
+    for (int k = lane; k < m.K; k += 64) {
+        float wv;
+        if (m.quant) {
+            const uint8_t byte = m.q[src][(size_t)r * (m.K / 2) + (k >> 1)];
+            const float code = (float)((k & 1) ? (byte >> 4) : (byte & 15));
+            const size_t g = (size_t)r * ng + k / kGroup;
+            const float zf = __half2float(__ushort_as_half(m.z[src][g]));
+            const float sf = __half2float(__ushort_as_half(m.s[src][g]));
+            wv = (code - zf) * sf;  // exact: 5-bit integer times an 11-bit significand
+        } else {
+            wv = m.w[src][(size_t)r * m.K + k];
+        }
+#pragma unroll
+        for (int j = 0; j < BT; ++j) {
+            const int b = min(b0 + j, nrows - 1);
+            acc[j] = fmaf(wv, x[(size_t)b * m.K + k], acc[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < BT; ++j) {
+        const float v = wave_sum(acc[j]);
+        if (lane == 0 && b0 + j < nrows) out[(size_t)(b0 + j) * m.N + n] = v;
+    }
+}
+
+hipError_t launch_proj_f32(const Mat& W, const float* x, int rows, float* out, hipStream_t st) {
+    F32Mat m{};
+    m.nsrc = W.nsrc;
+    m.N = W.N;
+    m.K = W.K;
+    m.quant = W.kind == MAT_W4_LOGICAL;
+    if (!m.quant && W.kind != MAT_F32) return hipErrorInvalidValue;
+    for (int i = 0; i < 3; ++i) {
+        m.w[i] = (const float*)W.wsrc[i];
+        m.q[i] = W.q[i];
+        m.s[i] = W.s[i];
+        m.z[i] = W.z[i];
+        m.rows[i] = W.src_rows[i];
+    }
+    constexpr int BT = 8;
+    dim3 grid((W.N + 3) / 4, (rows + BT - 1) / BT);
+    hipLaunchKernelGGL(proj_f32_kernel<BT>, grid, dim3(256), 0, st, m, x, rows, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// packing
+// ---------------------------------------------------------------------------------
+
+size_t packed_bf16_bytes(int N, int K) { return (size_t)N * K * 2; }
+size_t packed_w4_bytes(int N, int K) { return (size_t)N * K / 2; }
+size_t packed_w4_sz_bytes(int N, int K) { return (size_t)N * (K / 128) * 4; }
+
+struct PackSrc {
+    const void* p[3];
+    const void* s[3];
+    const void* z[3];
+    int rows[3];
+    int nsrc, mode, K, N;
+};
+
+// packed row pn -> (source, row).  mode 0: stacked.  mode 1: blocks of 16 rows alternate
+// between source 0 (gate) and source 1 (up).
+__device__ __forceinline__ void pack_row(const PackSrc& s, int pn, int& src, int& row) {
+    if (s.mode == 1) {
+        src = (pn >> 4) & 1;
+        row = (pn >> 5) * 16 + (pn & 15);
+    } else {
+        src = 0;
+        row = pn;
+        while (src + 1 < s.nsrc && row >= s.rows[src]) {
+            row -= s.rows[src];
+            ++src;
+        }
+    }
+}
+
+// one thread per 16-byte unit of the packed matrix: [N/32][K/128][8][64] x 8 bf16
+__global__ __launch_bounds__(256) void pack_bf16_kernel(PackSrc s, u32x4* __restrict__ dst) {
+    const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)s.N * s.K / 8;
+    if (u >= total) return;
+    const int lane = (int)(u & 63), kk = (int)((u >> 6) & 7);
+    const size_t t = u >> 9;
+    const int kch = s.K / 128;
+    const int c = (int)(t % kch), nb = (int)(t / kch);
+    const int pn = nb * 32 + (lane & 31), half = lane >> 5;
+    const int k = c * 128 + half * 64 + kk * 8;
+    int src, row;
+    pack_row(s, pn, src, row);
+    dst[u] = *reinterpret_cast<const u32x4*>((const uint16_t*)s.p[src] + (size_t)row * s.K + k);
+}
+
+// one thread per packed dword (8 codes): [N/32][K/128][2][64][4 dwords]
+__global__ __launch_bounds__(256) void pack_w4_kernel(PackSrc s, uint32_t* __restrict__ dst,
+                                                      uint32_t* __restrict__ dst_sz) {
+    const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)s.N * s.K / 8;
+    if (u >= total) return;
+    const int comp = (int)(u & 3), lane = (int)((u >> 2) & 63), j = (int)((u >> 8) & 1);
+    const size_t t = u >> 9;
+    const int kch = s.K / 128;
+    const int c = (int)(t % kch), nb = (int)(t / kch);
+    const int kk = j * 4 + comp;
+    const int pn = nb * 32 + (lane & 31), half = lane >> 5;
+    const int k = c * 128 + half * 64 + kk * 8;
+    int src, row;
+    pack_row(s, pn, src, row);
+    const uint32_t word = *reinterpret_cast<const uint32_t*>((const uint8_t*)s.p[src] + ((size_t)row * s.K + k) / 2);
+    // logical: code e at bits [4e, 4e+4).  packed: e = 2p at bits [4p..], e = 2p+1 at bits [16+4p..]
+    uint32_t o = 0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        o |= ((word >> (8 * p)) & 15u) << (4 * p);
+        o |= ((word >> (8 * p + 4)) & 15u) << (16 + 4 * p);
+    }
+    dst[u] = o;
+    if (kk == 0 && half == 0) {
+        const size_t g = (size_t)row * kch + c;
+        const uint32_t sv = ((const uint16_t*)s.s[src])[g], zv = ((const uint16_t*)s.z[src])[g];
+        dst_sz[((size_t)nb * kch + c) * 32 + (lane & 31)] = sv | (zv << 16);
+    }
+}
+
+static PackSrc make_src(const void* const p[3], const void* const s[3], const void* const z[3],
+                        const int rows[3], int nsrc, int mode, int K) {
+    PackSrc ps{};
+    ps.nsrc = nsrc;
+    ps.mode = mode;
+    ps.K = K;
+    ps.N = 0;
+    for (int i = 0; i < 3; ++i) {
+        ps.p[i] = p[i];
+        ps.s[i] = s ? s[i] : nullptr;
+        ps.z[i] = z ? z[i] : nullptr;
+        ps.rows[i] = i < nsrc ? rows[i] : 0;
+        ps.N += ps.rows[i];
+    }
+    return ps;
+}
+
+hipError_t launch_pack_bf16(const void* const src[3], const int src_rows[3], int nsrc, int mode, int K, void* dst,
+                            hipStream_t st) {
+    PackSrc ps = make_src(src, nullptr, nullptr, src_rows, nsrc, mode, K);
+    const size_t total = (size_t)ps.N * K / 8;
+    hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, ps, (u32x4*)dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_w4(const sun_qmat src[3], const int src_rows[3], int nsrc, int mode, int K, void* dst_codes,
+                          void* dst_sz, hipStream_t st) {
+    const void *p[3] = {nullptr, nullptr, nullptr}, *s[3] = {nullptr, nullptr, nullptr}, *z[3] = {nullptr, nullptr, nullptr};
+    for (int i = 0; i < nsrc; ++i) {
+        p[i] = src[i].q;
+        s[i] = src[i].s;
+        z[i] = src[i].z;
+    }
+    PackSrc ps = make_src(p, s, z, src_rows, nsrc, mode, K);
+    const size_t total = (size_t)ps.N * K / 8;
+    hipLaunchKernelGGL(pack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, ps,
+                       (uint32_t*)dst_codes, (uint32_t*)dst_sz);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// round-to-nearest group quantiser (one wave per group of 128 weights)
+// ---------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void quantize_w4_kernel(const void* __restrict__ w, int dtype, int rows, int cols,
+                                                          int mode, uint8_t* __restrict__ q, uint16_t* __restrict__ s,
+                                                          uint16_t* __restrict__ z) {
+    const int lane = threadIdx.x & 63;
+    const size_t grp = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int ng = cols / kGroup;
+    if (grp >= (size_t)rows * ng) return;
+    const size_t row = grp / ng;
+    const int g = (int)(grp % ng);
+    const size_t e0 = row * cols + (size_t)g * kGroup + 2 * lane;
+    float a, b;
+    if (dtype == SUN_BF16) {
+        const uint32_t pr = *reinterpret_cast<const uint32_t*>((const uint16_t*)w + e0);
+        a = bf16_lo(pr);
+        b = bf16_hi(pr);
+    } else {
+        a = ((const float*)w)[e0];
+        b = ((const float*)w)[e0 + 1];
+    }
+    const float mn = -wave_max(-fminf(a, b)), mx = wave_max(fmaxf(a, b));
+    const float amax = wave_max(fmaxf(fabsf(a), fabsf(b)));
+    const float sf = mode == 0 ? __fdiv_rn(mx - mn, 15.0f) : __fdiv_rn(amax, 7.0f);
+    __half sh = __float2half_rn(sf);
+    float S = __half2float(sh);
+    if (S == 0.f) {
+        S = 1.f;
+        sh = __float2half_rn(1.f);
+    }
+    const float Z = mode == 0 ? fminf(fmaxf(rintf(__fdiv_rn(-mn, S)), 0.f), 15.f) : 8.f;
+    const int qa = (int)fminf(fmaxf(rintf(__fdiv_rn(a, S)) + Z, 0.f), 15.f);
+    const int qb = (int)fminf(fmaxf(rintf(__fdiv_rn(b, S)) + Z, 0.f), 15.f);
+    q[(row * cols + (size_t)g * kGroup) / 2 + lane] = (uint8_t)(qa | (qb << 4));
+    if (lane == 0) {
+        s[grp] = __half_as_ushort(sh);
+        z[grp] = __half_as_ushort(__float2half_rn(Z));
+    }
+}
+
+hipError_t launch_quantize_w4(const void* w, int dtype, int rows, int cols, int group, int mode, void* q, void* s,
+                              void* z, hipStream_t st) {
+    if (group != kGroup || cols % kGroup) return hipErrorInvalidValue;
+    const size_t groups = (size_t)rows * (cols / kGroup);
+    hipLaunchKernelGGL(quantize_w4_kernel, dim3((unsigned)((groups + 3) / 4)), dim3(256), 0, st, w, dtype, rows, cols,
+                       mode, (uint8_t*)q, (uint16_t*)s, (uint16_t*)z);
+    return hipGetLastError();
+}
+
+}  // namespace sun

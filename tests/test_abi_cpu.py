@@ -1,0 +1,158 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_02599_amd import binding as sun
+from paper_2603_02599_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2603_02599_amd.build import build_lib
+    build_lib()
+    return sun.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "sun.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(sun_[a-z0-9_]+)\s*\(", header))
+    assert len(names) >= 19
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in sun.h but not exported"
+    assert set(sun.EXPORTS) == names
+    assert b"gfx950" in lib.sun_version()
+
+
+def test_struct_sizes_match_the_header():
+    assert C.sizeof(sun.ModelCfg) == 40
+    assert C.sizeof(sun.KvLayout) == 8 + 8 + 12 * 8 + 8
+    assert C.sizeof(sun.QMat) == 24
+
+
+FAKE = 0x7F0000000000  # aligned, never dereferenced: these calls fail (or only store it) before any GPU work
+
+
+def _pool(lib, cfg, n_pages=4, nsrc=3):
+    out = C.c_void_p()
+    nbytes = lib.sun_kv_pool_bytes(C.byref(cfg), n_pages, 16)
+    rc = lib.sun_kv_pool_create(C.byref(cfg), FAKE, nbytes, 16, nsrc, C.byref(out))
+    return rc, out
+
+
+def test_pool_create_and_layout(lib):
+    cfg = sun.make_cfg(wl.TINY, "f32")
+    rc, pool = _pool(lib, cfg, 5)
+    assert rc == 0
+    lay = sun.KvLayout()
+    assert lib.sun_kv_pool_layout(pool, C.byref(lay)) == 0
+    assert lay.n_pages == 5 and lay.page_tokens == 16
+    per_page = 2 * wl.TINY.n_kv_heads * 16 * wl.TINY.head_dim
+    assert lay.total_elems == wl.TINY.n_layers * 5 * per_page == lib.sun_kv_pool_bytes(C.byref(cfg), 5, 16) // 2
+    # K is [token][dim], V is [dim][token] inside a (layer, page, head) block; blocks do not overlap
+    assert (lay.k_token, lay.k_dim, lay.v_token, lay.v_dim) == (64, 1, 1, 16)
+    assert lay.v_off - lay.k_off == wl.TINY.n_kv_heads * 16 * 64 and lay.k_page == per_page
+    lib.sun_kv_pool_destroy(pool)
+
+
+def test_pool_create_errors(lib):
+    cfg = sun.make_cfg(wl.TINY, "f32")
+    out = C.c_void_p()
+    assert lib.sun_kv_pool_create(C.byref(cfg), None, 1 << 20, 16, 1, C.byref(out)) == 1       # NULL memory
+    assert lib.sun_kv_pool_create(C.byref(cfg), FAKE, 1 << 20, 8, 1, C.byref(out)) == 2        # page size
+    assert lib.sun_kv_pool_create(C.byref(cfg), FAKE, 100, 16, 1, C.byref(out)) == 3           # no page fits
+    assert lib.sun_kv_pool_create(C.byref(cfg), FAKE + 4, 1 << 20, 16, 1, C.byref(out)) == 3   # misaligned
+    assert lib.sun_kv_pool_create(C.byref(cfg), FAKE, 1 << 20, 16, 0, C.byref(out)) == 7       # no source model
+    assert b"source" in lib.sun_last_error()
+    bad = sun.make_cfg(wl.TINY, "f32")
+    bad.head_dim = 48
+    assert lib.sun_kv_pool_create(C.byref(bad), FAKE, 1 << 20, 16, 1, C.byref(out)) == 2
+    bad = sun.make_cfg(wl.TINY, "bf16")      # ffn 688 is not a multiple of 128
+    assert lib.sun_kv_pool_create(C.byref(bad), FAKE, 1 << 20, 16, 1, C.byref(out)) == 2
+    assert lib.sun_kv_pool_create(None, FAKE, 1 << 20, 16, 1, C.byref(out)) == 1
+
+
+def _f32_weights(lib, cfg, shape):
+    nl = shape.n_layers
+    arrs = [(C.c_void_p * nl)(*([FAKE] * nl)) for _ in range(9)]
+    ptrs = sun.WeightPtrs()
+    ptrs.embed = ptrs.gf = ptrs.wlm = FAKE
+    for k, a in zip(sun.LAYER_KEYS, arrs):
+        setattr(ptrs, k, C.cast(a, C.POINTER(C.c_void_p)))
+    out = C.c_void_p()
+    rc = lib.sun_weights_create(C.byref(cfg), C.byref(ptrs), None, 0, None, C.byref(out))
+    return rc, out, (arrs, ptrs)
+
+
+def test_weights_create_errors_and_sizes(lib):
+    cfg = sun.make_cfg(wl.TINY, "f32")
+    rc, w, keep = _f32_weights(lib, cfg, wl.TINY)
+    assert rc == 0 and w.value
+    lib.sun_weights_destroy(w)
+    ptrs = keep[1]
+    ptrs.wlm = None
+    out = C.c_void_p()
+    assert lib.sun_weights_create(C.byref(cfg), C.byref(ptrs), None, 0, None, C.byref(out)) == 1
+    # bf16 needs pack memory
+    cfg_b = sun.make_cfg(wl.SMALL128, "bf16")
+    assert lib.sun_weights_pack_bytes(C.byref(cfg_b)) == 2 * (wl.SMALL128.body_params + wl.SMALL128.vocab * wl.SMALL128.hidden)
+    rc, _, _ = _f32_weights(lib, cfg_b, wl.SMALL128)
+    assert rc == 1
+    cfg8 = sun.make_cfg(wl.LLAMA_8B, "bf16")
+    assert lib.sun_weights_pack_bytes(C.byref(cfg8)) == 2 * (wl.LLAMA_8B.body_params + 128256 * 4096)
+    qb = lib.sun_qweights_pack_bytes(C.byref(cfg8), 128)
+    assert qb == int(wl.LLAMA_8B.body_params * 0.53125) + 2 * 128256 * 4096      # 4 bits + fp16 scale and zero per 128
+    assert lib.sun_qweights_pack_bytes(C.byref(cfg8), 64) == 0
+
+
+def test_step_rejects_bad_arguments_before_enqueueing(lib):
+    cfg = sun.make_cfg(wl.TINY, "f32")
+    rc, pool = _pool(lib, cfg)
+    assert rc == 0
+    rc, w, keep = _f32_weights(lib, cfg, wl.TINY)
+    assert rc == 0
+    need = lib.sun_workspace_bytes(C.byref(cfg), 8, 9)
+    assert need > 0 and lib.sun_workspace_bytes(C.byref(cfg), 0, 9) == 0
+
+    def step(fn=lib.sun_decode_step, pool=pool, w=w, batch=8, tok=FAKE, pt=FAKE, mp=9, lens=FAKE, ids=FAKE, nxt=FAKE,
+             ws=FAKE, wsb=need):
+        return fn(pool, w, batch, tok, pt, mp, lens, None, ids, None, nxt, ws, wsb, None, 0)
+
+    assert step(pool=None) == 1 and step(w=None) == 1
+    assert step(tok=None) == 1 and step(pt=None) == 1 and step(lens=None) == 1 and step(ids=None) == 1
+    assert step(nxt=None) == 1 and step(ws=None) == 1
+    assert step(batch=0) == 2 and step(batch=257) == 2 and step(mp=0) == 2
+    assert step(wsb=need - 1) == 4 and b"workspace" in lib.sun_last_error()
+    assert step(ws=FAKE + 8) == 4
+    assert step(fn=lib.sun_qdecode_step) == 2          # dense weights handed to the QSUN entry point
+    other = sun.make_cfg(wl.TINY_Q, "f32")
+    rc, pool2 = _pool(lib, other)
+    assert rc == 0 and step(pool=pool2) == 2           # pool and weights of different shapes
+    lib.sun_kv_pool_destroy(pool2)
+    lib.sun_weights_destroy(w)
+    lib.sun_kv_pool_destroy(pool)
+
+
+def test_single_op_argument_checks(lib):
+    cfg = sun.make_cfg(wl.TINY, "f32")
+    rc, pool = _pool(lib, cfg)
+    assert lib.sun_paged_attention(pool, 5, 1, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == 2
+    assert lib.sun_paged_attention(pool, 0, 1, None, FAKE, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == 1
+    assert lib.sun_paged_attention(pool, 0, 1, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, 16, None) == 4
+    assert lib.sun_quantize_w4(FAKE, 0, 4, 256, 64, 0, FAKE, FAKE, FAKE, None) == 2
+    assert lib.sun_quantize_w4(FAKE, 0, 4, 200, 128, 0, FAKE, FAKE, FAKE, None) == 2
+    assert lib.sun_quantize_w4(None, 0, 4, 256, 128, 0, FAKE, FAKE, FAKE, None) == 1
+    lib.sun_kv_pool_destroy(pool)
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(sun, "_lib", None)
+    monkeypatch.setattr(sun, "LIB_PATH", "/nonexistent/libsun.so")
+    with pytest.raises(FileNotFoundError):
+        sun.lib()

@@ -1,0 +1,282 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on identical
+seeded inputs.  fp32 logits: max-abs <= 1e-4.  bf16 / QSUN logits: |g - o| <= 2e-2 + 1e-2 |o|.
+Next tokens: exact, except documented near-ties (oracle top-2 gap below twice the tolerance)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2603_02599_amd import binding as sun  # noqa: E402
+from paper_2603_02599_amd import workloads as wl  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_harness
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    sun.lib()
+    return gpu_harness
+
+
+def _full_step_parity(H, case, rows=None, tol=None):
+    from oracle import oracle as orc
+    work = case.work
+    rows = list(range(work.batch)) if rows is None else list(rows)
+    before_host, _, tabs, used = case.extract_pool(rows)
+    ref = H.run_oracle(case, rows)
+    case.step(flags=sun.SUN_VALIDATE)
+    got_logits = case.logits.cpu().numpy()[rows]
+    got_next = case.next.cpu().numpy()[rows]
+    rep = H.logits_report(got_logits, ref["logits"])
+    H.say(f"{work.name}/{work.shape.name}/{work.dtype} B={work.batch} rows={len(rows)} logits {rep}")
+    H.check_logits(got_logits, ref["logits"], work.dtype)
+    tol = tol if tol is not None else (1e-4 if work.dtype == "f32" else 2e-2)
+    near = H.check_next_tokens(got_next, ref["logits"], tol)
+    st = H.layout_strides(case.lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
+    mask = H.appended_mask(work.shape, st, before_host.size, tabs, work.seq_lens[rows])
+    off, total = H.check_appended_kv(case.pool_pages_now(used), ref["pool_after"], before_host, mask, work.dtype)
+    H.say(f"   next-token near-ties {near}; appended K/V elements off by >=1 bf16 ulp: {off} of {total}")
+    return rep
+
+
+# ------------------------------------------------------------------ fp32 parity configuration
+def test_cfg1_tiny_fp32_full_step(H):
+    H.say("cfg1 tiny fp32")
+    case = H.GpuCase(wl.make_workload("cfg1"))
+    rep = _full_step_parity(H, case)
+    assert rep["ref_std"] > 0.05
+
+
+@pytest.mark.parametrize("lens", [[0, 1, 15, 16, 17, 31, 32, 255, 256, 257, 600]])
+def test_fp32_edge_lengths(H, lens):
+    """Empty cache, page boundaries, chunk boundaries (256) and a multi-chunk request."""
+    H.say(f"fp32 edge lengths {lens}")
+    work = wl.make_workload("cfg1", batch=len(lens), seed=77)
+    rng = np.random.default_rng(5)
+    work.seq_lens = np.array(lens, np.int32)
+    work.page_tables, work.n_pages = wl.deal_page_tables(work.seq_lens, rng)
+    case = H.GpuCase(work)
+    _full_step_parity(H, case)
+
+
+def test_fp32_single_request_and_no_logits_output(H):
+    H.say("fp32 batch 1, logits_out NULL")
+    work = wl.make_workload("cfg1", batch=1, n_models=1, seed=78)
+    case = H.GpuCase(work)
+    ref = H.run_oracle(case, [0])
+    fn = sun.sun_decode_step
+    fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, None, case.next, case.ws)
+    torch.cuda.synchronize()
+    assert int(case.next.cpu()[0]) == int(ref["next"][0])
+
+
+def test_fp32_qsun_tiny(H):
+    """QSUN with fp32 activations: tight check of the dequantised projections (1e-4)."""
+    for mode in ("asym", "sym"):
+        H.say(f"fp32 QSUN tiny_q {mode}")
+        work = wl.make_workload("cfg1", shape=wl.TINY_Q, seed=79)
+        case = H.GpuCase(work, quant_mode=mode)
+        _full_step_parity(H, case)
+
+
+# ------------------------------------------------------------------ kernel-level parity
+def test_quantiser_matches_oracle_bit_for_bit(H):
+    from oracle import oracle as orc
+    g = torch.Generator(device=H.DEV).manual_seed(3)
+    for dtype in (torch.float32, torch.bfloat16):
+        w = (torch.randn((96, 1024), generator=g, device=H.DEV) * 0.02).to(dtype)
+        w[0, :128] = 0          # an all-zero group
+        w[1, :128] = 0.5        # a constant group
+        for mode in ("asym", "sym"):
+            H.say(f"quantiser {dtype} {mode}")
+            q, s, z = sun.sun_quantize_w4(w, 128, mode)
+            torch.cuda.synchronize()
+            qo, so, zo = orc.quantize_w4(w.float().cpu().numpy(), 128, mode)
+            assert int((H.to_np(q) != qo).sum()) == 0
+            assert int((H.to_np(s) != so).sum()) == 0
+            assert int((H.to_np(z) != zo).sum()) == 0
+
+
+@pytest.mark.parametrize("shape,dtype", [(wl.TINY, "f32"), (wl.SMALL128, "bf16"), (wl.TINY_Q, "bf16")])
+def test_paged_attention_op(H, shape, dtype):
+    """Attention sub-step alone against the oracle's paged attention (ragged lengths, shuffled tables)."""
+    from oracle import oracle as orc
+    lens = [1, 2, 16, 17, 33, 255, 256, 257, 511, 513, 1000, 31]
+    H.say(f"paged attention {shape.name} {dtype}")
+    work = wl.make_workload("cfg1", shape=shape, dtype=dtype, batch=len(lens), seed=80)
+    rng = np.random.default_rng(6)
+    work.seq_lens = np.array(lens, np.int32) - 1
+    work.page_tables, work.n_pages = wl.deal_page_tables(work.seq_lens, rng)
+    case = H.GpuCase(work)
+    B, QD = len(lens), shape.n_q_heads * shape.head_dim
+    q = torch.randn((B, QD), device=H.DEV, generator=torch.Generator(device=H.DEV).manual_seed(4)) * 2.0
+    n = torch.tensor(lens, dtype=torch.int32, device=H.DEV)
+    out = torch.empty_like(q)
+    layer = shape.n_layers - 1
+    for host in (np.array(lens, np.int32), None):
+        out.zero_()
+        sun.sun_paged_attention(case.pool, layer, q, case.tables, n, out, case.ws, n_tokens_host=host)
+        torch.cuda.synchronize()
+        host_pool, pool, tabs, used = case.extract_pool(range(B))
+        ocfg = orc.make_cfg(shape)
+        worst = 0.0
+        for i in range(B):
+            a, rs = orc.attention_paged(ocfg, pool, layer, tabs[i], q[i].double().cpu().numpy(), lens[i])
+            assert abs(rs - 1).max() < 1e-12
+            worst = max(worst, float(np.abs(out[i].double().cpu().numpy() - a).max()))
+        H.say(f"   max abs diff {worst:.3e} (host lengths {'given' if host is not None else 'absent'})")
+        assert worst < (2e-5 if dtype == "f32" else 2e-4)
+
+
+@pytest.mark.parametrize("batch", [1, 8, 33, 64, 100, 200, 256])
+def test_linear_op_bf16(H, batch):
+    """Every projection of the step (stacked QKV, O, fused SwiGLU, down, lm_head) alone."""
+    from oracle import oracle as orc
+    shape = wl.SMALL128
+    H.say(f"linear bf16 batch {batch}")
+    cfg = sun.make_cfg(shape, "bf16")
+    w = wl.make_weights(shape, "bf16", H.DEV, 11, std=0.05)
+    W = sun.sun_weights_create(cfg, w)
+    ws = torch.empty(sun.sun_workspace_bytes(cfg, batch, 4), dtype=torch.uint8, device=H.DEV)
+    g = torch.Generator(device=H.DEV).manual_seed(batch)
+    wn = H.weights_to_np(w)
+    for mat, K, N in ((0, 512, 1536), (1, 1024, 512), (2, 512, 1024), (3, 1024, 512), (4, 512, 2048)):
+        x = torch.randn((batch, K), device=H.DEV, generator=g)
+        out = torch.full((batch, N), float("nan"), device=H.DEV)
+        sun.sun_linear(W, 1, mat, x, out, ws)
+        torch.cuda.synchronize()
+        xr = x.to(torch.bfloat16).double().cpu().numpy()       # the kernel rounds its input to bf16
+        lin = lambda key: orc.linear(orc.dense_mat(wn[key][1] if isinstance(wn[key], list) else wn[key]), xr)
+        if mat == 0:
+            want = np.concatenate([lin("wq"), lin("wk"), lin("wv")], axis=1)
+        elif mat == 2:
+            gate, up = lin("wg"), lin("wu")
+            want = gate / (1 + np.exp(-gate)) * up
+        else:
+            want = lin({1: "wo", 3: "wd", 4: "wlm"}[mat])
+        got = out.double().cpu().numpy()
+        tol = 1e-2 * np.abs(want) + 2e-3 if mat == 2 else 2e-4 + 1e-5 * np.abs(want)   # mat 2 output is bf16
+        assert np.all(np.abs(got - want) <= tol), f"mat {mat}: max diff {np.abs(got - want).max():.3e}"
+
+
+@pytest.mark.parametrize("batch", [8, 64, 130, 256])
+def test_linear_op_w4(H, batch):
+    from oracle import oracle as orc
+    shape = wl.SMALL128
+    H.say(f"linear W4 batch {batch}")
+    cfg = sun.make_cfg(shape, "bf16")
+    w = wl.make_weights(shape, "bf16", H.DEV, 12, std=0.05)
+    quant = {k: [sun.sun_quantize_w4(m, 128, "asym") for m in w[k]] for k in sun.QUANT_KEYS}
+    W = sun.sun_qweights_create(cfg, w, quant)
+    ws = torch.empty(sun.sun_workspace_bytes(cfg, batch, 4), dtype=torch.uint8, device=H.DEV)
+    g = torch.Generator(device=H.DEV).manual_seed(100 + batch)
+
+    def qlin(key, xr):
+        q, s, z = (H.to_np(t) for t in quant[key][0])
+        return orc.linear(orc.w4_mat(q, s, z, w[key][0].shape[1], 128), xr)
+
+    for mat, K, N in ((0, 512, 1536), (1, 1024, 512), (2, 512, 1024), (3, 1024, 512)):
+        x = torch.randn((batch, K), device=H.DEV, generator=g)
+        out = torch.full((batch, N), float("nan"), device=H.DEV)
+        sun.sun_linear(W, 0, mat, x, out, ws)
+        torch.cuda.synchronize()
+        xr = x.to(torch.bfloat16).double().cpu().numpy()
+        if mat == 0:
+            want = np.concatenate([qlin("wq", xr), qlin("wk", xr), qlin("wv", xr)], axis=1)
+        elif mat == 2:
+            gate, up = qlin("wg", xr), qlin("wu", xr)
+            want = gate / (1 + np.exp(-gate)) * up
+        else:
+            want = qlin({1: "wo", 3: "wd"}[mat], xr)
+        got = out.double().cpu().numpy()
+        tol = 1e-2 * np.abs(want) + 2e-3 if mat == 2 else 1e-3 + 1e-4 * np.abs(want)
+        assert np.all(np.abs(got - want) <= tol), f"mat {mat}: max diff {np.abs(got - want).max():.3e}"
+
+
+# ------------------------------------------------------------------ bf16 and QSUN full steps, small shapes
+@pytest.mark.parametrize("batch", [8, 48, 100])
+def test_bf16_small_full_step(H, batch):
+    H.say(f"bf16 small128 batch {batch}")
+    work = wl.make_workload("cfg2", shape=wl.SMALL128, batch=batch, lo=1, hi=700, seed=81 + batch)
+    case = H.GpuCase(work)
+    _full_step_parity(H, case)
+
+
+@pytest.mark.parametrize("mode", ["asym", "sym"])
+def test_qsun_small_full_step(H, mode):
+    H.say(f"QSUN small128 {mode}")
+    work = wl.make_workload("cfg2", shape=wl.SMALL128, batch=40, lo=1, hi=700, seed=91)
+    case = H.GpuCase(work, quant_mode=mode)
+    _full_step_parity(H, case)
+
+
+def test_bf16_head_dim_64(H):
+    H.say("bf16 tiny_q (head_dim 64, G=2)")
+    work = wl.make_workload("cfg1", shape=wl.TINY_Q, dtype="bf16", batch=12, lo=1, hi=400, seed=92)
+    case = H.GpuCase(work)
+    _full_step_parity(H, case)
+
+
+# ------------------------------------------------------------------ the SUN property on the GPU
+@pytest.mark.parametrize("dtype,shape", [("f32", wl.TINY), ("bf16", wl.SMALL128)])
+def test_batch_mix_invariance_is_bitwise(H, dtype, shape):
+    """Relabelling model ids, and replacing every *other* request of the batch, must leave a
+    request's logits bit-identical (same batch size and row index)."""
+    H.say(f"batch-mix invariance {dtype}")
+    work = wl.make_workload("cfg1", shape=shape, dtype=dtype, batch=8, lo=1, hi=600, seed=93)
+    case = H.GpuCase(work)
+    pool0 = case.pool_mem.clone()
+    case.step()
+    base = case.logits.clone()
+    base_next = case.next.clone()
+    # (a) relabel the source models
+    case.pool_mem.copy_(pool0)
+    ids2 = ((case.ids + 1) % work.n_models).contiguous()
+    case.step(ids=ids2)
+    assert torch.equal(case.logits, base) and torch.equal(case.next, base_next)
+    # (b) keep request 3, swap tokens / lengths / tables of all the others for different ones
+    keep = 3
+    rng = np.random.default_rng(9)
+    lens2 = work.seq_lens.copy()
+    toks2 = work.tokens.copy()
+    for i in range(work.batch):
+        if i != keep:
+            lens2[i] = rng.integers(0, int(work.seq_lens[i]) + 1)     # shorter prefixes of their own pages
+            toks2[i] = rng.integers(0, shape.vocab)
+    case.pool_mem.copy_(pool0)
+    case.step(tokens=torch.from_numpy(toks2).to(H.DEV), lens=torch.from_numpy(lens2).to(H.DEV))
+    assert torch.equal(case.logits[keep], base[keep]) and case.next[keep] == base_next[keep]
+    assert not torch.equal(case.logits[0], base[0])
+    # (c) the same step twice gives the same bits (no atomics, fixed reduction order)
+    case.pool_mem.copy_(pool0)
+    case.step(host_lens=False)
+    assert torch.equal(case.logits, base)
+
+
+def test_validation_errors(H):
+    H.say("SUN_VALIDATE error paths")
+    work = wl.make_workload("cfg1", seed=94)
+    case = H.GpuCase(work)
+    bad = case.tables.clone()
+    bad[2, 0] = work.n_pages
+    with pytest.raises(sun.SunError) as e:
+        case.step(flags=sun.SUN_VALIDATE, tables=bad)
+    assert e.value.status == 5
+    dup = case.tables.clone()
+    need = wl.pages_needed(work.seq_lens)
+    dup[1, need[1] - 1] = dup[0, need[0] - 1]
+    with pytest.raises(sun.SunError) as e:
+        case.step(flags=sun.SUN_VALIDATE, tables=dup)
+    assert e.value.status == 5
+    with pytest.raises(sun.SunError) as e:
+        case.step(flags=sun.SUN_VALIDATE, lens=torch.full_like(case.lens, work.max_pages * 16))
+    assert e.value.status == 6
+    with pytest.raises(sun.SunError) as e:
+        case.step(flags=sun.SUN_VALIDATE, ids=torch.full_like(case.ids, work.n_models))
+    assert e.value.status == 7
+    with pytest.raises(sun.SunError) as e:
+        case.step(flags=sun.SUN_VALIDATE, tokens=torch.full_like(case.tokens, -1))
+    assert e.value.status == 9
+    case.step(flags=sun.SUN_VALIDATE)   # and the good call still works afterwards

@@ -141,3 +141,11 @@ def test_qsun_step_equals_dense_step_on_dequantised_weights(orc):
     r_f = orc.decode_step(cfg, orc.params_from_arrays(w), orc.make_pool(b3, n_pages, 16, orc.default_strides(shape, n_pages)), toks, tables, lens, ids)
     gap = np.abs(r_f["logits"] - r_q["logits"]).max()
     assert 0 < gap < 1.0
+
+
+def test_zero_point_is_a_plain_integer_code(orc):
+    """Z holds an integer in [0,15]; a group whose minimum is 0 stores +0 (bit pattern 0), not -0."""
+    W = np.zeros((2, 128), dtype=np.float32)
+    W[1, :] = np.linspace(0, 1, 128)
+    q, s, z = orc.quantize_w4(W, 128, "asym")
+    assert z[0, 0] == 0 and z[1, 0] == 0
