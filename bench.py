@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-decode step on one MI355X.
+
+A "step" is one full decode step (all layers, lm_head, argmax) over one synthetic mixed-model
+batch whose weights, KV pool, page tables and lengths are resident in HBM before timing starts.
+Prints ONE JSON line: tokens/s (= batch / step time), TPOT (= step time), the roofline of the
+dominant kernel (paged attention, HBM bound) measured with HIP events inside this run, and the
+CPU oracle timed on a bounded sample of the same workload on this machine's host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5b] [--quant asym|sym]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(shape, work, quant: bool, logits_out: bool = True):
+    """Bytes the method must move per step: weights once, lm_head (bf16), embedding rows,
+    KV read for every cached position incl. the new one, KV write, fp32 logits."""
+    b_w = 0.53125 if quant else 2.0
+    weights = shape.body_params * b_w + shape.vocab * shape.hidden * 2
+    kv_tok = shape.kv_bytes_per_token()
+    kv_read = float(work.kv_tokens_read) * kv_tok
+    kv_write = work.batch * kv_tok
+    other = work.batch * shape.hidden * 2 + (work.batch * shape.vocab * 4 if logits_out else 0)
+    return {"weights": weights, "kv_read": kv_read, "kv_write": kv_write, "other": other,
+            "total": weights + kv_read + kv_write + other}
+
+
+def build_workload(name: str):
+    from paper_2603_02599_amd import workloads as wl
+    if name == "cfg2":
+        return wl.make_workload("cfg2"), "8B-shaped shared decode, batch 64 over 4 source models, L~U[512,4096]"
+    if name == "cfg3":
+        return wl.make_workload("cfg3"), "8B-shaped shared decode, batch 256 over 8 Zipf(1.2) source models, log-normal L (median 1024, clip [64,16384])"
+    if name == "cfg5b":
+        # 14B shape; requests admitted in draw order until ~200 GB of KV pool is full (no aliasing)
+        full = wl.make_workload("cfg5")
+        kv_tok = full.shape.kv_bytes_per_token()
+        keep, tot = 0, 0
+        for L in full.seq_lens:
+            pages = (int(L) + 16) // 16
+            if (tot + pages) * 16 * kv_tok > 200e9:
+                break
+            tot += pages
+            keep += 1
+        w = wl.make_workload("cfg5", batch=keep)
+        return w, f"14B-shaped shared decode, first {keep} of 128 Zipf(1.2) requests fitting a 200 GB pool, L~U[2048,32768]"
+    if name == "small":
+        return (wl.make_workload("cfg2", shape=wl.SMALL128, batch=64, lo=64, hi=512, seed=7),
+                "small128 test shape, batch 64 (not a benchmark configuration)")
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(case, work, n_sample: int):
+    """Times the oracle (as it stands) on n_sample requests spread over the length distribution."""
+    tests = os.path.join(ROOT, "tests")
+    if tests not in sys.path:
+        sys.path.insert(0, tests)
+    import gpu_harness as H
+    from oracle import oracle as orc
+    order = np.argsort(work.seq_lens)
+    rows = sorted({int(order[int(round(q * (work.batch - 1)))]) for q in np.linspace(0, 1, n_sample)})
+    params = case.oracle_params()
+    host, pool, tabs, used = case.extract_pool(rows)
+    ocfg = orc.make_cfg(work.shape)
+    t0 = time.perf_counter()
+    orc.decode_step(ocfg, params, pool, work.tokens[rows], tabs, work.seq_lens[rows], work.model_ids[rows])
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "tokens/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"{len(rows)} of {work.batch} requests of the same batch (lengths "
+                      f"{[int(work.seq_lens[r]) for r in rows]}), all {work.shape.n_layers} layers + lm_head, "
+                      f"one oracle step took {dt:.1f} s; gcc -O2 -fopenmp, fp64"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--quant", default=None, choices=[None, "asym", "sym"])
+    ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build measures one GPU only (one decode worker holds a full copy of the "
+                         "shared decode weights; more GPUs are more independent workers). Run with --gpus 1.")
+    import torch
+    tests = os.path.join(ROOT, "tests")
+    if tests not in sys.path:
+        sys.path.insert(0, tests)
+    from paper_2603_02599_amd import binding as sun
+    sun.lib()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    import gpu_harness as H   # plumbing only (device buffers, handles); the oracle is used in cpu_baseline alone
+
+    work, desc = build_workload(args.workload)
+    shape = work.shape
+    t_setup = time.perf_counter()
+    case = H.GpuCase(work, quant_mode=args.quant)
+    if args.quant:  # the dense projection sources are no longer needed on the device
+        for k in sun.QUANT_KEYS:
+            case.w[k] = None
+    torch.cuda.synchronize()
+    print(f"[bench] setup {time.perf_counter() - t_setup:.1f} s; pool {work.n_pages} pages, "
+          f"{work.kv_tokens_read} KV tokens read per layer-step", file=sys.stderr, flush=True)
+    host_lens = work.seq_lens.copy()
+    fn = sun.sun_qdecode_step if args.quant else sun.sun_decode_step
+
+    def one_step(flags=0):
+        # seq_lens is held fixed so every step overwrites the same slot and moves identical bytes
+        fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, case.logits, case.next, case.ws,
+           seq_lens_host=host_lens, flags=flags)
+
+    graph = None
+    if args.graph:
+        one_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_step()
+        run = graph.replay
+    else:
+        run = one_step
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        run()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_step = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)])
+    ms_per_step = wall * 1e3 / args.steps
+
+    alg = algorithmic_bytes(shape, work, bool(args.quant))
+    roof = None
+    kernels = {}
+    if not args.no_profile:
+        sun.sun_profile_reset()
+        for _ in range(args.steps):
+            one_step(flags=sun.SUN_PROFILE)
+        torch.cuda.synchronize()
+        prof = sun.sun_profile_read()
+        sun.sun_profile_reset()
+        for k, v in prof.items():
+            if v["launches"]:
+                kernels[k] = {"avg_us": 1e3 * v["ms"] / v["launches"], "launches_per_step": v["launches"] // args.steps,
+                              "ms_per_step": v["ms"] / args.steps}
+        att = prof["attn_split"]
+        # one launch = one layer: K and V of every cached position of every request, once
+        per_launch = float(work.kv_tokens_read) * 2 * shape.n_kv_heads * shape.head_dim * 2
+        avg_s = att["ms"] / att["launches"] * 1e-3
+        roof = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": per_launch / avg_s / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
+                "traffic": None, "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
+        w_bytes = {"qkv_proj": 0, "o_proj": 1, "gate_up_proj": 2, "down_proj": 3}
+        b_w = 0.53125 if args.quant else 2.0
+        H_, QD, KD, F = shape.hidden, shape.q_dim, shape.kv_dim, shape.ffn
+        sizes = {"qkv_proj": (QD + 2 * KD) * H_ * b_w, "o_proj": H_ * QD * b_w, "gate_up_proj": 2 * F * H_ * b_w,
+                 "down_proj": H_ * F * b_w, "lm_head": shape.vocab * H_ * 2.0}
+        for k, nbytes in sizes.items():
+            if k in kernels:
+                kernels[k]["weight_GBps"] = nbytes / (kernels[k]["avg_us"] * 1e-6) / 1e9
+
+    cpu = None
+    if args.cpu_sample > 0:
+        cpu = cpu_baseline(case, work, args.cpu_sample)
+
+    out = {
+        "metric": "shared-decode tokens/sec",
+        "value": work.batch / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "tpot_ms": ms_per_step,
+        "step_ms_p10_p50_p90": [float(np.percentile(per_step, p)) for p in (10, 50, 90)],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if not args.quant else "bf16 activations, 4-bit group-128 weights",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "shape": shape.name, "batch": work.batch,
+                   "quant": args.quant, "kv_tokens": work.kv_tokens_read, "graph": bool(args.graph)},
+        "algorithmic_GB_per_step": alg["total"] / 1e9,
+        "step_GBps": alg["total"] / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": alg["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": roof,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
