@@ -124,6 +124,7 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
     w.plan.chunk_off = (int32_t*)take((size_t)(batch + 1) * 4);
     w.plan.item_req = (int32_t*)take(mc * 4);
     w.plan.item_chunk = (int32_t*)take(mc * 4);
+    w.plan.records = (int32_t*)take(mc * c.n_kv_heads * 24 * 4);
     w.plan.partial = (float*)take(mc * c.n_q_heads * (c.head_dim + 2) * 4);
     w.logits = (float*)take((size_t)batch * c.vocab * 4);
     w.bytes = off;
@@ -548,7 +549,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
         ProfScope p(prof, 7, st);
         SUN_HIP_CHECK(launch_embed(c, W.embed, token_ids, batch, ws.x, st));
         SUN_HIP_CHECK(launch_rope_table(c, seq_lens, batch, ws.table, st));
-        SUN_HIP_CHECK(launch_attn_plan(ws.plan, seq_lens, 1, batch, max_pages, st));
+        SUN_HIP_CHECK(launch_attn_plan(ws.plan, seq_lens, 1, batch, page_tables, max_pages, (int)pool.lay.n_pages, c.n_kv_heads, st));
     }
     int down_parts = 0;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -677,7 +678,7 @@ int sun_paged_attention(sun_kv_pool* pool_, int layer, int batch, const float* q
     if (ws.bytes > workspace_bytes) return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, ws.bytes);
     hipStream_t st = (hipStream_t)stream;
     const int hint = total_chunks_from_host(n_tokens_host, 0, batch);
-    SUN_HIP_CHECK(launch_attn_plan(ws.plan, n_tokens, 0, batch, max_pages, st));
+    SUN_HIP_CHECK(launch_attn_plan(ws.plan, n_tokens, 0, batch, page_tables, max_pages, (int)pool.lay.n_pages, c.n_kv_heads, st));
     SUN_HIP_CHECK(launch_attn_split(pool, layer, ws.plan, q, page_tables, max_pages, n_tokens, 0, batch, hint,
                                     c.act_dtype == SUN_F32, st));
     SUN_HIP_CHECK(launch_attn_combine(c, ws.plan, batch, out, nullptr, nullptr, st));

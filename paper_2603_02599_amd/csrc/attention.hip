@@ -25,6 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CH = kAttnChunk;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kRecInts = 24;  // ints per item record
 
 size_t attn_max_chunks(int batch, int max_pages) {
     const size_t per_req = ((size_t)max_pages * kPageTokens + CH - 1) / CH;
@@ -64,11 +65,44 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t* __restri
     }
 }
 
-hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch, int max_pages,
-                            hipStream_t st) {
+// One record per item, ordered (request, kv head, chunk): the 16 page ids of the chunk
+// (clamped into the pool, -1 where the chunk has no page), then request, kv head, first
+// and one-past-last token, and the chunk's index in the partial array.
+__global__ __launch_bounds__(256) void attn_records_kernel(const int32_t* __restrict__ n_or_len, int len_plus, int batch,
+                                                           const int32_t* __restrict__ chunk_off,
+                                                           const int32_t* __restrict__ page_tables, int max_pages,
+                                                           int n_pages, int Hkv, int32_t* __restrict__ records) {
+    const int total = chunk_off[batch] * Hkv;
+    for (int item = blockIdx.x * 16 + (threadIdx.x >> 4); item < total; item += gridDim.x * 16) {
+        const int slot = threadIdx.x & 15;
+        int lo = 0, hi = batch;  // request whose item range [chunk_off[r]*Hkv, chunk_off[r+1]*Hkv) holds item
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (chunk_off[mid] * Hkv <= item) lo = mid; else hi = mid;
+        }
+        const int req = lo, nc = chunk_off[req + 1] - chunk_off[req];
+        const int local = item - chunk_off[req] * Hkv, head = local / nc, cj = local % nc;
+        const int n = min(max(n_or_len[req] + len_plus, 1), max_pages * kPageTokens);
+        const int t0 = cj * CH, t1 = min(n, t0 + CH);
+        const int npages = (t1 - t0 + kPageTokens - 1) / kPageTokens;
+        int32_t* rec = records + (size_t)item * kRecInts;
+        rec[slot] = slot < npages ? min(max(page_tables[(size_t)req * max_pages + t0 / kPageTokens + slot], 0), n_pages - 1) : -1;
+        if (slot < 8) {
+            const int vals[8] = {req, head, t0, t1, chunk_off[req] + cj, 0, 0, 0};
+            rec[16 + slot] = vals[slot];
+        }
+    }
+}
+
+hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch,
+                            const int32_t* page_tables, int max_pages, int n_pages, int Hkv, hipStream_t st) {
     if (batch > 1024) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_or_len, len_plus, batch, plan.chunk_off,
                        plan.item_req, plan.item_chunk, plan.max_chunks, max_pages * kPageTokens);
+    const long long items = (long long)plan.max_chunks * Hkv;
+    const int grid = (int)max(1LL, min((items + 15) / 16, 1024LL));
+    hipLaunchKernelGGL(attn_records_kernel, dim3(grid), dim3(256), 0, st, n_or_len, len_plus, batch, plan.chunk_off,
+                       page_tables, max_pages, n_pages, Hkv, plan.records);
     return hipGetLastError();
 }
 
@@ -82,6 +116,7 @@ struct AttnArgs {
     const int32_t* chunk_off;
     const int32_t* item_req;
     const int32_t* item_chunk;
+    const int32_t* records;
     float* partial;
     int len_plus, max_pages, batch, Hq, Hkv, n_pages;
     float qscale;           // log2(e) / sqrt(D)
@@ -101,156 +136,194 @@ template <int D, int G>
 __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
     constexpr int NS = D / 32;  // dim slices of a QK MFMA
     constexpr int NB = D / 16;  // dim blocks of a PV MFMA
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
     const int c16 = lane & 15, kq = lane >> 4;
-    const int total_items = a.chunk_off[a.batch] * a.Hkv;
+    // every wave owns a contiguous range of items; items are ordered (request, kv head, chunk),
+    // so consecutive items mostly share q, and the record of the next item is prefetched
+    const long long total_items = (long long)a.chunk_off[a.batch] * a.Hkv;
+    const long long wid = (long long)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (long long)gridDim.x * 4;
+    int item = (int)(wid * total_items / nw);
+    const int item_end = (int)((wid + 1) * total_items / nw);
+    if (item >= item_end) return;
 
-    for (int item = blockIdx.x * 4 + wave; item < total_items; item += gridDim.x * 4) {
-        const int chunk_idx = item / a.Hkv, head = item % a.Hkv;
-        const int req = __builtin_amdgcn_readfirstlane(a.item_req[chunk_idx]);
-        const int cj = __builtin_amdgcn_readfirstlane(a.item_chunk[chunk_idx]);
-        const int n = __builtin_amdgcn_readfirstlane(min(max(a.n_or_len[req] + a.len_plus, 1), a.max_pages * kPageTokens));
-        const int t0 = cj * CH, t1 = min(n, t0 + CH);
-        const int npages = (t1 - t0 + kPageTokens - 1) / kPageTokens;
-        const int npairs = (npages + 1) / 2;
+    // K operand rows: MFMA row i of tile 0 <-> page (i>>3), token 8*((i>>2)&1) + (i&3); tile 1: +4
+    const int k_psel = c16 >> 3, k_tok = 8 * ((c16 >> 2) & 1) + (c16 & 3);
+    const int64_t k_lane_off = (int64_t)k_tok * D + kq * 8;
+    // V^T operand: lane (dim c16 of a 16-dim block, token octet kq): page (kq>>1), tokens 8*(kq&1)..+7
+    const int v_psel = kq >> 1;
+    const int64_t v_lane_off = (int64_t)c16 * kPageTokens + 8 * (kq & 1);
 
-        // page ids of this chunk, one per lane
-        int ptv = -1;
-        if (lane < npages)  // ids are validated on the host under SUN_VALIDATE; clamp so a bad table cannot fault
-            ptv = min(max(a.page_tables[(size_t)req * a.max_pages + t0 / kPageTokens + lane], 0), a.n_pages - 1);
-
-        // q as MFMA B operand: lane (head g = c16, dim octet kq) per 32-dim slice, hi + lo bf16
-        bf16x8 qhi[NS], qlo[NS];
-        {
-            const float* qp = a.q + ((size_t)req * a.Hq + head * G + (c16 < G ? c16 : 0)) * D;
+    auto load_rec = [&](int it) { return lane < kRecInts ? a.records[(size_t)it * kRecInts + lane] : 0; };
+    u32x4 kr[2][NS], vr[NB];  // K and V^T operand registers of one 32-token page pair
+    auto load_k = [&](int recv, int head, int pp) {
+        const int pA = __builtin_amdgcn_readlane(recv, 2 * pp);
+        int pB = __builtin_amdgcn_readlane(recv, 2 * pp + 1);
+        if (pB < 0) pB = pA;
+        const uint16_t* kp = a.kbase + head * a.k_head + (int64_t)(k_psel ? pB : pA) * a.k_page + k_lane_off;
+#ifdef SUN_EXP_KCONTIG
+        const uint16_t* ka_ = a.kbase + head * a.k_head + (int64_t)pA * a.k_page + lane * 8;
+        const uint16_t* kb_ = a.kbase + head * a.k_head + (int64_t)pB * a.k_page + lane * 8;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                u32x4 h, l;
-                const f32x4 v0 = *reinterpret_cast<const f32x4*>(qp + s * 32 + kq * 8);
-                const f32x4 v1 = *reinterpret_cast<const f32x4*>(qp + s * 32 + kq * 8 + 4);
-                float x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const float xa = c16 < G ? x[2 * p] * a.qscale : 0.f;
-                    const float xb = c16 < G ? x[2 * p + 1] * a.qscale : 0.f;
-                    float ra, rb;
-                    h[p] = bf16_pair_hi(xa, xb, ra, rb);
-                    l[p] = pack_bf16(ra, rb);
-                }
-                qhi[s] = __builtin_bit_cast(bf16x8, h);
-                qlo[s] = __builtin_bit_cast(bf16x8, l);
-            }
+        for (int s = 0; s < NS; ++s) {
+            kr[0][s] = *reinterpret_cast<const u32x4*>(ka_ + s * 512);
+            kr[1][s] = *reinterpret_cast<const u32x4*>(kb_ + s * 512);
         }
+        (void)kp;
+#else
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            kr[0][s] = *reinterpret_cast<const u32x4*>(kp + s * 32);
+            kr[1][s] = *reinterpret_cast<const u32x4*>(kp + 4 * D + s * 32);
+        }
+#endif
+    };
+    auto load_v = [&](int recv, int head, int pp) {
+        const int pA = __builtin_amdgcn_readlane(recv, 2 * pp);
+        int pB = __builtin_amdgcn_readlane(recv, 2 * pp + 1);
+        if (pB < 0) pB = pA;
+        const uint16_t* vp = a.vbase + head * a.v_head + (int64_t)(v_psel ? pB : pA) * a.v_page + v_lane_off;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) vr[b] = *reinterpret_cast<const u32x4*>(vp + b * 16 * kPageTokens);
+    };
 
-        const uint16_t* kb = a.kbase + head * a.k_head;
-        const uint16_t* vb = a.vbase + head * a.v_head;
-        // K operand rows: MFMA row i of tile 0 <-> page (i>>3), token 8*((i>>2)&1) + (i&3); tile 1: +4
-        const int k_psel = c16 >> 3, k_tok = 8 * ((c16 >> 2) & 1) + (c16 & 3);
-        const int64_t k_lane_off = (int64_t)k_tok * D + kq * 8;
-        // V^T operand: lane (dim c16 of a 16-dim block, token octet kq): page (kq>>1), tokens 8*(kq&1)..+7
-        const int v_psel = kq >> 1;
-        const int64_t v_lane_off = (int64_t)c16 * kPageTokens + 8 * (kq & 1);
-
-        u32x4 kc[2][NS], kn[2][NS], vc[NB], vn[NB];
-        auto load_pair = [&](int pp, u32x4(&k)[2][NS], u32x4(&v)[NB]) {
-            const int pA = __builtin_amdgcn_readlane(ptv, 2 * pp);
-            int pB = __builtin_amdgcn_readlane(ptv, 2 * pp + 1);
-            if (pB < 0) pB = pA;
-            const uint16_t* kp = kb + (int64_t)(k_psel ? pB : pA) * a.k_page + k_lane_off;
-            const uint16_t* vp = vb + (int64_t)(v_psel ? pB : pA) * a.v_page + v_lane_off;
+    bf16x8 qhi[NS], qlo[NS];
+    // q as MFMA B operand: lane (head g = c16, dim octet kq) per 32-dim slice, hi + lo bf16
+    auto load_q = [&](int req, int head) {
+        const float* qp = a.q + ((size_t)req * a.Hq + head * G + (c16 < G ? c16 : 0)) * D;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                k[0][s] = *reinterpret_cast<const u32x4*>(kp + s * 32);
-                k[1][s] = *reinterpret_cast<const u32x4*>(kp + 4 * D + s * 32);
-            }
+        for (int s = 0; s < NS; ++s) {
+            u32x4 h, l;
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(qp + s * 32 + kq * 8);
+            const f32x4 v1 = *reinterpret_cast<const f32x4*>(qp + s * 32 + kq * 8 + 4);
+            float x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
 #pragma unroll
-            for (int b = 0; b < NB; ++b) v[b] = *reinterpret_cast<const u32x4*>(vp + b * 16 * kPageTokens);
-        };
-
-        f32x4 O[NB];
-#pragma unroll
-        for (int b = 0; b < NB; ++b) O[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-        float m_run = -INFINITY, l_run = 0.f;
-
-        auto process = [&](int pp, u32x4(&k)[2][NS], u32x4(&v)[NB]) {
-            f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const bf16x8 kx = __builtin_bit_cast(bf16x8, k[0][s]), ky = __builtin_bit_cast(bf16x8, k[1][s]);
-                sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qhi[s], sx, 0, 0, 0);
-                sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ky, qhi[s], sy, 0, 0, 0);
-                sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qlo[s], sx, 0, 0, 0);
-                sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ky, qlo[s], sy, 0, 0, 0);
-            }
-            // this lane: head c16, tokens tb + r (tile X) and tb + 4 + r (tile Y)
-            const int tb = t0 + pp * 32 + (kq >> 1) * 16 + 8 * (kq & 1);
-            float mloc = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                sx[r] = (tb + r < t1) ? sx[r] : -INFINITY;
-                sy[r] = (tb + 4 + r < t1) ? sy[r] : -INFINITY;
-                mloc = fmaxf(mloc, fmaxf(sx[r], sy[r]));
-            }
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            const float m_new = fmaxf(m_run, mloc);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            float p[8], psum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                p[r] = __builtin_amdgcn_exp2f(sx[r] - m_new);
-                p[4 + r] = __builtin_amdgcn_exp2f(sy[r] - m_new);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) psum += p[e];
-            l_run = l_run * alpha + psum;
-            u32x4 ph, pl;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int p = 0; p < 4; ++p) {
+                const float xa = c16 < G ? x[2 * p] * a.qscale : 0.f;
+                const float xb = c16 < G ? x[2 * p + 1] * a.qscale : 0.f;
                 float ra, rb;
-                ph[e] = bf16_pair_hi(p[2 * e], p[2 * e + 1], ra, rb);
-                pl[e] = pack_bf16(ra, rb);
+                h[p] = bf16_pair_hi(xa, xb, ra, rb);
+                l[p] = pack_bf16(ra, rb);
             }
-            const bf16x8 phi = __builtin_bit_cast(bf16x8, ph), plo = __builtin_bit_cast(bf16x8, pl);
-            // rescale O: row (head) 4*kq + r of the output tile needs alpha of lane (head)
+            qhi[s] = __builtin_bit_cast(bf16x8, h);
+            qlo[s] = __builtin_bit_cast(bf16x8, l);
+        }
+    };
+
+    // current item state (wave-uniform scalars) and accumulators
+    int rec = load_rec(item);
+    int req = __builtin_amdgcn_readlane(rec, 16), head = __builtin_amdgcn_readlane(rec, 17);
+    int t0 = __builtin_amdgcn_readlane(rec, 18), t1 = __builtin_amdgcn_readlane(rec, 19);
+    int cidx = __builtin_amdgcn_readlane(rec, 20);
+    int npairs = ((t1 - t0 + kPageTokens - 1) / kPageTokens + 1) / 2, pp = 0;
+    load_k(rec, head, 0);
+    load_v(rec, head, 0);
+    int rec_n = load_rec(item + 1 < item_end ? item + 1 : item);
+    load_q(req, head);
+    int head_n = __builtin_amdgcn_readlane(rec_n, 17);
+
+    f32x4 O[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) O[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // bf16 hi/lo split of two fp32 values with the hardware converter (round to nearest even)
+    auto split2 = [&](float x0, float x1, uint32_t& hi, uint32_t& lo) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float fl2 __attribute__((ext_vector_type(2)));
+        const bf2 h = __builtin_convertvector(fl2{x0, x1}, bf2);
+        hi = __builtin_bit_cast(uint32_t, h);
+        const bf2 l = __builtin_convertvector(fl2{x0 - bf16_lo(hi), x1 - bf16_hi(hi)}, bf2);
+        lo = __builtin_bit_cast(uint32_t, l);
+    };
+
+    // One pipeline step = one 32-token page pair.  On entry K of the pair has been requested
+    // earlier and V is still in flight.  K of the following pair (of this item or of the wave's
+    // next item) is requested as soon as the score MFMAs have consumed the K registers, V of the
+    // following pair right after the output MFMAs.  Returns false when the wave's range is done.
+    auto step = [&]() -> bool {
+        f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const bf16x8 kx = __builtin_bit_cast(bf16x8, kr[0][s]), ky = __builtin_bit_cast(bf16x8, kr[1][s]);
+            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qhi[s], sx, 0, 0, 0);
+            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ky, qhi[s], sy, 0, 0, 0);
+            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qlo[s], sx, 0, 0, 0);
+            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ky, qlo[s], sy, 0, 0, 0);
+        }
+        // The following pair is requested unconditionally (branch-free, so that the K and V
+        // requests can stay in flight across each other); past the end of the wave's range it
+        // re-reads a valid pair that is never used.
+        const bool more_pairs = pp + 1 < npairs;
+        const int nrec = more_pairs ? rec : rec_n, nhead = more_pairs ? head : head_n, npp = more_pairs ? pp + 1 : 0;
+        load_k(nrec, nhead, npp);
+
+        // this lane: head c16, tokens tb + r (tile X) and tb + 4 + r (tile Y)
+        const int tb = t0 + pp * 32 + (kq >> 1) * 16 + 8 * (kq & 1);
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            sx[r] = (tb + r < t1) ? sx[r] : -INFINITY;
+            sy[r] = (tb + 4 + r < t1) ? sy[r] : -INFINITY;
+            mloc = fmaxf(mloc, fmaxf(sx[r], sy[r]));
+        }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(sx[r] - m_new);
+            p[4 + r] = __builtin_amdgcn_exp2f(sy[r] - m_new);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) psum += p[e];
+        l_run = l_run * alpha + psum;
+        u32x4 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t hi, lo;
+            split2(p[2 * e], p[2 * e + 1], hi, lo);
+            ph[e] = hi;
+            pl[e] = lo;
+        }
+        const bf16x8 phi = __builtin_bit_cast(bf16x8, ph), plo = __builtin_bit_cast(bf16x8, pl);
+        // rescale O only when some head's running maximum moved (rare after the first pairs);
+        // row (head) 4*kq + r of the output tile needs alpha of lane (head)
+        if (__any(alpha != 1.f)) {
             float al[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) al[r] = __shfl(alpha, 4 * kq + r);
-            // pool slots past the end of the cache may hold anything: zero their V
-            if (t0 + pp * 32 + 32 > t1) {
-                const int vt = t0 + pp * 32 + (kq >> 1) * 16 + 8 * (kq & 1);
-                uint32_t msk[4];
 #pragma unroll
-                for (int w = 0; w < 4; ++w)
-                    msk[w] = (vt + 2 * w < t1 ? 0x0000ffffu : 0u) | (vt + 2 * w + 1 < t1 ? 0xffff0000u : 0u);
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) v[b][w] &= msk[w];
-            }
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) O[b][r] *= al[r];
-                const bf16x8 vt8 = __builtin_bit_cast(bf16x8, v[b]);
-                O[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, vt8, O[b], 0, 0, 0);
-                O[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, vt8, O[b], 0, 0, 0);
-            }
-        };
-
-        load_pair(0, kc, vc);
-        for (int pp = 0; pp < npairs; pp += 2) {
-            if (pp + 1 < npairs) load_pair(pp + 1, kn, vn);
-            process(pp, kc, vc);
-            if (pp + 1 >= npairs) break;
-            if (pp + 2 < npairs) load_pair(pp + 2, kc, vc);
-            process(pp + 1, kn, vn);
         }
+        // pool slots past the end of the cache may hold anything: zero their V
+        if (t0 + pp * 32 + 32 > t1) {
+            const int vt = t0 + pp * 32 + (kq >> 1) * 16 + 8 * (kq & 1);
+            uint32_t msk[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                msk[w] = (vt + 2 * w < t1 ? 0x0000ffffu : 0u) | (vt + 2 * w + 1 < t1 ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) vr[b][w] &= msk[w];
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const bf16x8 vt8 = __builtin_bit_cast(bf16x8, vr[b]);
+            O[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, vt8, O[b], 0, 0, 0);
+            O[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, vt8, O[b], 0, 0, 0);
+        }
+        load_v(nrec, nhead, npp);
+        if (++pp < npairs) return true;
 
         float l_tot = l_run + __shfl_xor(l_run, 16);
         l_tot += __shfl_xor(l_tot, 32);
-        float* pbase = a.partial + ((size_t)chunk_idx * a.Hq + head * G) * (D + 2);
+        float* pbase = a.partial + ((size_t)cidx * a.Hq + head * G) * (D + 2);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int g = 4 * kq + r;
@@ -263,6 +336,26 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
             pbase[(size_t)c16 * (D + 2) + D] = m_run;
             pbase[(size_t)c16 * (D + 2) + D + 1] = l_tot;
         }
+        if (++item >= item_end) return false;
+        rec = rec_n;
+        req = __builtin_amdgcn_readlane(rec, 16);
+        head = __builtin_amdgcn_readlane(rec, 17);
+        t0 = __builtin_amdgcn_readlane(rec, 18);
+        t1 = __builtin_amdgcn_readlane(rec, 19);
+        cidx = __builtin_amdgcn_readlane(rec, 20);
+        npairs = ((t1 - t0 + kPageTokens - 1) / kPageTokens + 1) / 2;
+        pp = 0;
+        rec_n = load_rec(item + 1 < item_end ? item + 1 : item);
+        load_q(req, head);  // also drains every outstanding request before the steady state resumes
+        head_n = __builtin_amdgcn_readlane(rec_n, 17);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) O[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = -INFINITY;
+        l_run = 0.f;
+        return true;
+    };
+
+    while (step()) {
     }
 }
 
@@ -358,6 +451,7 @@ hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan
     a.chunk_off = plan.chunk_off;
     a.item_req = plan.item_req;
     a.item_chunk = plan.item_chunk;
+    a.records = plan.records;
     a.partial = plan.partial;
     a.len_plus = len_plus;
     a.max_pages = max_pages;
@@ -376,8 +470,15 @@ hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
-    // persistent waves: 2 workgroups of 4 waves per CU at most
-    const int grid = (int)max(1LL, min((items + 3) / 4, 512LL));
+    // persistent waves, at most 2 workgroups of 4 waves per CU; when the item count is known the
+    // wave count is trimmed so that every wave gets the same number of items
+    #ifndef SUN_ATTN_MAX_WAVES
+#define SUN_ATTN_MAX_WAVES 2048
+#endif
+    const long long max_waves = SUN_ATTN_MAX_WAVES;
+    const long long rounds = (items + max_waves - 1) / max_waves;
+    const long long waves = total_chunks_hint >= 0 ? (items + rounds - 1) / max(rounds, 1LL) : max_waves;
+    const int grid = (int)max(1LL, min((waves + 3) / 4, max_waves / 4));
     if (D == 64) return launch_split_d<64>(a, G, grid, st);
     if (D == 128) return launch_split_d<128>(a, G, grid, st);
     return hipErrorInvalidValue;

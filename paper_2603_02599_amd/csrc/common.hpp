@@ -13,7 +13,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kWave = 64;
 constexpr int kPageTokens = 16;     // tokens per KV page
-constexpr int kAttnChunk = 256;     // tokens per split-K work item; a request's chunking depends on its own length only
+#ifndef SUN_ATTN_CHUNK
+#define SUN_ATTN_CHUNK 256
+#endif
+constexpr int kAttnChunk = SUN_ATTN_CHUNK;  // tokens per split-K work item; a request's chunking depends on its own length only
 constexpr int kGroup = 128;         // quantisation group along K (Appendix A.1)
 constexpr int kMaxBatchTile = 256;  // rows one projection launch covers
 

@@ -48,12 +48,13 @@ struct AttnPlan {           // device arrays inside the workspace
     int32_t* chunk_off;     // [batch+1] prefix sum of chunks per request
     int32_t* item_req;      // [max_chunks]
     int32_t* item_chunk;    // [max_chunks]
+    int32_t* records;       // [max_chunks * Hkv][24] per-item records, ordered (request, kv head, chunk)
     float* partial;         // [max_chunks][Hq][d+2]  (o[d], m, l)
     int max_chunks;
 };
 size_t attn_max_chunks(int batch, int max_pages);
-hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch, int max_pages,
-                            hipStream_t st);
+hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch,
+                            const int32_t* page_tables, int max_pages, int n_pages, int Hkv, hipStream_t st);
 // n_tokens(i) = n_or_len[i] + len_plus.  q fp32 [batch, Hq*d].  total_chunks_hint < 0 if unknown.
 hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan, const float* q,
                              const int32_t* page_tables, int max_pages, const int32_t* n_or_len, int len_plus,
