@@ -503,13 +503,32 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
     const int c0 = a.chunk_off[b], c1 = a.chunk_off[b + 1];
     const size_t stride = (size_t)a.Hq * (a.D + 2);
     const float* p = a.partial + (size_t)c0 * stride + (size_t)h * (a.D + 2);
-    float M = -INFINITY;
-    for (int c = 0; c < c1 - c0; ++c) M = fmaxf(M, p[c * stride + a.D]);
-    float num = 0.f, den = 0.f;
-    for (int c = 0; c < c1 - c0; ++c) {
-        const float w = exp2f(p[c * stride + a.D] - M);
-        den = fmaf(w, p[c * stride + a.D + 1], den);
-        num = fmaf(w, p[c * stride + j], num);
+    // chunks are merged in order, eight at a time so that their loads are in flight together
+    float M = -INFINITY, num = 0.f, den = 0.f;
+    for (int cb = 0; cb < c1 - c0; cb += 8) {
+        float m8[8], l8[8], o8[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = min(cb + i, c1 - c0 - 1);
+            m8[i] = p[c * stride + a.D];
+            l8[i] = p[c * stride + a.D + 1];
+            o8[i] = p[c * stride + j];
+        }
+        float Mn = M;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (cb + i < c1 - c0) Mn = fmaxf(Mn, m8[i]);
+        const float sc = exp2f(M - Mn);
+        num *= sc;
+        den *= sc;
+        M = Mn;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (cb + i < c1 - c0) {
+                const float w = exp2f(m8[i] - M);
+                den = fmaf(w, l8[i], den);
+                num = fmaf(w, o8[i], num);
+            }
     }
     const float v = num / den;
     if (a.out_f32) a.out_f32[(size_t)b * a.Hq * a.D + col] = v;

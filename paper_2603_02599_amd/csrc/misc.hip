@@ -38,43 +38,61 @@ struct NormArgs {
     float eps;
 };
 
-__global__ __launch_bounds__(256) void residual_norm_kernel(NormArgs a) {
-    __shared__ float red[4];
-    const int b = blockIdx.x, tid = threadIdx.x, H = a.H;
+// One 8-element unit per thread and pass (up to two passes, i.e. hidden <= 16 * blockDim), all
+// slab loads of a unit independent of one another so that they are in flight together.
+__global__ __launch_bounds__(1024) void residual_norm_kernel(NormArgs a) {
+    __shared__ float red[16];
+    const int b = blockIdx.x, tid = threadIdx.x, H = a.H, nunits = H / 8, nthreads = blockDim.x;
     float* xr = a.x + (size_t)b * H;
+    float v[2][8];
     float ss = 0.f;
-    for (int u = tid; u < H / 8; u += 256) {
-        float v[8];
-        *reinterpret_cast<f32x4*>(v) = *reinterpret_cast<const f32x4*>(xr + u * 8);
-        *reinterpret_cast<f32x4*>(v + 4) = *reinterpret_cast<const f32x4*>(xr + u * 8 + 4);
-        for (int s = 0; s < a.nparts; ++s) {
-            const float* p = a.partial + ((size_t)s * a.ld_rows + b) * H + u * 8;
-            const f32x4 p0 = *reinterpret_cast<const f32x4*>(p), p1 = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int u = tid + it * nthreads;
+        if (u < nunits) {
+            f32x4 lo = *reinterpret_cast<const f32x4*>(xr + u * 8), hi = *reinterpret_cast<const f32x4*>(xr + u * 8 + 4);
+            const float* p = a.partial + (size_t)b * H + u * 8;
+            const size_t slab = (size_t)a.ld_rows * H;
+            for (int s0 = 0; s0 < a.nparts; s0 += 4) {
+                f32x4 pl[4], ph[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int s = min(s0 + j, a.nparts - 1);
+                    pl[j] = *reinterpret_cast<const f32x4*>(p + s * slab);
+                    ph[j] = *reinterpret_cast<const f32x4*>(p + s * slab + 4);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (s0 + j < a.nparts) {  // slabs are added in ascending order
+                        lo += pl[j];
+                        hi += ph[j];
+                    }
+            }
+            if (a.nparts > 0) {
+                *reinterpret_cast<f32x4*>(xr + u * 8) = lo;
+                *reinterpret_cast<f32x4*>(xr + u * 8 + 4) = hi;
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                v[e] += p0[e];
-                v[4 + e] += p1[e];
+                v[it][e] = lo[e];
+                v[it][4 + e] = hi[e];
             }
-        }
-        if (a.nparts > 0) {
-            *reinterpret_cast<f32x4*>(xr + u * 8) = *reinterpret_cast<f32x4*>(v);
-            *reinterpret_cast<f32x4*>(xr + u * 8 + 4) = *reinterpret_cast<f32x4*>(v + 4);
-        }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(v[e], v[e], ss);
+            for (int e = 0; e < 8; ++e) ss = fmaf(v[it][e], v[it][e], ss);
+        }
     }
     ss = wave_sum(ss);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
-    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    float tot = 0.f;
+    for (int w = 0; w < nthreads / 64; ++w) tot += red[w];
     const float rinv = 1.0f / sqrtf(tot / (float)H + a.eps);
-    for (int u0 = 0; u0 < H / 8; u0 += 256) {
-        const int u = u0 + tid;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int u = tid + it * nthreads;
         float gsum = 0.f;
-        if (u < H / 8) {
-            float v[8], g[8];
-            *reinterpret_cast<f32x4*>(v) = *reinterpret_cast<const f32x4*>(xr + u * 8);
-            *reinterpret_cast<f32x4*>(v + 4) = *reinterpret_cast<const f32x4*>(xr + u * 8 + 4);
+        if (u < nunits) {
+            float g[8], y[8];
             if (a.gain_bf16) {
                 const u32x4 gw = *reinterpret_cast<const u32x4*>((const uint16_t*)a.gain + u * 8);
 #pragma unroll
@@ -87,16 +105,16 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(NormArgs a) {
                 for (int e = 0; e < 8; ++e) g[e] = ((const float*)a.gain)[u * 8 + e];
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = v[e] * rinv * g[e];
+            for (int e = 0; e < 8; ++e) y[e] = v[it][e] * rinv * g[e];
             if (a.h_f32) {
-                *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8) = *reinterpret_cast<f32x4*>(v);
-                *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8 + 4) = *reinterpret_cast<f32x4*>(v + 4);
+                *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8) = f32x4{y[0], y[1], y[2], y[3]};
+                *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8 + 4) = f32x4{y[4], y[5], y[6], y[7]};
             }
             if (a.h_tiled) {
                 u32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    o[e] = pack_bf16(v[2 * e], v[2 * e + 1]);
+                    o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
                     gsum += bf16_lo(o[e]) + bf16_hi(o[e]);
                 }
                 reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, b, u)] = o;
@@ -107,7 +125,7 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(NormArgs a) {
             gsum += __shfl_xor(gsum, 2);
             gsum += __shfl_xor(gsum, 4);
             gsum += __shfl_xor(gsum, 8);
-            if (u < H / 8 && (tid & 15) == 0) a.hsum[(size_t)(u >> 4) * (a.mb * 32) + b] = gsum;
+            if (u < nunits && (tid & 15) == 0) a.hsum[(size_t)(u >> 4) * (a.mb * 32) + b] = gsum;
         }
     }
 }
@@ -127,8 +145,10 @@ hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float*
     a.gain_bf16 = cfg.act_dtype == SUN_BF16;
     a.mb = atile_for_rows(batch).MB;
     a.eps = cfg.rms_eps;
-    if (cfg.hidden % 8) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(residual_norm_kernel, dim3(batch), dim3(256), 0, st, a);
+    if (cfg.hidden % 8 || cfg.hidden > 16 * 1024) return hipErrorInvalidValue;
+    const int units = cfg.hidden / 8;
+    const int threads = units <= 1024 ? (units + 63) / 64 * 64 : ((units + 1) / 2 + 63) / 64 * 64;
+    hipLaunchKernelGGL(residual_norm_kernel, dim3(batch), dim3(threads), 0, st, a);
     return hipGetLastError();
 }
 

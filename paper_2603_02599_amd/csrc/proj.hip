@@ -15,6 +15,7 @@
 // which equals sum_k (q_k - Z) S x_k up to fp32 rounding; the integer grid is never
 // rounded.  sum_k x_k per group comes from the activation producer.
 #include <hip/hip_fp16.h>
+#include <stdlib.h>
 
 #include "kernels.hpp"
 
@@ -36,7 +37,7 @@ struct ProjArgs {
     int out_mb;    // tiling of out_tiled
 };
 
-template <int MB, int KS, int NW, int EPI, bool W4>
+template <int MB, int KS, int NW, int EPI, bool W4, int NBUF>
 __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     constexpr int KK = KS / 16;                // MFMA k-steps per stage
     constexpr int STAGE_UNITS = KK * MB * 64;  // 16-byte units of activations per stage
@@ -45,10 +46,10 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     static_assert(STAGE_UNITS % NT == 0, "stage must divide evenly over the workgroup");
     constexpr int WREGS = W4 ? KK / 4 : KK;    // 16-byte weight loads per lane per stage
 
-    __shared__ u32x4 lds[2][STAGE_UNITS];
-    float* hs_lds = nullptr;  // W4: [2][MB*32] group sums of the activations, double buffered per chunk
+    __shared__ u32x4 lds[NBUF][STAGE_UNITS];  // ring of staged activation tiles (prefetch distance NBUF-1)
+    float* hs_lds = nullptr;  // W4: [4][MB*32] group sums of the activations, ring indexed by chunk
     if constexpr (W4) {
-        __shared__ __attribute__((aligned(16))) float hs_store[2 * MB * 32];
+        __shared__ __attribute__((aligned(16))) float hs_store[4 * MB * 32];
         hs_lds = hs_store;
     }
 
@@ -61,6 +62,7 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     const int s1 = min(a.n_stages, s0 + a.stages_per_split);
     const int kch = a.K / 128;
 
+    // waves past the last column block work on block 0 and drop their result (keeps the loop branch-free)
     const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * (W4 ? 2 : 8) * 64 + lane;
     const uint32_t* SZl = W4 ? a.SZ + ((size_t)(active ? nb : 0) * kch) * 32 + (lane & 31) : nullptr;
 
@@ -71,16 +73,14 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
 
-    u32x4 w0[WREGS], w1[WREGS], areg[UPT];
-    uint32_t sz0 = 0, sz1 = 0;
+    u32x4 w0[WREGS], w1[WREGS], w2[NBUF == 3 ? WREGS : 1], areg[UPT];
+    uint32_t sz0 = 0, sz1 = 0, sz2 = 0;
     float hreg = 0.f;
 
     auto load_w = [&](u32x4(&w)[WREGS], uint32_t& sz, int st) {
-        if (active) {
 #pragma unroll
-            for (int j = 0; j < WREGS; ++j) w[j] = Wl[((size_t)st * WREGS + j) * 64];
-            if (W4) sz = SZl[(size_t)((st * KK) >> 3) * 32];
-        }
+        for (int j = 0; j < WREGS; ++j) w[j] = Wl[((size_t)st * WREGS + j) * 64];
+        if (W4) sz = SZl[(size_t)((st * KK) >> 3) * 32];
     };
     auto load_a = [&](int st) {
 #pragma unroll
@@ -95,10 +95,9 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     auto store_a = [&](int buf, int st) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i) lds[buf][i * NT + tid] = areg[i];
-        if (W4 && ((st * KK) & 7) == 0 && tid < MB * 32) hs_lds[(((st * KK) >> 3) & 1) * MB * 32 + tid] = hreg;
+        if (W4 && ((st * KK) & 7) == 0 && tid < MB * 32) hs_lds[(((st * KK) >> 3) & 3) * MB * 32 + tid] = hreg;
     };
     auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
-        if (!active) return;
         const bool first = (KS == 128) || ((st & 1) == 0);
         const bool last = (KS == 128) || ((st & 1) == 1);
 #pragma unroll
@@ -133,7 +132,7 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
         if (W4 && last) {
             const __half2 h2 = __builtin_bit_cast(__half2, sz);
             const float s = __low2float(h2), nzz = -(128.f + __high2float(h2));
-            const float* hs = hs_lds + (((st * KK) >> 3) & 1) * MB * 32;
+            const float* hs = hs_lds + (((st * KK) >> 3) & 3) * MB * 32;
 #pragma unroll
             for (int m = 0; m < MB; ++m)
 #pragma unroll
@@ -146,29 +145,55 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
         }
     };
 
+    // Steady state without branches around the loads, so that the requests of the following
+    // stages stay in flight while this stage is computed; past the end the last stage is
+    // re-read and never used.
     if (s0 < s1) {
-        load_w(w0, sz0, s0);
-        load_a(s0);
-        store_a(0, s0);
-        __syncthreads();
-        for (int st = s0; st < s1; st += 2) {
-            const bool more1 = st + 1 < s1;
-            if (more1) {
-                load_w(w1, sz1, st + 1);
-                load_a(st + 1);
-            }
-            compute(0, w0, sz0, st);
-            if (more1) store_a(1, st + 1);
+        if constexpr (NBUF == 3) {
+            auto phase = [&](const u32x4(&wc)[WREGS], uint32_t szc, u32x4(&wn)[WREGS], uint32_t& szn, int bufc, int bufn,
+                             int st) {
+                const int nx = min(st + 2, s1 - 1);
+                load_a(nx);  // before the weights: the LDS store below then waits for these only
+                load_w(wn, szn, nx);
+                compute(bufc, wc, szc, st);
+                store_a(bufn, nx);
+                __syncthreads();
+            };
+            const int sA = min(s0 + 1, s1 - 1);
+            load_w(w0, sz0, s0);
+            load_a(s0);
+            store_a(0, s0);
+            load_w(w1, sz1, sA);
+            load_a(sA);
+            store_a(1, sA);
             __syncthreads();
-            if (!more1) break;
-            const bool more2 = st + 2 < s1;
-            if (more2) {
-                load_w(w0, sz0, st + 2);
-                load_a(st + 2);
+            for (int st = s0; st < s1; st += 3) {
+                phase(w0, sz0, w2, sz2, 0, 2, st);
+                if (st + 1 >= s1) break;
+                phase(w1, sz1, w0, sz0, 1, 0, st + 1);
+                if (st + 2 >= s1) break;
+                phase(w2, sz2, w1, sz1, 2, 1, st + 2);
             }
-            compute(1, w1, sz1, st + 1);
-            if (more2) store_a(0, st + 2);
+        } else {
+            load_w(w0, sz0, s0);
+            load_a(s0);
+            store_a(0, s0);
             __syncthreads();
+            for (int st = s0; st < s1; st += 2) {
+                const int n1 = min(st + 1, s1 - 1);
+                load_a(n1);
+                load_w(w1, sz1, n1);
+                compute(0, w0, sz0, st);
+                store_a(1, n1);
+                __syncthreads();
+                if (st + 1 >= s1) break;
+                const int n2 = min(st + 2, s1 - 1);
+                load_a(n2);
+                load_w(w0, sz0, n2);
+                compute(1, w1, sz1, st + 1);
+                store_a(0, n2);
+                __syncthreads();
+            }
         }
     }
     if (!active) return;
@@ -204,11 +229,12 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
 template <int MB, int KS, bool W4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
     constexpr int NW = 4;
+    constexpr int NBUF = (MB * KS * 4 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
     if (epilogue == EPI_STORE)
-        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4, NBUF>), grid, block, 0, st, a);
     else
-        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, W4>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, W4, NBUF>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 
@@ -216,7 +242,8 @@ static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / s
 
 int proj_pick_splits(const Mat& W, int rows, int max_splits) {
     const int tiles = (W.N / 32 + 3) / 4, kch = W.K / 128;
-    const int target = rows <= 64 ? 512 : 256;
+    static const int env_target = getenv("SUN_SPLIT_TARGET") ? atoi(getenv("SUN_SPLIT_TARGET")) : 0;
+    const int target = env_target ? env_target : 256;
     int s = (target + tiles - 1) / tiles;
     s = min(s, max_splits);
     s = min(s, max(1, kch / 2));
