@@ -31,7 +31,8 @@ def build(force: bool = False) -> str:
 class Cfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
-                ("vocab", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double)]
+                ("vocab", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double),
+                ("act_bf16", C.c_int32), ("pad_", C.c_int32)]
 
 
 class Mat(C.Structure):
@@ -76,10 +77,11 @@ def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
 
-def make_cfg(shape) -> Cfg:
-    """shape: any object with the Shape fields (n_layers, hidden, ...)."""
+def make_cfg(shape, act_bf16: bool = False) -> Cfg:
+    """shape: any object with the Shape fields (n_layers, hidden, ...).  act_bf16 selects the
+    16-bit configuration, in which every projection consumes bf16-rounded activations."""
     return Cfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
-               shape.ffn, shape.vocab, float(shape.rms_eps), float(shape.rope_base))
+               shape.ffn, shape.vocab, float(shape.rms_eps), float(shape.rope_base), int(act_bf16), 0)
 
 
 _KIND = {np.dtype(np.float32): F32, np.dtype(np.uint16): BF16, np.dtype(np.float64): F64}

@@ -28,6 +28,10 @@
  * written and before this step attends to it, so the step consumes exactly
  * what later steps will read.  cos/sin of the rotary angle are evaluated in
  * double from a double angle and then rounded to float.
+ * In the 16-bit configuration (act_bf16) activations are bf16 as in a 16-bit
+ * deployment: the vector fed to each projection (normalised hidden state,
+ * attention output, SwiGLU product) is rounded to bfloat16 first; sums, the
+ * residual stream, softmax and norms stay double.
  *
  * Pins (see tests, "not gpu"): causal full forward == prefill + decode
  * (Eq. 1 vs Eq. 2+3 with theta_p = theta_d), library special cases
@@ -52,6 +56,8 @@ enum { ORC_OK = 0, ORC_ERR_ARG = 1, ORC_ERR_PAGE = 2, ORC_ERR_TOKEN = 3, ORC_ERR
 typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
     double rms_eps, rope_base;
+    int32_t act_bf16; /* 16-bit configuration: the input of every projection is a bf16 value */
+    int32_t pad_;
 } orc_cfg;
 
 /* One parameter tensor, row-major [rows, cols]; y = M x contracts over cols. */
@@ -219,6 +225,12 @@ static void rope(double *u, int d, int64_t pos, double base) {
 
 static double silu(double z) { return z / (1.0 + exp(-z)); }
 
+/* 16-bit configuration: a projection consumes bf16 activations. */
+static void act_round(const orc_cfg *c, double *x, size_t n) {
+    if (!c->act_bf16) return;
+    for (size_t i = 0; i < n; ++i) x[i] = bf16_to_double(double_to_bf16(x[i]));
+}
+
 /* ---------- attention over one request, one layer ---------- */
 
 /* softmax-weighted sum for one query head: scores[0..n-1] already scaled. */
@@ -262,12 +274,13 @@ static uint16_t *pool_v(const orc_pool *p, int layer, int64_t page, int head, in
     return p->base + p->v_off + layer * p->v_layer + page * p->v_page + head * p->v_head + slot * p->v_token;
 }
 
-/* Paged cache: token t of the request lives in page pt[t / P], slot t % P. */
+/* Paged cache: token t of the request lives in page pt[t / P], slot t % P.
+ * Query heads h0 <= h < h1 (heads are independent of one another). */
 static void attend_paged(const orc_cfg *c, const orc_pool *p, int layer, const int32_t *pt,
-                         const double *q, int64_t n, double *a, double *rowsum, double *scratch) {
+                         const double *q, int64_t n, double *a, double *rowsum, double *scratch, int h0, int h1) {
     const int d = c->head_dim, G = c->n_q_heads / c->n_kv_heads, P = p->page_tokens;
     const double scale = 1.0 / sqrt((double)d);
-    for (int h = 0; h < c->n_q_heads; ++h) {
+    for (int h = h0; h < h1; ++h) {
         int kvh = h / G;
         for (int64_t t = 0; t < n; ++t) {
             const uint16_t *k = pool_k(p, layer, pt[t / P], kvh, (int)(t % P));
@@ -309,9 +322,11 @@ static void feed_forward(const orc_cfg *c, const orc_mat *mats, int l, int B, do
                          double *Hn, double *Gt, double *Up, double *Dn) {
     const int H = c->hidden, F = c->ffn;
     for (int b = 0; b < B; ++b) rmsnorm(MAT_L(mats, l, M_G2), X + (size_t)b * H, H, c->rms_eps, Hn + (size_t)b * H);
+    act_round(c, Hn, (size_t)B * H);
     linear(MAT_L(mats, l, M_WG), Hn, B, Gt);
     linear(MAT_L(mats, l, M_WU), Hn, B, Up);
     for (size_t i = 0; i < (size_t)B * F; ++i) Gt[i] = silu(Gt[i]) * Up[i];
+    act_round(c, Gt, (size_t)B * F);
     linear(MAT_L(mats, l, M_WD), Gt, B, Dn);
     for (size_t i = 0; i < (size_t)B * H; ++i) X[i] += Dn[i];
 }
@@ -320,6 +335,7 @@ static void final_logits(const orc_cfg *c, const orc_mat *mats, int B, const dou
                          double *logits, int32_t *next) {
     const int H = c->hidden, V = c->vocab, NL = c->n_layers;
     for (int b = 0; b < B; ++b) rmsnorm(MAT_GF(mats, NL), X + (size_t)b * H, H, c->rms_eps, Hn + (size_t)b * H);
+    act_round(c, Hn, (size_t)B * H);
     linear(MAT_LM(mats, NL), Hn, B, logits);
     if (next) for (int b = 0; b < B; ++b) next[b] = argmax_lowest(logits + (size_t)b * V, V);
 }
@@ -365,6 +381,7 @@ int orc_decode_step(const orc_cfg *c, const orc_mat *mats, const orc_pool *pool,
     int rc = embed_rows(c, mats, B, tokens, X);
     for (int l = 0; l < NL && rc == ORC_OK; ++l) {
         for (int b = 0; b < B; ++b) rmsnorm(MAT_L(mats, l, M_G1), X + (size_t)b * H, H, c->rms_eps, Hn + (size_t)b * H);
+        act_round(c, Hn, nx);
         linear(MAT_L(mats, l, M_WQ), Hn, B, Q);
         linear(MAT_L(mats, l, M_WK), Hn, B, K);
         linear(MAT_L(mats, l, M_WV), Hn, B, Vv);
@@ -384,12 +401,10 @@ int orc_decode_step(const orc_cfg *c, const orc_mat *mats, const orc_pool *pool,
                     vd[j * pool->v_dim] = double_to_bf16(v[h * d + j]);
                 }
             }
-            double *scratch = malloc(sizeof(double) * (size_t)n);
-            double *rs = rowsums ? rowsums + ((size_t)b * NL + l) * Hq : NULL;
-            double *a = A + (size_t)b * QD;
-            if (mode == 0) {
-                attend_paged(c, pool, l, pt, q, n, a, rs, scratch);
-            } else {
+            if (mode != 0) {
+                double *scratch = malloc(sizeof(double) * (size_t)n);
+                double *rs = rowsums ? rowsums + ((size_t)b * NL + l) * Hq : NULL;
+                double *a = A + (size_t)b * QD;
                 double *Kc = malloc(sizeof(double) * (size_t)n * KD), *Vc = malloc(sizeof(double) * (size_t)n * KD);
                 for (int64_t t = 0; t < n; ++t)
                     for (int h = 0; h < Hkv; ++h) {
@@ -403,10 +418,26 @@ int orc_decode_step(const orc_cfg *c, const orc_mat *mats, const orc_pool *pool,
                 attend_contig(c, q, Kc, Vc, n, a, rs, scratch);
                 free(Kc);
                 free(Vc);
+                free(scratch);
             }
-            free(scratch);
-            if (attn_probe) memcpy(attn_probe + ((size_t)b * NL + l) * QD, a, sizeof(double) * QD);
         }
+        if (mode == 0) {
+            /* every (request, query head) pair is independent: spread them over the cores */
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+            for (int b = 0; b < B; ++b)
+                for (int h = 0; h < Hq; ++h) {
+                    const int64_t n = (int64_t)seq_lens[b] + 1;
+                    double *scratch = malloc(sizeof(double) * (size_t)n);
+                    double *rs = rowsums ? rowsums + ((size_t)b * NL + l) * Hq : NULL;
+                    attend_paged(c, pool, l, page_tables + (size_t)b * max_pages, Q + (size_t)b * QD, n,
+                                 A + (size_t)b * QD, rs, scratch, h, h + 1);
+                    free(scratch);
+                }
+        }
+        if (attn_probe)
+            for (int b = 0; b < B; ++b)
+                memcpy(attn_probe + ((size_t)b * NL + l) * QD, A + (size_t)b * QD, sizeof(double) * QD);
+        act_round(c, A, (size_t)B * QD);
         linear(MAT_L(mats, l, M_WO), A, B, O);
         for (size_t i = 0; i < nx; ++i) X[i] += O[i];
         feed_forward(c, mats, l, B, X, Hn, Gt, Up, Dn);
@@ -437,6 +468,7 @@ int orc_decode_contig_f64(const orc_cfg *c, const orc_mat *mats, int32_t token, 
     int rc = embed_rows(c, mats, 1, &token, X);
     for (int l = 0; l < NL && rc == ORC_OK; ++l) {
         rmsnorm(MAT_L(mats, l, M_G1), X, H, c->rms_eps, Hn);
+        act_round(c, Hn, H);
         linear(MAT_L(mats, l, M_WQ), Hn, 1, q);
         linear(MAT_L(mats, l, M_WK), Hn, 1, k);
         linear(MAT_L(mats, l, M_WV), Hn, 1, v);
@@ -448,6 +480,7 @@ int orc_decode_contig_f64(const orc_cfg *c, const orc_mat *mats, int32_t token, 
             Vl[(size_t)L * KD + j] = round_kv ? bf16_to_double(double_to_bf16(v[j])) : v[j];
         }
         attend_contig(c, q, Kl, Vl, L + 1, a, NULL, scratch);
+        act_round(c, a, QD);
         linear(MAT_L(mats, l, M_WO), a, 1, O);
         for (int j = 0; j < H; ++j) X[j] += O[j];
         feed_forward(c, mats, l, 1, X, Hn, Gt, Up, Dn);
@@ -477,6 +510,7 @@ int orc_full_forward(const orc_cfg *c, const orc_mat *mats, int T, const int32_t
     int rc = embed_rows(c, mats, T, tokens, X);
     for (int l = 0; l < NL && rc == ORC_OK; ++l) {
         for (int t = 0; t < T; ++t) rmsnorm(MAT_L(mats, l, M_G1), X + (size_t)t * H, H, c->rms_eps, Hn + (size_t)t * H);
+        act_round(c, Hn, nx);
         linear(MAT_L(mats, l, M_WQ), Hn, T, Q);
         linear(MAT_L(mats, l, M_WK), Hn, T, K);
         linear(MAT_L(mats, l, M_WV), Hn, T, V);
@@ -506,6 +540,7 @@ int orc_full_forward(const orc_cfg *c, const orc_mat *mats, int T, const int32_t
                     A[(size_t)t * QD + h * d + j] = acc;
                 }
             }
+        act_round(c, A, (size_t)T * QD);
         linear(MAT_L(mats, l, M_WO), A, T, O);
         for (size_t i = 0; i < nx; ++i) X[i] += O[i];
         feed_forward(c, mats, l, T, X, Hn, Gt, Up, Dn);
@@ -536,7 +571,7 @@ int orc_attention_paged(const orc_cfg *c, const orc_pool *pool, int layer, const
                         const double *q, int64_t n, double *a, double *rowsum) {
     double *scratch = malloc(sizeof(double) * (size_t)n);
     if (!scratch) return ORC_ERR_ALLOC;
-    attend_paged(c, pool, layer, pt, q, n, a, rowsum, scratch);
+    attend_paged(c, pool, layer, pt, q, n, a, rowsum, scratch, 0, c->n_q_heads);
     free(scratch);
     return ORC_OK;
 }

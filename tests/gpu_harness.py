@@ -45,15 +45,48 @@ def layout_strides(lay) -> Dict[str, int]:
     return {k: int(getattr(lay, k)) for k in keys}
 
 
+class SharedWeights:
+    """Decode weights on the GPU (dense, and optionally their 4-bit quantisation) with the library
+    handle and a lazily built oracle mirror; shared by several workloads of the same shape."""
+
+    def __init__(self, shape, dtype: str, seed: int, quant_mode: Optional[str] = None):
+        self.shape, self.dtype = shape, dtype
+        self.cfg = sun.make_cfg(shape, dtype)
+        self.w = wl.make_weights(shape, dtype, DEV, seed)
+        self.quant = None
+        if quant_mode is None:
+            self.handle = sun.sun_weights_create(self.cfg, self.w)
+        else:
+            self.quant = {k: [sun.sun_quantize_w4(m, 128, quant_mode) for m in self.w[k]] for k in sun.QUANT_KEYS}
+            self.handle = sun.sun_qweights_create(self.cfg, self.w, self.quant)
+        torch.cuda.synchronize()
+        self._params = None
+
+    def oracle_params(self):
+        if self._params is None:
+            wnp = weights_to_np(self.w)
+            qnp = None
+            if self.quant is not None:
+                qnp = {k: [tuple(to_np(t) for t in trip) for trip in v] for k, v in self.quant.items()}
+            self._keep = (wnp, qnp)
+            self._params = orc.params_from_arrays(wnp, qnp)
+        return self._params
+
+
 class GpuCase:
     """One workload resident on the GPU with handles created through the C ABI."""
 
     def __init__(self, work: wl.Workload, weights: Optional[Dict[str, object]] = None, quant_mode: Optional[str] = None,
-                 pool_seed: Optional[int] = None, weights_seed: Optional[int] = None):
+                 pool_seed: Optional[int] = None, weights_seed: Optional[int] = None,
+                 shared: Optional[SharedWeights] = None):
         self.work = work
         shape = work.shape
         self.cfg = sun.make_cfg(shape, work.dtype)
-        self.w = weights if weights is not None else wl.make_weights(shape, work.dtype, DEV, weights_seed or work.seed + 1)
+        self.shared = shared
+        if shared is not None:
+            self.w = shared.w
+        else:
+            self.w = weights if weights is not None else wl.make_weights(shape, work.dtype, DEV, weights_seed or work.seed + 1)
         nbytes = sun.sun_kv_pool_bytes(self.cfg, work.n_pages)
         self.pool_mem = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=DEV)
         wl.fill_kv_pool(self.pool_mem, pool_seed or work.seed + 2)
@@ -61,7 +94,9 @@ class GpuCase:
         self.lay = self.pool.layout()
         assert self.lay.n_pages == work.n_pages
         self.quant = None
-        if quant_mode is None:
+        if shared is not None:
+            self.quant, self.weights = shared.quant, shared.handle
+        elif quant_mode is None:
             self.weights = sun.sun_weights_create(self.cfg, self.w)
         else:
             self.quant = {k: [sun.sun_quantize_w4(m, 128, quant_mode) for m in self.w[k]] for k in sun.QUANT_KEYS}
@@ -87,6 +122,8 @@ class GpuCase:
 
     # ---- oracle mirror ----
     def oracle_params(self):
+        if self.shared is not None:
+            return self.shared.oracle_params()
         wnp = weights_to_np(self.w)
         qnp = None
         if self.quant is not None:
@@ -127,7 +164,7 @@ def run_oracle(case: GpuCase, rows: Sequence[int], params=None, tokens=None, len
     rows = list(rows)
     host, pool, tabs, used = case.extract_pool(rows)
     params = params if params is not None else case.oracle_params()
-    ocfg = orc.make_cfg(work.shape)
+    ocfg = orc.make_cfg(work.shape, act_bf16=(work.dtype == "bf16"))
     toks = (work.tokens if tokens is None else tokens)[rows]
     ln = (work.seq_lens if lens is None else lens)[rows]
     mi = (work.model_ids if ids is None else ids)[rows]

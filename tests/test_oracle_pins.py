@@ -49,8 +49,10 @@ def _rope_complex(x, pos, base):
     return torch.cat([z.real, z.imag], dim=-1)
 
 
-def torch_causal_forward(shape, w, tokens):
-    """tokens: list of ints. Returns logits [T, V] (float64) using only torch library ops."""
+def torch_causal_forward(shape, w, tokens, act_bf16=False):
+    """tokens: list of ints. Returns logits [T, V] (float64) using only torch library ops.
+    act_bf16: the input of every projection is rounded to bfloat16 by torch's own conversion."""
+    rb = (lambda t: t.to(torch.bfloat16).to(torch.float64)) if act_bf16 else (lambda t: t)
     tw = {k: ([torch.from_numpy(np.asarray(a, dtype=np.float64)) for a in v] if isinstance(v, list)
               else torch.from_numpy(np.asarray(v, dtype=np.float64))) for k, v in w.items()}
     T = len(tokens)
@@ -58,7 +60,7 @@ def torch_causal_forward(shape, w, tokens):
     x = tw["embed"][torch.tensor(tokens, dtype=torch.long)]
     pos = torch.arange(T)
     for l in range(shape.n_layers):
-        h = F.rms_norm(x, (shape.hidden,), tw["g1"][l], eps=shape.rms_eps)
+        h = rb(F.rms_norm(x, (shape.hidden,), tw["g1"][l], eps=shape.rms_eps))
         q = F.linear(h, tw["wq"][l]).view(T, Hq, d)
         k = F.linear(h, tw["wk"][l]).view(T, Hkv, d)
         v = F.linear(h, tw["wv"][l]).view(T, Hkv, d)
@@ -67,11 +69,11 @@ def torch_causal_forward(shape, w, tokens):
         vr = v.repeat_interleave(Hq // Hkv, dim=1)
         a = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kr.transpose(0, 1)[None],
                                            vr.transpose(0, 1)[None], is_causal=True)[0]
-        a = a.transpose(0, 1).reshape(T, Hq * d)
+        a = rb(a.transpose(0, 1).reshape(T, Hq * d))
         x = x + F.linear(a, tw["wo"][l])
-        h = F.rms_norm(x, (shape.hidden,), tw["g2"][l], eps=shape.rms_eps)
-        x = x + F.linear(F.silu(F.linear(h, tw["wg"][l])) * F.linear(h, tw["wu"][l]), tw["wd"][l])
-    h = F.rms_norm(x, (shape.hidden,), tw["gf"], eps=shape.rms_eps)
+        h = rb(F.rms_norm(x, (shape.hidden,), tw["g2"][l], eps=shape.rms_eps))
+        x = x + F.linear(rb(F.silu(F.linear(h, tw["wg"][l])) * F.linear(h, tw["wu"][l])), tw["wd"][l])
+    h = rb(F.rms_norm(x, (shape.hidden,), tw["gf"], eps=shape.rms_eps))
     return F.linear(h, tw["wlm"]).numpy()
 
 
@@ -88,6 +90,29 @@ def test_full_forward_equals_torch_library_forward(orc, shape):
     want = torch_causal_forward(shape, w, toks)
     assert np.abs(got - want).max() < 1e-10
     assert np.abs(want).max() > 0.05  # not a vacuous comparison
+
+
+def test_sixteen_bit_configuration_rounds_projection_inputs(orc):
+    """16-bit configuration: the vectors fed to the projections are bf16 values.  Pinned to the
+    torch-library forward with torch's own bfloat16 conversion at the same five places, through
+    the brute-force forward and through prefill + contiguous decode."""
+    shape = MiniShape()
+    rng = np.random.default_rng(31)
+    w = random_weights(shape, rng)
+    toks = rng.integers(0, shape.vocab, size=19)
+    cfg, params = orc.make_cfg(shape, act_bf16=True), orc.params_from_arrays(w)
+    want = torch_causal_forward(shape, w, toks.tolist(), act_bf16=True)
+    got = orc.full_forward(cfg, params, toks)
+    assert np.abs(got - want).max() < 1e-10
+    plain = orc.full_forward(orc.make_cfg(shape), params, toks)
+    assert 1e-5 < np.abs(got - plain).max() < 0.3        # the rounding is really applied, and is small
+    L = len(toks) - 1
+    _, K, V = orc.full_forward(cfg, params, toks[:L], want_kv=True)
+    Kc = np.zeros((shape.n_layers, L + 1, shape.n_kv_heads, shape.head_dim))
+    Vc = np.zeros_like(Kc)
+    Kc[:, :L], Vc[:, :L] = K, V
+    logits, _ = orc.decode_contig_f64(cfg, params, int(toks[L]), L, Kc, Vc)
+    assert np.abs(logits - want[-1]).max() < 1e-10
 
 
 @pytest.mark.parametrize("L", [0, 1, 15, 16, 17, 37])
