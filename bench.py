@@ -75,7 +75,7 @@ def cpu_baseline(case, work, n_sample: int):
     rows = sorted({int(order[int(round(q * (work.batch - 1)))]) for q in np.linspace(0, 1, n_sample)})
     params = case.oracle_params()
     host, pool, tabs, used = case.extract_pool(rows)
-    ocfg = orc.make_cfg(work.shape, act_bf16=(work.dtype == "bf16"))
+    ocfg = orc.make_cfg(work.shape)
     t0 = time.perf_counter()
     orc.decode_step(ocfg, params, pool, work.tokens[rows], tabs, work.seq_lens[rows], work.model_ids[rows])
     dt = time.perf_counter() - t0

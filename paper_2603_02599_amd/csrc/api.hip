@@ -106,9 +106,9 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
     w.q = (float*)take((size_t)batch * QD * 4);
     w.table = (float*)take((size_t)batch * c.head_dim * 4);
     if (c.act_dtype == SUN_BF16) {
-        w.hA = take((size_t)mb * 32 * H * 2);
-        w.aA = take((size_t)mb * 32 * QD * 2);
-        w.uA = take((size_t)mb * 32 * F * 2);
+        w.hA = take(atile_bytes(ATile{mb}, H));
+        w.aA = take(atile_bytes(ATile{mb}, QD));
+        w.uA = take(atile_bytes(ATile{mb}, F));
         w.hs = (float*)take((size_t)(std::max(std::max(H, QD), F) / 128 + 1) * mb * 32 * 4);
         w.part = (float*)take((size_t)kMaxSplits * batch * std::max(Nqkv, H) * 4);
     } else {

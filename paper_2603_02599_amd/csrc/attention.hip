@@ -533,10 +533,12 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
     const float v = num / den;
     if (a.out_f32) a.out_f32[(size_t)b * a.Hq * a.D + col] = v;
     if (a.out_tiled) {
-        const uint16_t bits = f32_to_bf16_bits(v);
-        a.out_tiled[atile_elem(ATile{a.out_mb}, b, col)] = bits;
+        uint16_t lo;
+        const uint16_t hi = split_bf16(v, lo);
+        a.out_tiled[atile_elem(ATile{a.out_mb}, 0, b, col)] = hi;
+        a.out_tiled[atile_elem(ATile{a.out_mb}, 1, b, col)] = lo;
         if (a.hsum) {
-            const float s = wave_sum(bf16_bits_to_f32(bits));
+            const float s = wave_sum(bf16_bits_to_f32(hi) + bf16_bits_to_f32(lo));
             if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
             __syncthreads();
             if (threadIdx.x == 0) a.hsum[(size_t)blockIdx.x * (a.out_mb * 32) + b] = red[0] + red[1];

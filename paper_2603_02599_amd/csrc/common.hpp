@@ -34,30 +34,41 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
 }
 
-// ---- projection activations: "fragment-tiled" bf16 layout ----
-// A [rows, K] is stored so that one staging step of the MFMA projection kernels is a
-// linear copy into LDS and each 16-byte unit (8 consecutive k of one row) is one
-// lane's A operand of a 32x32x16 MFMA:
-//   unit(b, k/8) = ((chunk * 8 + kk) * MB + b/32) * 64 + half * 32 + b%32
-// with chunk = k / 128, g = (k % 128) / 8, half = g / 8, kk = g % 8.  Lane-half `half`
-// of k-step kk of a 128-wide chunk therefore carries k = chunk*128 + half*64 + kk*8 .. +7;
-// the packed weights use the same assignment, and any bijection is valid because the
-// MFMA sums over k.  MB = number of 32-row blocks (1, 2, 4 or 8).
+// ---- projection activations: "fragment-tiled" two-plane bf16 layout ----
+// An fp32 activation x is carried into the matrix cores as two bf16 values, hi = bf16(x) and
+// lo = bf16(x - hi) (16 significant bits together); the projection multiplies both planes with
+// the same weight fragment and adds the two results.  Rounding activations to a single bf16
+// would make the result depend on which way values near a rounding boundary fall, and a deep
+// stack amplifies that noise beyond the parity tolerance.
+// A [rows, K] is stored so that one staging step of the MFMA projection kernels is a linear
+// copy into LDS and each 16-byte unit (8 consecutive k of one row) is one lane's A operand of a
+// 32x32x16 MFMA.  With MB = number of 32-row blocks of real rows (1, 2, 4 or 8) the tiling has
+// 2*MB blocks, plane p of row block r at block p*MB + r:
+//   unit(p, b, k/8) = ((chunk * 8 + kk) * 2*MB + p*MB + b/32) * 64 + half * 32 + b%32
+// with chunk = k / 128, g = (k % 128) / 8, half = g / 8, kk = g % 8.  Lane-half `half` of k-step
+// kk of a 128-wide chunk therefore carries k = chunk*128 + half*64 + kk*8 .. +7; the packed
+// weights use the same assignment, and any bijection is valid because the MFMA sums over k.
 struct ATile {
     int MB;
 };
 __host__ __device__ __forceinline__ ATile atile_for_rows(int rows) {
     return ATile{rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 128 ? 4 : 8};
 }
-__host__ __device__ __forceinline__ size_t atile_unit(ATile t, int b, int k8) {
+__host__ __device__ __forceinline__ size_t atile_unit(ATile t, int plane, int b, int k8) {
     const int chunk = k8 >> 4, g = k8 & 15;
     const int half = g >> 3, kk = g & 7;
-    return ((size_t)(chunk * 8 + kk) * t.MB + (b >> 5)) * 64 + half * 32 + (b & 31);
+    return ((size_t)(chunk * 8 + kk) * (2 * t.MB) + plane * t.MB + (b >> 5)) * 64 + half * 32 + (b & 31);
 }
-__host__ __device__ __forceinline__ size_t atile_elem(ATile t, int b, int k) {
-    return atile_unit(t, b, k >> 3) * 8 + (k & 7);
+__host__ __device__ __forceinline__ size_t atile_elem(ATile t, int plane, int b, int k) {
+    return atile_unit(t, plane, b, k >> 3) * 8 + (k & 7);
 }
-__host__ __device__ __forceinline__ size_t atile_bytes(ATile t, int K) { return (size_t)t.MB * 32 * K * 2; }
+__host__ __device__ __forceinline__ size_t atile_bytes(ATile t, int K) { return (size_t)2 * t.MB * 32 * K * 2; }
+// hi/lo split of one value; returns hi bits, lo bits via reference
+__device__ __forceinline__ uint16_t split_bf16(float x, uint16_t& lo) {
+    const uint16_t hi = f32_to_bf16_bits(x);
+    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+    return hi;
+}
 
 // ---- wave reductions (all lanes receive the result; fixed order => deterministic) ----
 __device__ __forceinline__ float wave_sum(float v) {

@@ -111,13 +111,15 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(NormArgs a) {
                 *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8 + 4) = f32x4{y[4], y[5], y[6], y[7]};
             }
             if (a.h_tiled) {
-                u32x4 o;
+                u32x4 o, ol;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
-                    gsum += bf16_lo(o[e]) + bf16_hi(o[e]);
+                    ol[e] = pack_bf16(y[2 * e] - bf16_lo(o[e]), y[2 * e + 1] - bf16_hi(o[e]));
+                    gsum += (bf16_lo(o[e]) + bf16_lo(ol[e])) + (bf16_hi(o[e]) + bf16_hi(ol[e]));
                 }
-                reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, b, u)] = o;
+                reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, 0, b, u)] = o;
+                reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, 1, b, u)] = ol;
             }
         }
         if (a.hsum) {  // 16 consecutive units (lanes) form one 128-wide group
@@ -319,13 +321,15 @@ __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict_
     float gsum = 0.f;
     if (u < K / 8) {
         const float* p = x + (size_t)b * K + u * 8;
-        u32x4 o;
+        u32x4 o, ol;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             o[e] = pack_bf16(p[2 * e], p[2 * e + 1]);
-            gsum += bf16_lo(o[e]) + bf16_hi(o[e]);
+            ol[e] = pack_bf16(p[2 * e] - bf16_lo(o[e]), p[2 * e + 1] - bf16_hi(o[e]));
+            gsum += (bf16_lo(o[e]) + bf16_lo(ol[e])) + (bf16_hi(o[e]) + bf16_hi(ol[e]));
         }
-        tiled[atile_unit(ATile{mb}, b, u)] = o;
+        tiled[atile_unit(ATile{mb}, 0, b, u)] = o;
+        tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
     }
     if (hsum) {
         gsum += __shfl_xor(gsum, 1);
@@ -353,9 +357,10 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const u32x4* __restrict
     const int b = idx % rows, g = idx / rows;
     float s = 0.f;
     for (int u = 0; u < 16; ++u) {
-        const u32x4 w = tiled[atile_unit(ATile{mb}, b, g * 16 + u)];
+        const u32x4 w = tiled[atile_unit(ATile{mb}, 0, b, g * 16 + u)];
+        const u32x4 wl = tiled[atile_unit(ATile{mb}, 1, b, g * 16 + u)];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) s += bf16_lo(w[e]) + bf16_hi(w[e]);
+        for (int e = 0; e < 4; ++e) s += (bf16_lo(w[e]) + bf16_lo(wl[e])) + (bf16_hi(w[e]) + bf16_hi(wl[e]));
     }
     hsum[(size_t)g * (mb * 32) + b] = s;
 }
@@ -388,7 +393,8 @@ __global__ __launch_bounds__(256) void untile_rows_kernel(const uint16_t* __rest
                                                           float* __restrict__ out) {
     const int b = blockIdx.y, k = blockIdx.x * 256 + threadIdx.x;
     if (k >= K) return;
-    out[(size_t)b * K + k] = bf16_bits_to_f32(tiled[atile_elem(ATile{mb}, b, k)]);
+    out[(size_t)b * K + k] = bf16_bits_to_f32(tiled[atile_elem(ATile{mb}, 0, b, k)]) +
+                             bf16_bits_to_f32(tiled[atile_elem(ATile{mb}, 1, b, k)]);
 }
 
 hipError_t launch_untile_rows(const void* tiled, int rows, int K, float* out, hipStream_t st) {

@@ -33,12 +33,18 @@ struct ProjArgs {
     int rows, N, K;
     int n_stages, stages_per_split;
     int ldo, ld_rows;
-    int mb_total;  // 32-row blocks in the activation tiling
-    int out_mb;    // tiling of out_tiled
+    int mb_rows;   // 32-row blocks of real rows in the activation tiling (it holds twice as many: hi and lo plane)
+    int out_mb;    // row blocks of out_tiled
 };
 
+// MB counts the 32-row operand blocks of the workgroup: MR = MB/2 blocks of rows, each present
+// as a hi and a lo bf16 plane (operand block m < MR is the hi plane of row block m, block MR+m
+// its lo plane); both are multiplied with the same weight fragment and added at the end.
 template <int MB, int KS, int NW, int EPI, bool W4, int NBUF>
-__global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB <= 4 ? 2 : 1, MB <= 4 ? 2 : 1)))
+void proj_kernel(ProjArgs a) {
+    constexpr int MR = MB / 2;
+    static_assert(MB % 2 == 0, "operand blocks come in hi/lo pairs");
     constexpr int KK = KS / 16;                // MFMA k-steps per stage
     constexpr int STAGE_UNITS = KK * MB * 64;  // 16-byte units of activations per stage
     constexpr int NT = NW * 64;
@@ -47,9 +53,9 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     constexpr int WREGS = W4 ? KK / 4 : KK;    // 16-byte weight loads per lane per stage
 
     __shared__ u32x4 lds[NBUF][STAGE_UNITS];  // ring of staged activation tiles (prefetch distance NBUF-1)
-    float* hs_lds = nullptr;  // W4: [4][MB*32] group sums of the activations, ring indexed by chunk
+    float* hs_lds = nullptr;  // W4: [4][MR*32] group sums of the activations, ring indexed by chunk
     if constexpr (W4) {
-        __shared__ __attribute__((aligned(16))) float hs_store[4 * MB * 32];
+        __shared__ __attribute__((aligned(16))) float hs_store[4 * MR * 32];
         hs_lds = hs_store;
     }
 
@@ -57,7 +63,7 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     const int nb = blockIdx.x * NW + wave;
     const bool active = nb < a.N / 32;
     const int split = blockIdx.y;
-    const int mb_off = blockIdx.z * MB;
+    const int mb_off = blockIdx.z * MR;  // first row block of this workgroup
     const int s0 = split * a.stages_per_split;
     const int s1 = min(a.n_stages, s0 + a.stages_per_split);
     const int kch = a.K / 128;
@@ -66,10 +72,11 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * (W4 ? 2 : 8) * 64 + lane;
     const uint32_t* SZl = W4 ? a.SZ + ((size_t)(active ? nb : 0) * kch) * 32 + (lane & 31) : nullptr;
 
-    f32x16 acc[MB];
+    constexpr int NACC = W4 ? MR : MB;  // W4 folds hi and lo when it scales a group
+    f32x16 acc[NACC];
     f32x16 accg[W4 ? MB : 1];
 #pragma unroll
-    for (int m = 0; m < MB; ++m)
+    for (int m = 0; m < NACC; ++m)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
 
@@ -87,15 +94,17 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
         for (int i = 0; i < UPT; ++i) {
             const int u = i * NT + tid;
             const int kk = u / (MB * 64), rem = u % (MB * 64);
-            areg[i] = a.A[((size_t)(st * KK + kk) * a.mb_total + mb_off) * 64 + rem];
+            const int m = rem >> 6;  // operand block: hi plane of row block m, or lo plane of row block m - MR
+            const int gb = m < MR ? mb_off + m : a.mb_rows + mb_off + (m - MR);
+            areg[i] = a.A[((size_t)(st * KK + kk) * (2 * a.mb_rows) + gb) * 64 + (rem & 63)];
         }
-        if (W4 && ((st * KK) & 7) == 0 && tid < MB * 32)
-            hreg = a.hsum[(size_t)((st * KK) >> 3) * (a.mb_total * 32) + mb_off * 32 + tid];
+        if (W4 && ((st * KK) & 7) == 0 && tid < MR * 32)
+            hreg = a.hsum[(size_t)((st * KK) >> 3) * (a.mb_rows * 32) + mb_off * 32 + tid];
     };
     auto store_a = [&](int buf, int st) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i) lds[buf][i * NT + tid] = areg[i];
-        if (W4 && ((st * KK) & 7) == 0 && tid < MB * 32) hs_lds[(((st * KK) >> 3) & 3) * MB * 32 + tid] = hreg;
+        if (W4 && ((st * KK) & 7) == 0 && tid < MR * 32) hs_lds[(((st * KK) >> 3) & 3) * MR * 32 + tid] = hreg;
     };
     auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
         const bool first = (KS == 128) || ((st & 1) == 0);
@@ -132,15 +141,17 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
         if (W4 && last) {
             const __half2 h2 = __builtin_bit_cast(__half2, sz);
             const float s = __low2float(h2), nzz = -(128.f + __high2float(h2));
-            const float* hs = hs_lds + (((st * KK) >> 3) & 3) * MB * 32;
+            const float* hs = hs_lds + (((st * KK) >> 3) & 3) * MR * 32;
 #pragma unroll
-            for (int m = 0; m < MB; ++m)
+            for (int m = 0; m < MR; ++m)
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs + m * 32 + 8 * rr + 4 * half);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        acc[m][rr * 4 + q] = fmaf(s, fmaf(nzz, h4[q], accg[m][rr * 4 + q]), acc[m][rr * 4 + q]);
+                    for (int q = 0; q < 4; ++q) {
+                        const float g = accg[m][rr * 4 + q] + accg[MR + m][rr * 4 + q];  // hi + lo plane
+                        acc[m][rr * 4 + q] = fmaf(s, fmaf(nzz, h4[q], g), acc[m][rr * 4 + q]);
+                    }
                 }
         }
     };
@@ -199,10 +210,16 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
     if (!active) return;
 
     const int col = lane & 31;
+    if constexpr (!W4) {  // add the lo-plane products to the hi-plane products
+#pragma unroll
+        for (int m = 0; m < MR; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][r] += acc[MR + m][r];
+    }
     if (EPI == EPI_STORE) {
         float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
 #pragma unroll
-        for (int m = 0; m < MB; ++m)
+        for (int m = 0; m < MR; ++m)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -212,7 +229,7 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
         const ATile ot{a.out_mb};
         const int ucol = nb * 16 + (lane & 15);
 #pragma unroll
-        for (int m = 0; m < MB; ++m)
+        for (int m = 0; m < MR; ++m)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float v = acc[m][r];
@@ -220,7 +237,10 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
                 const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 if ((lane & 16) == 0 && b < a.rows) {
                     const float y = v / (1.f + __expf(-v)) * other;
-                    a.out_tiled[atile_elem(ot, b, ucol)] = f32_to_bf16_bits(y);
+                    uint16_t lo;
+                    const uint16_t hi = split_bf16(y, lo);
+                    a.out_tiled[atile_elem(ot, 0, b, ucol)] = hi;
+                    a.out_tiled[atile_elem(ot, 1, b, ucol)] = lo;
                 }
             }
     }
@@ -229,7 +249,7 @@ __global__ __launch_bounds__(NW * 64) void proj_kernel(ProjArgs a) {
 template <int MB, int KS, bool W4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
     constexpr int NW = 4;
-    constexpr int NBUF = (MB * KS * 4 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
+    constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
     if (epilogue == EPI_STORE)
         hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4, NBUF>), grid, block, 0, st, a);
@@ -270,7 +290,7 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     a.K = W.K;
     a.ldo = p.ldo;
     a.ld_rows = p.ld_rows;
-    a.mb_total = at.MB;
+    a.mb_rows = at.MB;
     a.out_mb = at.MB;
     const int kch = W.K / 128;
     int splits = p.epilogue == EPI_STORE ? max(1, p.splits) : 1;
@@ -278,22 +298,20 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     splits = (kch + cps - 1) / cps;
     const int mb = at.MB;
     if (w4 && p.hsum == nullptr) return hipErrorInvalidValue;
-    // stage width: 128 for up to 64 rows, 64 above (LDS budget)
-    if (mb <= 2) {
+    // operand blocks = 2 * row blocks (hi and lo plane); stage width 128 up to 32 rows, 64 above (LDS budget)
+    if (mb == 1) {
         a.n_stages = kch;
         a.stages_per_split = cps;
-        if (mb == 1) return w4 ? launch_proj_t<1, 128, true>(a, p.epilogue, splits, 1, st)
-                               : launch_proj_t<1, 128, false>(a, p.epilogue, splits, 1, st);
         return w4 ? launch_proj_t<2, 128, true>(a, p.epilogue, splits, 1, st)
                   : launch_proj_t<2, 128, false>(a, p.epilogue, splits, 1, st);
     }
     a.n_stages = kch * 2;
     a.stages_per_split = cps * 2;
-    if (mb == 4) return w4 ? launch_proj_t<4, 64, true>(a, p.epilogue, splits, 1, st)
+    if (mb == 2) return w4 ? launch_proj_t<4, 64, true>(a, p.epilogue, splits, 1, st)
                            : launch_proj_t<4, 64, false>(a, p.epilogue, splits, 1, st);
-    // 256 rows: bf16 covers them in one pass; W4 runs two 128-row tiles (accumulator budget)
-    return w4 ? launch_proj_t<4, 64, true>(a, p.epilogue, splits, 2, st)
-              : launch_proj_t<8, 64, false>(a, p.epilogue, splits, 1, st);
+    // more than 64 rows: 128-row tiles (8 operand blocks, the accumulator budget); 256 rows run as two tiles
+    return w4 ? launch_proj_t<8, 64, true>(a, p.epilogue, splits, mb / 4, st)
+              : launch_proj_t<8, 64, false>(a, p.epilogue, splits, mb / 4, st);
 }
 
 // ---------------------------------------------------------------------------------

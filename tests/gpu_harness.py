@@ -68,6 +68,9 @@ class SharedWeights:
             qnp = None
             if self.quant is not None:
                 qnp = {k: [tuple(to_np(t) for t in trip) for trip in v] for k, v in self.quant.items()}
+                for k, v in qnp.items():   # dense sources may have been released: only their width is needed
+                    if k not in wnp:
+                        wnp[k] = [np.empty((0, 2 * trip[0].shape[1]), np.float32) for trip in v]
             self._keep = (wnp, qnp)
             self._params = orc.params_from_arrays(wnp, qnp)
         return self._params
@@ -164,7 +167,7 @@ def run_oracle(case: GpuCase, rows: Sequence[int], params=None, tokens=None, len
     rows = list(rows)
     host, pool, tabs, used = case.extract_pool(rows)
     params = params if params is not None else case.oracle_params()
-    ocfg = orc.make_cfg(work.shape, act_bf16=(work.dtype == "bf16"))
+    ocfg = orc.make_cfg(work.shape)
     toks = (work.tokens if tokens is None else tokens)[rows]
     ln = (work.seq_lens if lens is None else lens)[rows]
     mi = (work.model_ids if ids is None else ids)[rows]

@@ -147,7 +147,7 @@ def test_linear_op_bf16(H, batch):
         out = torch.full((batch, N), float("nan"), device=H.DEV)
         sun.sun_linear(W, 1, mat, x, out, ws)
         torch.cuda.synchronize()
-        xr = x.to(torch.bfloat16).double().cpu().numpy()       # the kernel rounds its input to bf16
+        xr = x.double().cpu().numpy()       # activations enter the matrix cores as hi+lo bf16 (16 significant bits)
         lin = lambda key: orc.linear(orc.dense_mat(wn[key][1] if isinstance(wn[key], list) else wn[key]), xr)
         if mat == 0:
             want = np.concatenate([lin("wq"), lin("wk"), lin("wv")], axis=1)
@@ -182,7 +182,7 @@ def test_linear_op_w4(H, batch):
         out = torch.full((batch, N), float("nan"), device=H.DEV)
         sun.sun_linear(W, 0, mat, x, out, ws)
         torch.cuda.synchronize()
-        xr = x.to(torch.bfloat16).double().cpu().numpy()
+        xr = x.double().cpu().numpy()
         if mat == 0:
             want = np.concatenate([qlin("wq", xr), qlin("wk", xr), qlin("wv", xr)], axis=1)
         elif mat == 2:
