@@ -12,7 +12,7 @@ from typing import Dict, List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsun.so")
+LIB_PATH = os.environ.get("SUN_LIB_PATH", os.path.join(_HERE, "libsun.so"))  # override: another build of libsun
 
 SUN_F32, SUN_BF16 = 0, 1
 SUN_VALIDATE, SUN_PROFILE = 1, 2

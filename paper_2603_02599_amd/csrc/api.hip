@@ -90,6 +90,7 @@ struct Workspace {
 };
 
 constexpr int kMaxSplits = 16;
+constexpr int kMaxSplitsWide = 4;   // gate/up (2*ffn columns)
 
 static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* base) {
     Workspace w{};
@@ -110,7 +111,7 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
         w.aA = take(atile_bytes(ATile{mb}, QD));
         w.uA = take(atile_bytes(ATile{mb}, F));
         w.hs = (float*)take((size_t)(std::max(std::max(H, QD), F) / 128 + 1) * mb * 32 * 4);
-        w.part = (float*)take((size_t)kMaxSplits * batch * std::max(Nqkv, H) * 4);
+        w.part = (float*)take(std::max((size_t)kMaxSplits * batch * std::max(Nqkv, H), (size_t)kMaxSplitsWide * batch * 2 * F) * 4);
     } else {
         w.h32 = (float*)take((size_t)batch * H * 4);
         w.a32 = (float*)take((size_t)batch * QD * 4);
@@ -602,14 +603,15 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
                 SUN_HIP_CHECK(launch_residual_norm(c, ws.x, ws.part, so, batch, L.g2, batch, nullptr, ws.hA,
                                                    W.quant ? ws.hs : nullptr, st));
             }
+            const int sg = proj_pick_splits(L.gu, batch, kMaxSplitsWide);
             {
                 ProfScope p(prof, 4, st);
-                ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_SWIGLU, 1, nullptr, 0, batch, ws.uA};
+                ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch, nullptr};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
-            if (W.quant) {
+            {
                 ProfScope p(prof, 7, st);
-                SUN_HIP_CHECK(launch_group_sums(ws.uA, batch, c.ffn, ws.hs, st));
+                SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, W.quant ? ws.hs : nullptr, st));
             }
             const int sd = proj_pick_splits(L.down, batch, kMaxSplits);
             {
@@ -712,8 +714,10 @@ int sun_linear(const sun_weights* weights_, int layer, int mat, int batch, const
     const bool w4 = M.kind == MAT_W4_PACKED;
     SUN_HIP_CHECK(launch_tile_rows(x, batch, M.K, in, w4 ? ws.hs : nullptr, st));
     if (mat == 2) {
-        ProjLaunch pl{&M, in, ws.hs, batch, EPI_SWIGLU, 1, nullptr, 0, batch, ws.uA};
+        const int s = proj_pick_splits(M, batch, kMaxSplitsWide);
+        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch, nullptr};
         SUN_HIP_CHECK(launch_proj(pl, st));
+        SUN_HIP_CHECK(launch_swiglu_tile(ws.part, s, batch, batch, c.ffn, ws.uA, nullptr, st));
         SUN_HIP_CHECK(launch_untile_rows(ws.uA, batch, c.ffn, out, st));
     } else if (mat == 4) {
         ProjLaunch pl{&M, in, nullptr, batch, EPI_STORE, 1, out, M.N, batch, nullptr};

@@ -8,7 +8,7 @@ namespace sun {
 
 enum ProjEpilogue {
     EPI_STORE = 0,   // fp32 partial sums: out[(split * ld_rows + b) * ldo + n]
-    EPI_SWIGLU = 1   // rows of W interleave 16 gate / 16 up; writes silu(g)*u as tiled bf16
+    EPI_SWIGLU = 1   // (unused by the step) single-split gate/up with the activation fused
 };
 
 struct ProjLaunch {
@@ -78,6 +78,9 @@ hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, i
                               const float* table, const int32_t* seq_lens, const int32_t* page_tables, int max_pages,
                               int batch, float* q_out, hipStream_t st);
 hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipStream_t st);
+// gate/up partial sums (projection column order) -> silu(g)*u as two-plane tiled bf16 (+ group sums)
+hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,
+                              hipStream_t st);
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next, hipStream_t st);
 // fp32 [rows, K] -> tiled bf16 (+ group sums)
 hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st);

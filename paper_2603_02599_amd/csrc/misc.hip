@@ -269,6 +269,60 @@ hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipS
     return hipGetLastError();
 }
 
+// ---------------- SwiGLU over the gate/up projection's partial sums ----------------
+// part: [nparts][ld_rows][2*ffn] fp32 with the projection's column order (blocks of 16 gate
+// columns followed by their 16 up columns).  Writes u = silu(sum g) * (sum u) as two-plane tiled
+// bf16 [rows, ffn] and, if asked, the per-128 group sums the 4-bit projection needs.
+__global__ __launch_bounds__(256) void swiglu_tile_kernel(const float* __restrict__ part, int nparts, int ld_rows,
+                                                          int ffn, int mb, u32x4* __restrict__ tiled,
+                                                          float* __restrict__ hsum) {
+    const int b = blockIdx.y, u = blockIdx.x * 256 + threadIdx.x;  // unit = 8 consecutive u columns
+    float gsum = 0.f;
+    if (u < ffn / 8) {
+        const int j = u * 8;
+        const float* p = part + (size_t)b * 2 * ffn + (j >> 4) * 32 + (j & 15);
+        const size_t slab = (size_t)ld_rows * 2 * ffn;
+        f32x4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = g0, u0 = g0, u1 = g0;
+        for (int s = 0; s < nparts; ++s) {  // slabs in ascending order
+            g0 += *reinterpret_cast<const f32x4*>(p + s * slab);
+            g1 += *reinterpret_cast<const f32x4*>(p + s * slab + 4);
+            u0 += *reinterpret_cast<const f32x4*>(p + s * slab + 16);
+            u1 += *reinterpret_cast<const f32x4*>(p + s * slab + 20);
+        }
+        float y[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            y[e] = g0[e] / (1.f + __expf(-g0[e])) * u0[e];
+            y[4 + e] = g1[e] / (1.f + __expf(-g1[e])) * u1[e];
+        }
+        u32x4 o, ol;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
+            ol[e] = pack_bf16(y[2 * e] - bf16_lo(o[e]), y[2 * e + 1] - bf16_hi(o[e]));
+            gsum += (bf16_lo(o[e]) + bf16_lo(ol[e])) + (bf16_hi(o[e]) + bf16_hi(ol[e]));
+        }
+        tiled[atile_unit(ATile{mb}, 0, b, u)] = o;
+        tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
+    }
+    if (hsum) {
+        gsum += __shfl_xor(gsum, 1);
+        gsum += __shfl_xor(gsum, 2);
+        gsum += __shfl_xor(gsum, 4);
+        gsum += __shfl_xor(gsum, 8);
+        if (u < ffn / 8 && (threadIdx.x & 15) == 0) hsum[(size_t)(u >> 4) * (mb * 32) + b] = gsum;
+    }
+}
+
+hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,
+                              hipStream_t st) {
+    if (ffn % 128) return hipErrorInvalidValue;
+    const int mb = atile_for_rows(rows).MB;
+    hipLaunchKernelGGL(swiglu_tile_kernel, dim3((ffn / 8 + 255) / 256, rows), dim3(256), 0, st, part, nparts, ld_rows, ffn,
+                       mb, (u32x4*)tiled, hsum);
+    return hipGetLastError();
+}
+
 // ---------------- greedy argmax, lowest index on ties ----------------
 __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ next) {
     __shared__ float bv[16];

@@ -39,7 +39,7 @@ struct ProjArgs {
 
 // MB counts the 32-row operand blocks of the workgroup: MR = MB/2 blocks of rows, each present
 // as a hi and a lo bf16 plane (operand block m < MR is the hi plane of row block m, block MR+m
-// its lo plane); both are multiplied with the same weight fragment and added at the end.
+// its lo plane); both are multiplied with the same weight fragment into the same accumulator.
 template <int MB, int KS, int NW, int EPI, bool W4, int NBUF>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB <= 4 ? 2 : 1, MB <= 4 ? 2 : 1)))
 void proj_kernel(ProjArgs a) {
@@ -72,11 +72,10 @@ void proj_kernel(ProjArgs a) {
     const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * (W4 ? 2 : 8) * 64 + lane;
     const uint32_t* SZl = W4 ? a.SZ + ((size_t)(active ? nb : 0) * kch) * 32 + (lane & 31) : nullptr;
 
-    constexpr int NACC = W4 ? MR : MB;  // W4 folds hi and lo when it scales a group
-    f32x16 acc[NACC];
-    f32x16 accg[W4 ? MB : 1];
+    f32x16 acc[MR];
+    f32x16 accg[W4 ? MR : 1];
 #pragma unroll
-    for (int m = 0; m < NACC; ++m)
+    for (int m = 0; m < MR; ++m)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
 
@@ -109,8 +108,17 @@ void proj_kernel(ProjArgs a) {
     auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
         const bool first = (KS == 128) || ((st & 1) == 0);
         const bool last = (KS == 128) || ((st & 1) == 1);
+        // A operands are read from LDS one k-step ahead of the MFMAs that use them
+        u32x4 afr[2][MB];
+#pragma unroll
+        for (int m = 0; m < MB; ++m) afr[0][m] = lds[buf][m * 64 + lane];
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
+            if (kk + 1 < KK) {
+#pragma unroll
+                for (int m = 0; m < MB; ++m) afr[(kk + 1) & 1][m] = lds[buf][((kk + 1) * MB + m) * 64 + lane];
+            }
+            __builtin_amdgcn_sched_barrier(0);
             bf16x8 bfrag;
             if (W4) {
                 const uint32_t word = w[kk >> 2][kk & 3];
@@ -122,21 +130,23 @@ void proj_kernel(ProjArgs a) {
                 bfrag = __builtin_bit_cast(bf16x8, w[kk]);
             }
 #pragma unroll
-            for (int m = 0; m < MB; ++m) {
-                const bf16x8 afrag = __builtin_bit_cast(bf16x8, lds[buf][(kk * MB + m) * 64 + lane]);
-                if (W4) {
-                    if (first && kk == 0) {
-                        f32x16 zero;
+            for (int pl = 0; pl < 2; ++pl)  // hi plane, then lo plane, into the same accumulators
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-                        accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, zero, 0, 0, 0);
+                for (int m = 0; m < MR; ++m) {
+                    const bf16x8 afrag = __builtin_bit_cast(bf16x8, afr[kk & 1][pl * MR + m]);
+                    if (W4) {
+                        if (first && kk == 0 && pl == 0) {
+                            f32x16 zero;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                            accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, zero, 0, 0, 0);
+                        } else {
+                            accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, accg[m], 0, 0, 0);
+                        }
                     } else {
-                        accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, accg[m], 0, 0, 0);
+                        acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[m], 0, 0, 0);
                     }
-                } else {
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[m], 0, 0, 0);
                 }
-            }
         }
         if (W4 && last) {
             const __half2 h2 = __builtin_bit_cast(__half2, sz);
@@ -148,10 +158,8 @@ void proj_kernel(ProjArgs a) {
                 for (int rr = 0; rr < 4; ++rr) {
                     const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs + m * 32 + 8 * rr + 4 * half);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float g = accg[m][rr * 4 + q] + accg[MR + m][rr * 4 + q];  // hi + lo plane
-                        acc[m][rr * 4 + q] = fmaf(s, fmaf(nzz, h4[q], g), acc[m][rr * 4 + q]);
-                    }
+                    for (int q = 0; q < 4; ++q)
+                        acc[m][rr * 4 + q] = fmaf(s, fmaf(nzz, h4[q], accg[m][rr * 4 + q]), acc[m][rr * 4 + q]);
                 }
         }
     };
@@ -210,12 +218,6 @@ void proj_kernel(ProjArgs a) {
     if (!active) return;
 
     const int col = lane & 31;
-    if constexpr (!W4) {  // add the lo-plane products to the hi-plane products
-#pragma unroll
-        for (int m = 0; m < MR; ++m)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[m][r] += acc[MR + m][r];
-    }
     if (EPI == EPI_STORE) {
         float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
 #pragma unroll
@@ -248,7 +250,10 @@ void proj_kernel(ProjArgs a) {
 
 template <int MB, int KS, bool W4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
-    constexpr int NW = 4;
+#ifndef SUN_PROJ_NW
+#define SUN_PROJ_NW 4
+#endif
+    constexpr int NW = MB <= 4 ? SUN_PROJ_NW : 4;
     constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
     if (epilogue == EPI_STORE)
@@ -261,7 +266,8 @@ static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int
 static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / splits; }
 
 int proj_pick_splits(const Mat& W, int rows, int max_splits) {
-    const int tiles = (W.N / 32 + 3) / 4, kch = W.K / 128;
+    const int nw = rows <= 64 ? SUN_PROJ_NW : 4;
+    const int tiles = (W.N / 32 + nw - 1) / nw, kch = W.K / 128;
     static const int env_target = getenv("SUN_SPLIT_TARGET") ? atoi(getenv("SUN_SPLIT_TARGET")) : 0;
     const int target = env_target ? env_target : 256;
     int s = (target + tiles - 1) / tiles;
