@@ -565,7 +565,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             const int sq = proj_pick_splits(L.qkv, batch, kMaxSplits);
             {
                 ProfScope p(prof, 2, st);
-                ProjLaunch pl{&L.qkv, ws.hA, ws.hs, batch, EPI_STORE, sq, ws.part, L.qkv.N, batch, nullptr};
+                ProjLaunch pl{&L.qkv, ws.hA, ws.hs, batch, EPI_STORE, sq, ws.part, L.qkv.N, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             {
@@ -595,7 +595,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             const int so = proj_pick_splits(L.o, batch, kMaxSplits);
             {
                 ProfScope p(prof, 3, st);
-                ProjLaunch pl{&L.o, ws.aA, ws.hs, batch, EPI_STORE, so, ws.part, H, batch, nullptr};
+                ProjLaunch pl{&L.o, ws.aA, ws.hs, batch, EPI_STORE, so, ws.part, H, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             {
@@ -606,7 +606,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             const int sg = proj_pick_splits(L.gu, batch, kMaxSplitsWide);
             {
                 ProfScope p(prof, 4, st);
-                ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch, nullptr};
+                ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             {
@@ -616,7 +616,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             const int sd = proj_pick_splits(L.down, batch, kMaxSplits);
             {
                 ProfScope p(prof, 5, st);
-                ProjLaunch pl{&L.down, ws.uA, ws.hs, batch, EPI_STORE, sd, ws.part, H, batch, nullptr};
+                ProjLaunch pl{&L.down, ws.uA, ws.hs, batch, EPI_STORE, sd, ws.part, H, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             down_parts = sd;
@@ -637,7 +637,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
     {
         ProfScope p(prof, 6, st);
         if (bf) {
-            ProjLaunch pl{&W.lm, ws.hA, nullptr, batch, EPI_STORE, 1, logits, c.vocab, batch, nullptr};
+            ProjLaunch pl{&W.lm, ws.hA, nullptr, batch, EPI_STORE, 1, logits, c.vocab, batch};
             SUN_HIP_CHECK(launch_proj(pl, st));
         } else {
             SUN_HIP_CHECK(launch_proj_f32(W.lm, ws.h32, batch, logits, st));
@@ -715,16 +715,16 @@ int sun_linear(const sun_weights* weights_, int layer, int mat, int batch, const
     SUN_HIP_CHECK(launch_tile_rows(x, batch, M.K, in, w4 ? ws.hs : nullptr, st));
     if (mat == 2) {
         const int s = proj_pick_splits(M, batch, kMaxSplitsWide);
-        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch, nullptr};
+        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch};
         SUN_HIP_CHECK(launch_proj(pl, st));
         SUN_HIP_CHECK(launch_swiglu_tile(ws.part, s, batch, batch, c.ffn, ws.uA, nullptr, st));
         SUN_HIP_CHECK(launch_untile_rows(ws.uA, batch, c.ffn, out, st));
     } else if (mat == 4) {
-        ProjLaunch pl{&M, in, nullptr, batch, EPI_STORE, 1, out, M.N, batch, nullptr};
+        ProjLaunch pl{&M, in, nullptr, batch, EPI_STORE, 1, out, M.N, batch};
         SUN_HIP_CHECK(launch_proj(pl, st));
     } else {
         const int s = proj_pick_splits(M, batch, kMaxSplits);
-        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch, nullptr};
+        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch};
         SUN_HIP_CHECK(launch_proj(pl, st));
         SUN_HIP_CHECK(launch_reduce_partials(ws.part, s, batch, batch, M.N, out, st));
     }

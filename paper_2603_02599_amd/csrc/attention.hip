@@ -160,22 +160,11 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
         int pB = __builtin_amdgcn_readlane(recv, 2 * pp + 1);
         if (pB < 0) pB = pA;
         const uint16_t* kp = a.kbase + head * a.k_head + (int64_t)(k_psel ? pB : pA) * a.k_page + k_lane_off;
-#ifdef SUN_EXP_KCONTIG
-        const uint16_t* ka_ = a.kbase + head * a.k_head + (int64_t)pA * a.k_page + lane * 8;
-        const uint16_t* kb_ = a.kbase + head * a.k_head + (int64_t)pB * a.k_page + lane * 8;
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            kr[0][s] = *reinterpret_cast<const u32x4*>(ka_ + s * 512);
-            kr[1][s] = *reinterpret_cast<const u32x4*>(kb_ + s * 512);
-        }
-        (void)kp;
-#else
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             kr[0][s] = *reinterpret_cast<const u32x4*>(kp + s * 32);
             kr[1][s] = *reinterpret_cast<const u32x4*>(kp + 4 * D + s * 32);
         }
-#endif
     };
     auto load_v = [&](int recv, int head, int pp) {
         const int pA = __builtin_amdgcn_readlane(recv, 2 * pp);

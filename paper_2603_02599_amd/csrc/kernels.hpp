@@ -7,8 +7,7 @@ namespace sun {
 // ---------------- projections (proj.hip) ----------------
 
 enum ProjEpilogue {
-    EPI_STORE = 0,   // fp32 partial sums: out[(split * ld_rows + b) * ldo + n]
-    EPI_SWIGLU = 1   // (unused by the step) single-split gate/up with the activation fused
+    EPI_STORE = 0    // fp32 partial sums: out[(split * ld_rows + b) * ldo + n]
 };
 
 struct ProjLaunch {
@@ -21,7 +20,6 @@ struct ProjLaunch {
     float* out;
     int ldo;               // leading dimension of out (>= N)
     int ld_rows;           // rows per split slab
-    void* out_tiled;       // EPI_SWIGLU: tiled bf16 [rows, N/2]
 };
 // Chooses the split-K factor the step uses for this matrix and row count.
 int proj_pick_splits(const Mat& W, int rows, int max_splits);
@@ -84,8 +82,6 @@ hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int ro
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next, hipStream_t st);
 // fp32 [rows, K] -> tiled bf16 (+ group sums)
 hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st);
-// group sums of an already tiled bf16 activation matrix
-hipError_t launch_group_sums(const void* tiled, int rows, int K, float* hsum, hipStream_t st);
 // out[b][n] = sum_s partial[s][b][n]
 hipError_t launch_reduce_partials(const float* partial, int nparts, int ld_rows, int rows, int N, float* out,
                                   hipStream_t st);

@@ -402,31 +402,6 @@ hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float*
     return hipGetLastError();
 }
 
-// one thread per (row, group): sums the 128 bf16 values of the group
-__global__ __launch_bounds__(256) void group_sums_kernel(const u32x4* __restrict__ tiled, int rows, int K, int mb,
-                                                         float* __restrict__ hsum) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    const int ng = K / 128;
-    if (idx >= rows * ng) return;
-    const int b = idx % rows, g = idx / rows;
-    float s = 0.f;
-    for (int u = 0; u < 16; ++u) {
-        const u32x4 w = tiled[atile_unit(ATile{mb}, 0, b, g * 16 + u)];
-        const u32x4 wl = tiled[atile_unit(ATile{mb}, 1, b, g * 16 + u)];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) s += (bf16_lo(w[e]) + bf16_lo(wl[e])) + (bf16_hi(w[e]) + bf16_hi(wl[e]));
-    }
-    hsum[(size_t)g * (mb * 32) + b] = s;
-}
-
-hipError_t launch_group_sums(const void* tiled, int rows, int K, float* hsum, hipStream_t st) {
-    const int mb = atile_for_rows(rows).MB;
-    const int total = rows * (K / 128);
-    hipLaunchKernelGGL(group_sums_kernel, dim3((total + 255) / 256), dim3(256), 0, st, (const u32x4*)tiled, rows, K, mb,
-                       hsum);
-    return hipGetLastError();
-}
-
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts,
                                                               int ld_rows, int N, float* __restrict__ out) {
     const int b = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;

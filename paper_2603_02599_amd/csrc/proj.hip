@@ -15,7 +15,6 @@
 // which equals sum_k (q_k - Z) S x_k up to fp32 rounding; the integer grid is never
 // rounded.  sum_k x_k per group comes from the activation producer.
 #include <hip/hip_fp16.h>
-#include <stdlib.h>
 
 #include "kernels.hpp"
 
@@ -29,12 +28,10 @@ struct ProjArgs {
     const u32x4* A;
     const float* hsum;
     float* out;
-    uint16_t* out_tiled;
     int rows, N, K;
     int n_stages, stages_per_split;
     int ldo, ld_rows;
     int mb_rows;   // 32-row blocks of real rows in the activation tiling (it holds twice as many: hi and lo plane)
-    int out_mb;    // row blocks of out_tiled
 };
 
 // MB counts the 32-row operand blocks of the workgroup: MR = MB/2 blocks of rows, each present
@@ -218,7 +215,7 @@ void proj_kernel(ProjArgs a) {
     if (!active) return;
 
     const int col = lane & 31;
-    if (EPI == EPI_STORE) {
+    {
         float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
 #pragma unroll
         for (int m = 0; m < MR; ++m)
@@ -227,49 +224,24 @@ void proj_kernel(ProjArgs a) {
                 const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 if (b < a.rows) o[(size_t)b * a.ldo] = acc[m][r];
             }
-    } else {
-        const ATile ot{a.out_mb};
-        const int ucol = nb * 16 + (lane & 15);
-#pragma unroll
-        for (int m = 0; m < MR; ++m)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float v = acc[m][r];
-                const float other = __shfl_xor(v, 16);
-                const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                if ((lane & 16) == 0 && b < a.rows) {
-                    const float y = v / (1.f + __expf(-v)) * other;
-                    uint16_t lo;
-                    const uint16_t hi = split_bf16(y, lo);
-                    a.out_tiled[atile_elem(ot, 0, b, ucol)] = hi;
-                    a.out_tiled[atile_elem(ot, 1, b, ucol)] = lo;
-                }
-            }
     }
 }
 
 template <int MB, int KS, bool W4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
-#ifndef SUN_PROJ_NW
-#define SUN_PROJ_NW 4
-#endif
-    constexpr int NW = MB <= 4 ? SUN_PROJ_NW : 4;
+    constexpr int NW = 4;
     constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
-    if (epilogue == EPI_STORE)
-        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4, NBUF>), grid, block, 0, st, a);
-    else
-        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, W4, NBUF>), grid, block, 0, st, a);
+    if (epilogue != EPI_STORE) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4, NBUF>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 
 static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / splits; }
 
 int proj_pick_splits(const Mat& W, int rows, int max_splits) {
-    const int nw = rows <= 64 ? SUN_PROJ_NW : 4;
-    const int tiles = (W.N / 32 + nw - 1) / nw, kch = W.K / 128;
-    static const int env_target = getenv("SUN_SPLIT_TARGET") ? atoi(getenv("SUN_SPLIT_TARGET")) : 0;
-    const int target = env_target ? env_target : 256;
+    const int tiles = (W.N / 32 + 3) / 4, kch = W.K / 128;
+    const int target = 256;  // about one workgroup per CU; more splits cost more in the consumer than they gain
     int s = (target + tiles - 1) / tiles;
     s = min(s, max_splits);
     s = min(s, max(1, kch / 2));
@@ -290,16 +262,14 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     a.A = (const u32x4*)p.A;
     a.hsum = p.hsum;
     a.out = p.out;
-    a.out_tiled = (uint16_t*)p.out_tiled;
     a.rows = p.rows;
     a.N = W.N;
     a.K = W.K;
     a.ldo = p.ldo;
     a.ld_rows = p.ld_rows;
     a.mb_rows = at.MB;
-    a.out_mb = at.MB;
     const int kch = W.K / 128;
-    int splits = p.epilogue == EPI_STORE ? max(1, p.splits) : 1;
+    int splits = max(1, p.splits);
     const int cps = chunks_per_split(kch, splits);
     splits = (kch + cps - 1) / cps;
     const int mb = at.MB;

@@ -60,10 +60,12 @@ TINY = Shape("tiny", 2, 256, 4, 2, 64, 688, 1024)
 TINY_Q = Shape("tiny_q", 2, 256, 4, 2, 64, 768, 1024)
 # A second small shape with head_dim 128 and GQA ratio 4 (the 8B head geometry).
 SMALL128 = Shape("small128", 2, 512, 8, 2, 128, 1024, 2048)
+# Small shape with the 14B head geometry (GQA ratio 5, head_dim 128).
+SMALL_G5 = Shape("small_g5", 2, 1280, 10, 2, 128, 1024, 2048)
 LLAMA_8B = Shape("llama8b", 32, 4096, 32, 8, 128, 14336, 128256)
 QWEN_14B = Shape("qwen14b", 48, 5120, 40, 8, 128, 13824, 152064)
 
-SHAPES = {s.name: s for s in (TINY, TINY_Q, SMALL128, LLAMA_8B, QWEN_14B)}
+SHAPES = {s.name: s for s in (TINY, TINY_Q, SMALL128, SMALL_G5, LLAMA_8B, QWEN_14B)}
 
 
 def zipf_probs(n_models: int, s: float) -> np.ndarray:

@@ -212,6 +212,15 @@ def test_qsun_small_full_step(H, mode):
     _full_step_parity(H, case)
 
 
+def test_bf16_and_qsun_gqa_ratio_5(H):
+    """The 14B head geometry (5 query heads per KV head) on a small shape, dense and 4-bit."""
+    for quant in (None, "asym"):
+        H.say(f"bf16 small_g5 quant={quant}")
+        work = wl.make_workload("cfg2", shape=wl.SMALL_G5, batch=20, n_models=4, lo=1, hi=900, seed=95)
+        case = H.GpuCase(work, quant_mode=quant)
+        _full_step_parity(H, case)
+
+
 def test_bf16_head_dim_64(H):
     H.say("bf16 tiny_q (head_dim 64, G=2)")
     work = wl.make_workload("cfg1", shape=wl.TINY_Q, dtype="bf16", batch=12, lo=1, hi=400, seed=92)

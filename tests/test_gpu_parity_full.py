@@ -90,3 +90,20 @@ def test_cfg4_qsun_batch64_sampled(H, quant8b):
 
 def test_cfg4_qsun_batch256_sampled(H, quant8b):
     _sampled_parity(H, wl.make_workload("cfg3"), quant8b, 4)
+
+
+def test_cfg5_14b_shape_sampled(H):
+    """14B shape (48 layers, 40 q / 8 kv heads, vocab 152064): the first 16 requests of the cfg5
+    draw (lengths up to 32768, ~50 GB of KV) in a pool without aliasing, dense and 4-bit; the
+    oracle recomputes 3 of them including the longest."""
+    work = wl.make_workload("cfg5", batch=16)
+    for quant in (None, "asym"):
+        H.say(f"building 14B-shaped weights quant={quant}")
+        sw = H.SharedWeights(wl.QWEN_14B, "bf16", wl.SEED_BASE + 105, quant_mode=quant)
+        if quant:
+            for k in sun.QUANT_KEYS:
+                sw.w[k] = None
+            torch.cuda.empty_cache()
+        case, rep = _sampled_parity(H, work, sw, 3)
+        del case, sw
+        torch.cuda.empty_cache()
