@@ -25,6 +25,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per attention launch from two counter runs (FETCH_SIZE, then WRITE_SIZE) of this script under
+# the profiler, each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration):
+# FETCH_SIZE reports 0.5 of the bytes read, WRITE_SIZE 1.0 of the bytes written.  Keyed by workload; the
+# summaries with the commands are under profiles/.  Workloads that were not counted report null.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2": (292854.7 / 0.5 + 9310.3 / 1.0) * 1024.0,
+}
+
 
 def algorithmic_bytes(shape, work, quant: bool, logits_out: bool = True):
     """Bytes the method must move per step: weights once, lm_head (bf16), embedding rows,
@@ -88,14 +96,25 @@ def cpu_baseline(case, work, n_sample: int):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--quant", default=None, choices=[None, "asym", "sym"])
     ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (known size) to calibrate FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
+        return
     if args.gpus != 1:
         raise SystemExit("bench.py: this build measures one GPU only (one decode worker holds a full copy of the "
                          "shared decode weights; more GPUs are more independent workers). Run with --gpus 1.")
@@ -171,7 +190,7 @@ def main():
         avg_s = att["ms"] / att["launches"] * 1e-3
         roof = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": per_launch / avg_s / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
-                "traffic": None, "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
         w_bytes = {"qkv_proj": 0, "o_proj": 1, "gate_up_proj": 2, "down_proj": 3}
         b_w = 0.53125 if args.quant else 2.0
         H_, QD, KD, F = shape.hidden, shape.q_dim, shape.kv_dim, shape.ffn
