@@ -123,8 +123,8 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
     const size_t mc = attn_max_chunks(batch, max_pages);
     w.plan.max_chunks = (int)std::min<size_t>(mc, 0x7fffffff);
     w.plan.chunk_off = (int32_t*)take((size_t)(batch + 1) * 4);
-    w.plan.item_req = (int32_t*)take(mc * 4);
-    w.plan.item_chunk = (int32_t*)take(mc * 4);
+    w.plan.full_off = (int32_t*)take((size_t)(batch + 1) * 4);
+    w.plan.small_off = (int32_t*)take((size_t)(batch + 1) * 4);
     w.plan.records = (int32_t*)take(mc * c.n_kv_heads * 24 * 4);
     w.plan.partial = (float*)take(mc * c.n_q_heads * (c.head_dim + 2) * 4);
     w.logits = (float*)take((size_t)batch * c.vocab * 4);
@@ -511,7 +511,9 @@ static int total_chunks_from_host(const int32_t* host, int len_plus, int batch) 
     long long tot = 0;
     for (int b = 0; b < batch; ++b) {
         const long long n = std::max<long long>((long long)host[b] + len_plus, 1);
-        tot += (n + kAttnChunk - 1) / kAttnChunk;
+        int nf, ns;
+        attn_chunking((int)std::min<long long>(n, 0x7fffffff), nf, ns);
+        tot += nf + ns;
     }
     return (int)std::min<long long>(tot, 0x7fffffff);
 }

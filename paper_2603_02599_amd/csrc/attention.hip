@@ -4,11 +4,12 @@
 // n_i cached positions of that request; requests of different source models are
 // handled identically, the pool is addressed through the page table only.
 //
-// Work decomposition: a work item is (request, kv head, chunk of 256 positions).
-// The chunk grid of a request depends on its own length only, so a request's
-// result does not depend on its batch-mates.  One wave per item streams the
-// item's K and V^T pages with 16-byte loads straight into matrix-core operand
-// registers:
+// Work decomposition: a work item is (request, kv head, chunk of positions).  All but the last
+// 256..511 positions of a request form full chunks of 256, the rest small chunks of 64; the
+// chunk grid of a request depends on its own length only, so a request's result does not depend
+// on its batch-mates.  One persistent workgroup of 8 waves per compute unit works through a
+// statically dealt item list, full chunks first; a wave streams an item's K and V^T pages with
+// 16-byte loads straight into matrix-core operand registers:
 //   S^T[token, head] = K[token, :] . q[head, :]      (16x16x32 MFMA, q split hi+lo bf16)
 //   O[head, dim]    += P[head, token] V^T[dim, token] (16x16x32 MFMA, P split hi+lo bf16)
 // The group's q heads occupy the first G of the 16 MFMA columns.  Softmax runs in
@@ -26,69 +27,77 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int CH = kAttnChunk;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kRecInts = 24;  // ints per item record
+#ifndef SUN_ATTN_TOPUP
+#define SUN_ATTN_TOPUP (CH / kAttnSmall)
+#endif
+constexpr int kTopUp = SUN_ATTN_TOPUP;  // small chunks that stand for one full chunk in a wave's item list
 
 size_t attn_max_chunks(int batch, int max_pages) {
-    const size_t per_req = ((size_t)max_pages * kPageTokens + CH - 1) / CH;
-    return (size_t)batch * (per_req > 0 ? per_req : 1);
+    const size_t per_req = ((size_t)max_pages * kPageTokens) / CH + CH / kAttnSmall + CH / kAttnSmall;
+    return (size_t)batch * per_req;
 }
 
 // ---------------------------------------------------------------------------------
-// plan: chunk list from the lengths (one block)
+// plan: chunk counts of every request and their prefix sums (one block)
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t* __restrict__ n_or_len, int len_plus, int batch,
-                                                         int32_t* __restrict__ chunk_off, int32_t* __restrict__ item_req,
-                                                         int32_t* __restrict__ item_chunk, int max_chunks, int max_tokens) {
-    __shared__ int scan[1024];
+                                                         int32_t* __restrict__ chunk_off, int32_t* __restrict__ full_off,
+                                                         int32_t* __restrict__ small_off, int max_tokens) {
+    __shared__ int scan_f[1024], scan_s[1024];
     const int t = threadIdx.x;
-    int mine = 0;
-    if (t < batch) {
-        const int n = min(max(n_or_len[t] + len_plus, 1), max_tokens);
-        mine = (n + CH - 1) / CH;
-    }
-    scan[t] = mine;
+    int nf = 0, ns = 0;
+    if (t < batch) attn_chunking(min(max(n_or_len[t] + len_plus, 1), max_tokens), nf, ns);
+    scan_f[t] = nf;
+    scan_s[t] = ns;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
-        const int v = t >= o ? scan[t - o] : 0;
+        const int vf = t >= o ? scan_f[t - o] : 0, vs = t >= o ? scan_s[t - o] : 0;
         __syncthreads();
-        scan[t] += v;
+        scan_f[t] += vf;
+        scan_s[t] += vs;
         __syncthreads();
     }
-    const int end = scan[t], begin = end - mine;
     if (t < batch) {
-        chunk_off[t + 1] = min(end, max_chunks);
-        if (t == 0) chunk_off[0] = 0;
-        for (int j = 0; j < mine; ++j)
-            if (begin + j < max_chunks) {
-                item_req[begin + j] = t;
-                item_chunk[begin + j] = j;
-            }
+        full_off[t + 1] = scan_f[t];
+        small_off[t + 1] = scan_s[t];
+        chunk_off[t + 1] = scan_f[t] + scan_s[t];
+        if (t == 0) full_off[0] = small_off[0] = chunk_off[0] = 0;
     }
 }
 
-// One record per item, ordered (request, kv head, chunk): the 16 page ids of the chunk
-// (clamped into the pool, -1 where the chunk has no page), then request, kv head, first
-// and one-past-last token, and the chunk's index in the partial array.
+// One record per work item.  Items of all full chunks come first, ordered (request, kv head,
+// chunk), then the items of all small chunks in the same order.  Record: the chunk's page ids
+// (clamped into the pool, -1 where the chunk has no page), then request, kv head, first and
+// one-past-last token, and the chunk's slot in the partial array (chunks of a request in token
+// order).
 __global__ __launch_bounds__(256) void attn_records_kernel(const int32_t* __restrict__ n_or_len, int len_plus, int batch,
                                                            const int32_t* __restrict__ chunk_off,
+                                                           const int32_t* __restrict__ full_off,
+                                                           const int32_t* __restrict__ small_off,
                                                            const int32_t* __restrict__ page_tables, int max_pages,
                                                            int n_pages, int Hkv, int32_t* __restrict__ records) {
-    const int total = chunk_off[batch] * Hkv;
+    const int total_full = full_off[batch] * Hkv, total = chunk_off[batch] * Hkv;
     for (int item = blockIdx.x * 16 + (threadIdx.x >> 4); item < total; item += gridDim.x * 16) {
         const int slot = threadIdx.x & 15;
-        int lo = 0, hi = batch;  // request whose item range [chunk_off[r]*Hkv, chunk_off[r+1]*Hkv) holds item
+        const bool is_full = item < total_full;
+        const int32_t* off = is_full ? full_off : small_off;
+        const int idx = is_full ? item : item - total_full;
+        int lo = 0, hi = batch;  // request whose item range [off[r]*Hkv, off[r+1]*Hkv) holds idx
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (chunk_off[mid] * Hkv <= item) lo = mid; else hi = mid;
+            if (off[mid] * Hkv <= idx) lo = mid; else hi = mid;
         }
-        const int req = lo, nc = chunk_off[req + 1] - chunk_off[req];
-        const int local = item - chunk_off[req] * Hkv, head = local / nc, cj = local % nc;
+        const int req = lo, nc = off[req + 1] - off[req];
+        const int local = idx - off[req] * Hkv, head = local / nc, cj = local % nc;
         const int n = min(max(n_or_len[req] + len_plus, 1), max_pages * kPageTokens);
-        const int t0 = cj * CH, t1 = min(n, t0 + CH);
+        const int nfull = full_off[req + 1] - full_off[req];
+        const int t0 = is_full ? cj * CH : nfull * CH + cj * kAttnSmall;
+        const int t1 = is_full ? t0 + CH : min(n, t0 + kAttnSmall);
         const int npages = (t1 - t0 + kPageTokens - 1) / kPageTokens;
         int32_t* rec = records + (size_t)item * kRecInts;
         rec[slot] = slot < npages ? min(max(page_tables[(size_t)req * max_pages + t0 / kPageTokens + slot], 0), n_pages - 1) : -1;
         if (slot < 8) {
-            const int vals[8] = {req, head, t0, t1, chunk_off[req] + cj, 0, 0, 0};
+            const int vals[8] = {req, head, t0, t1, chunk_off[req] + (is_full ? cj : nfull + cj), 0, 0, 0};
             rec[16 + slot] = vals[slot];
         }
     }
@@ -98,11 +107,11 @@ hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int l
                             const int32_t* page_tables, int max_pages, int n_pages, int Hkv, hipStream_t st) {
     if (batch > 1024) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_or_len, len_plus, batch, plan.chunk_off,
-                       plan.item_req, plan.item_chunk, plan.max_chunks, max_pages * kPageTokens);
+                       plan.full_off, plan.small_off, max_pages * kPageTokens);
     const long long items = (long long)plan.max_chunks * Hkv;
     const int grid = (int)max(1LL, min((items + 15) / 16, 1024LL));
     hipLaunchKernelGGL(attn_records_kernel, dim3(grid), dim3(256), 0, st, n_or_len, len_plus, batch, plan.chunk_off,
-                       page_tables, max_pages, n_pages, Hkv, plan.records);
+                       plan.full_off, plan.small_off, page_tables, max_pages, n_pages, Hkv, plan.records);
     return hipGetLastError();
 }
 
@@ -114,8 +123,7 @@ struct AttnArgs {
     const int32_t* page_tables;
     const int32_t* n_or_len;
     const int32_t* chunk_off;
-    const int32_t* item_req;
-    const int32_t* item_chunk;
+    const int32_t* full_off;
     const int32_t* records;
     float* partial;
     int len_plus, max_pages, batch, Hq, Hkv, n_pages;
@@ -133,18 +141,40 @@ __device__ __forceinline__ uint32_t bf16_pair_hi(float a, float b, float& ra, fl
 // split kernel, matrix-core variant
 // ---------------------------------------------------------------------------------
 template <int D, int G>
-__global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_split_kernel(AttnArgs a) {
     constexpr int NS = D / 32;  // dim slices of a QK MFMA
     constexpr int NB = D / 16;  // dim blocks of a PV MFMA
     const int lane = threadIdx.x & 63;
     const int c16 = lane & 15, kq = lane >> 4;
-    // every wave owns a contiguous range of items; items are ordered (request, kv head, chunk),
-    // so consecutive items mostly share q, and the record of the next item is prefetched
-    const long long total_items = (long long)a.chunk_off[a.batch] * a.Hkv;
-    const long long wid = (long long)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (long long)gridDim.x * 4;
-    int item = (int)(wid * total_items / nw);
-    const int item_end = (int)((wid + 1) * total_items / nw);
-    if (item >= item_end) return;
+    // One workgroup of 8 waves per compute unit.  Items are dealt to workgroups statically: full
+    // chunks (all of one size) round-robin; the workgroups that got one full chunk fewer are
+    // topped up with a block of kTopUp small chunks, the remaining small chunks go round-robin.
+    // Inside a workgroup the waves take the list's entries in order through a counter in LDS, so
+    // they run out of work within one small chunk of each other however unevenly the hardware
+    // serves them.  Which wave computes an item has no effect on its value.
+    __shared__ int list_cursor;
+    if (threadIdx.x == 0) list_cursor = 0;
+    __syncthreads();
+    const int n_full = a.full_off[a.batch] * a.Hkv, total_items = a.chunk_off[a.batch] * a.Hkv;
+    const int n_small = total_items - n_full;
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    const int fq = n_full / nwg, fr = n_full % nwg;
+    auto next_item = [&]() -> int {  // next unclaimed entry of this workgroup's list, total_items when it is over
+        int c = 0;
+        if (lane == 0) c = atomicAdd(&list_cursor, 1);
+        c = __builtin_amdgcn_readfirstlane(c);
+        const int mine_full = fq + (wg < fr ? 1 : 0);
+        if (c < mine_full) return wg + c * nwg;
+        c -= mine_full;
+        const int top = wg >= fr ? min(max(n_small - kTopUp * (wg - fr), 0), kTopUp) : 0;
+        if (c < top) return n_full + kTopUp * (wg - fr) + c;
+        c -= top;
+        const long long j = (long long)kTopUp * (nwg - fr) + wg + (long long)c * nwg;
+        return j < n_small ? n_full + (int)j : total_items;
+    };
+    int item = next_item();
+    if (item >= total_items) return;
+    int item_n = next_item();
 
     // K operand rows: MFMA row i of tile 0 <-> page (i>>3), token 8*((i>>2)&1) + (i&3); tile 1: +4
     const int k_psel = c16 >> 3, k_tok = 8 * ((c16 >> 2) & 1) + (c16 & 3);
@@ -206,7 +236,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
     int npairs = ((t1 - t0 + kPageTokens - 1) / kPageTokens + 1) / 2, pp = 0;
     load_k(rec, head, 0);
     load_v(rec, head, 0);
-    int rec_n = load_rec(item + 1 < item_end ? item + 1 : item);
+    int rec_n = load_rec(item_n < total_items ? item_n : item);
     load_q(req, head);
     int head_n = __builtin_amdgcn_readlane(rec_n, 17);
 
@@ -325,7 +355,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
             pbase[(size_t)c16 * (D + 2) + D] = m_run;
             pbase[(size_t)c16 * (D + 2) + D + 1] = l_tot;
         }
-        if (++item >= item_end) return false;
+        if (item_n >= total_items) return false;
+        item = item_n;
+        item_n = next_item();
         rec = rec_n;
         req = __builtin_amdgcn_readlane(rec, 16);
         head = __builtin_amdgcn_readlane(rec, 17);
@@ -334,7 +366,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
         cidx = __builtin_amdgcn_readlane(rec, 20);
         npairs = ((t1 - t0 + kPageTokens - 1) / kPageTokens + 1) / 2;
         pp = 0;
-        rec_n = load_rec(item + 1 < item_end ? item + 1 : item);
+        rec_n = load_rec(item_n < total_items ? item_n : item);
         load_q(req, head);  // also drains every outstanding request before the steady state resumes
         head_n = __builtin_amdgcn_readlane(rec_n, 17);
 #pragma unroll
@@ -357,10 +389,8 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(AttnArgs a, int G) {
     const int lane = threadIdx.x;
     const int total_items = a.chunk_off[a.batch] * a.Hkv;
     for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const int chunk_idx = item / a.Hkv, head = item % a.Hkv;
-        const int req = a.item_req[chunk_idx], cj = a.item_chunk[chunk_idx];
-        const int n = min(max(a.n_or_len[req] + a.len_plus, 1), a.max_pages * kPageTokens);
-        const int t0 = cj * CH, t1 = min(n, t0 + CH), cnt = t1 - t0;
+        const int32_t* rec = a.records + (size_t)item * kRecInts;
+        const int req = rec[16], head = rec[17], t0 = rec[18], t1 = rec[19], chunk_idx = rec[20], cnt = t1 - t0;
         const int32_t* pt = a.page_tables + (size_t)req * a.max_pages;
         const uint16_t* kb = a.kbase + head * a.k_head;
         const uint16_t* vb = a.vbase + head * a.v_head;
@@ -412,7 +442,7 @@ template <int D>
 static hipError_t launch_split_d(const AttnArgs& a, int G, int grid, hipStream_t st) {
     switch (G) {
 #define SUN_CASE(g) \
-    case g: hipLaunchKernelGGL((attn_split_kernel<D, g>), dim3(grid), dim3(256), 0, st, a); break;
+    case g: hipLaunchKernelGGL((attn_split_kernel<D, g>), dim3(grid), dim3(512), 0, st, a); break;
         SUN_CASE(1) SUN_CASE(2) SUN_CASE(3) SUN_CASE(4) SUN_CASE(5) SUN_CASE(6) SUN_CASE(7) SUN_CASE(8)
 #undef SUN_CASE
     default: return hipErrorInvalidValue;
@@ -438,8 +468,7 @@ hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan
     a.page_tables = page_tables;
     a.n_or_len = n_or_len;
     a.chunk_off = plan.chunk_off;
-    a.item_req = plan.item_req;
-    a.item_chunk = plan.item_chunk;
+    a.full_off = plan.full_off;
     a.records = plan.records;
     a.partial = plan.partial;
     a.len_plus = len_plus;
@@ -459,15 +488,9 @@ hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan
         else return hipErrorInvalidValue;
         return hipGetLastError();
     }
-    // persistent waves, at most 2 workgroups of 4 waves per CU; when the item count is known the
-    // wave count is trimmed so that every wave gets the same number of items
-    #ifndef SUN_ATTN_MAX_WAVES
-#define SUN_ATTN_MAX_WAVES 2048
-#endif
-    const long long max_waves = SUN_ATTN_MAX_WAVES;
-    const long long rounds = (items + max_waves - 1) / max_waves;
-    const long long waves = total_chunks_hint >= 0 ? (items + rounds - 1) / max(rounds, 1LL) : max_waves;
-    const int grid = (int)max(1LL, min((waves + 3) / 4, max_waves / 4));
+    // persistent workgroups of 8 waves, one per compute unit (fewer only when there are fewer
+    // items than waves)
+    const int grid = (int)max(1LL, min((items + 7) / 8, 256LL));
     if (D == 64) return launch_split_d<64>(a, G, grid, st);
     if (D == 128) return launch_split_d<128>(a, G, grid, st);
     return hipErrorInvalidValue;

@@ -16,7 +16,18 @@ constexpr int kPageTokens = 16;     // tokens per KV page
 #ifndef SUN_ATTN_CHUNK
 #define SUN_ATTN_CHUNK 256
 #endif
-constexpr int kAttnChunk = SUN_ATTN_CHUNK;  // tokens per split-K work item; a request's chunking depends on its own length only
+#ifndef SUN_ATTN_SMALL
+#define SUN_ATTN_SMALL 64
+#endif
+constexpr int kAttnChunk = SUN_ATTN_CHUNK;  // tokens per full split-K work item
+constexpr int kAttnSmall = SUN_ATTN_SMALL;  // tokens per small work item at the end of a request
+// A request's chunking depends on its own length only: all but the last full chunk's worth of
+// tokens go into full chunks, the remaining 1 .. 2*kAttnChunk-1 tokens into small chunks.
+__host__ __device__ inline void attn_chunking(int n, int& n_full, int& n_small) {
+    const int f = n / kAttnChunk;
+    n_full = f > 1 ? f - 1 : 0;
+    n_small = (n - n_full * kAttnChunk + kAttnSmall - 1) / kAttnSmall;
+}
 constexpr int kGroup = 128;         // quantisation group along K (Appendix A.1)
 constexpr int kMaxBatchTile = 256;  // rows one projection launch covers
 

@@ -43,10 +43,10 @@ hipError_t launch_quantize_w4(const void* w, int dtype, int rows, int cols, int 
 // ---------------- attention (attention.hip) ----------------
 
 struct AttnPlan {           // device arrays inside the workspace
-    int32_t* chunk_off;     // [batch+1] prefix sum of chunks per request
-    int32_t* item_req;      // [max_chunks]
-    int32_t* item_chunk;    // [max_chunks]
-    int32_t* records;       // [max_chunks * Hkv][24] per-item records, ordered (request, kv head, chunk)
+    int32_t* chunk_off;     // [batch+1] prefix sum of chunks (full + small) per request
+    int32_t* full_off;      // [batch+1] prefix sum of full chunks per request
+    int32_t* small_off;     // [batch+1] prefix sum of small chunks per request
+    int32_t* records;       // [max_chunks * Hkv][24] per-item records
     float* partial;         // [max_chunks][Hq][d+2]  (o[d], m, l)
     int max_chunks;
 };
