@@ -274,20 +274,27 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     splits = (kch + cps - 1) / cps;
     const int mb = at.MB;
     if (w4 && p.hsum == nullptr) return hipErrorInvalidValue;
-    // operand blocks = 2 * row blocks (hi and lo plane); stage width 128 up to 32 rows, 64 above (LDS budget)
-    if (mb == 1) {
+    // operand blocks = 2 * row blocks (hi and lo plane).  Up to 64 rows a stage is a whole 128-wide
+    // group: three 16 KB stages in LDS up to 32 rows, two 32 KB stages up to 64 rows (long stages
+    // amortise the workgroup barrier better than a third buffer does); above that 64-wide stages.
+    if (mb <= 2) {
         a.n_stages = kch;
         a.stages_per_split = cps;
-        return w4 ? launch_proj_t<2, 128, true>(a, p.epilogue, splits, 1, st)
-                  : launch_proj_t<2, 128, false>(a, p.epilogue, splits, 1, st);
+        if (mb == 1) return w4 ? launch_proj_t<2, 128, true>(a, p.epilogue, splits, 1, st)
+                               : launch_proj_t<2, 128, false>(a, p.epilogue, splits, 1, st);
+        return w4 ? launch_proj_t<4, 128, true>(a, p.epilogue, splits, 1, st)
+                  : launch_proj_t<4, 128, false>(a, p.epilogue, splits, 1, st);
+    }
+    // more than 64 rows: 128-row tiles (8 operand blocks, the accumulator budget); 256 rows run as two
+    // tiles.  The 4-bit kernel has the registers for 128-wide stages, the bf16 kernel has not.
+    if (w4) {
+        a.n_stages = kch;
+        a.stages_per_split = cps;
+        return launch_proj_t<8, 128, true>(a, p.epilogue, splits, mb / 4, st);
     }
     a.n_stages = kch * 2;
     a.stages_per_split = cps * 2;
-    if (mb == 2) return w4 ? launch_proj_t<4, 64, true>(a, p.epilogue, splits, 1, st)
-                           : launch_proj_t<4, 64, false>(a, p.epilogue, splits, 1, st);
-    // more than 64 rows: 128-row tiles (8 operand blocks, the accumulator budget); 256 rows run as two tiles
-    return w4 ? launch_proj_t<8, 64, true>(a, p.epilogue, splits, mb / 4, st)
-              : launch_proj_t<8, 64, false>(a, p.epilogue, splits, mb / 4, st);
+    return launch_proj_t<8, 64, false>(a, p.epilogue, splits, mb / 4, st);
 }
 
 // ---------------------------------------------------------------------------------
