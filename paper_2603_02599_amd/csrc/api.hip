@@ -86,6 +86,8 @@ struct Workspace {
     float* table;
     AttnPlan plan;
     float* logits;
+    float* amax_val;      // [batch][kArgmaxParts] slice winners of the greedy argmax
+    int32_t* amax_idx;
     size_t bytes;
 };
 
@@ -128,6 +130,8 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
     w.plan.records = (int32_t*)take(mc * c.n_kv_heads * 24 * 4);
     w.plan.partial = (float*)take(mc * c.n_q_heads * (c.head_dim + 2) * 4);
     w.logits = (float*)take((size_t)batch * c.vocab * 4);
+    w.amax_val = (float*)take((size_t)batch * kArgmaxParts * 4);
+    w.amax_idx = (int32_t*)take((size_t)batch * kArgmaxParts * 4);
     w.bytes = off;
     return w;
 }
@@ -647,7 +651,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
     }
     {
         ProfScope p(prof, 7, st);
-        SUN_HIP_CHECK(launch_argmax(logits, batch, c.vocab, next_tokens_out, st));
+        SUN_HIP_CHECK(launch_argmax(logits, batch, c.vocab, ws.amax_val, ws.amax_idx, next_tokens_out, st));
     }
     return SUN_OK;
 }

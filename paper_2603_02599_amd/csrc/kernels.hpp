@@ -79,7 +79,10 @@ hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipS
 // gate/up partial sums (projection column order) -> silu(g)*u as two-plane tiled bf16 (+ group sums)
 hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,
                               hipStream_t st);
-hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next, hipStream_t st);
+constexpr int kArgmaxParts = 16;  // slices of a logits row searched by separate workgroups
+// part_val / part_idx: scratch [batch][kArgmaxParts]
+hipError_t launch_argmax(const float* logits, int batch, int vocab, float* part_val, int32_t* part_idx, int32_t* next,
+                         hipStream_t st);
 // fp32 [rows, K] -> tiled bf16 (+ group sums)
 hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st);
 // out[b][n] = sum_s partial[s][b][n]

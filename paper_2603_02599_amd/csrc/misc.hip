@@ -324,16 +324,22 @@ hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int ro
 }
 
 // ---------------- greedy argmax, lowest index on ties ----------------
-__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ next) {
-    __shared__ float bv[16];
-    __shared__ int bi[16];
-    const int b = blockIdx.x, tid = threadIdx.x;
+// Two passes so that all compute units read the logits: kArgmaxParts slices of a row are
+// searched by one workgroup each, then one thread per row picks among the slice winners
+// (slices in index order, strict comparison, so the lowest index wins ties).
+__global__ __launch_bounds__(256) void argmax_part_kernel(const float* __restrict__ logits, int V,
+                                                          float* __restrict__ pval, int32_t* __restrict__ pidx) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    const int b = blockIdx.y, part = blockIdx.x, tid = threadIdx.x;
+    const int per = (V + kArgmaxParts - 1) / kArgmaxParts;
+    const int j0 = part * per, j1 = min(V, j0 + per);
     const float* row = logits + (size_t)b * V;
     float best = -INFINITY;
     int idx = 0x7fffffff;
-    for (int j = tid; j < V; j += 1024) {
+    for (int j = j0 + tid; j < j1; j += 256) {
         const float v = row[j];
-        if (v > best || (v == best && j < idx)) {
+        if (v > best) {  // a thread meets its indices in ascending order
             best = v;
             idx = j;
         }
@@ -353,17 +359,37 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     }
     __syncthreads();
     if (tid == 0) {
-        for (int w = 1; w < 16; ++w)
+        for (int w = 1; w < 4; ++w)
             if (bv[w] > best || (bv[w] == best && bi[w] < idx)) {
                 best = bv[w];
                 idx = bi[w];
             }
-        next[b] = idx == 0x7fffffff ? 0 : idx;
+        pval[(size_t)b * kArgmaxParts + part] = best;
+        pidx[(size_t)b * kArgmaxParts + part] = idx;
     }
 }
 
-hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next, hipStream_t st) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(batch), dim3(1024), 0, st, logits, vocab, next);
+__global__ __launch_bounds__(256) void argmax_pick_kernel(const float* __restrict__ pval, const int32_t* __restrict__ pidx,
+                                                          int batch, int32_t* __restrict__ next) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= batch) return;
+    float best = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int p = 0; p < kArgmaxParts; ++p) {
+        const float v = pval[(size_t)b * kArgmaxParts + p];
+        const int i = pidx[(size_t)b * kArgmaxParts + p];
+        if (v > best || (v == best && i < idx)) {
+            best = v;
+            idx = i;
+        }
+    }
+    next[b] = idx == 0x7fffffff ? 0 : idx;
+}
+
+hipError_t launch_argmax(const float* logits, int batch, int vocab, float* part_val, int32_t* part_idx, int32_t* next,
+                         hipStream_t st) {
+    hipLaunchKernelGGL(argmax_part_kernel, dim3(kArgmaxParts, batch), dim3(256), 0, st, logits, vocab, part_val, part_idx);
+    hipLaunchKernelGGL(argmax_pick_kernel, dim3((batch + 255) / 256), dim3(256), 0, st, part_val, part_idx, batch, next);
     return hipGetLastError();
 }
 

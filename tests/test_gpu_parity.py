@@ -49,9 +49,10 @@ def test_cfg1_tiny_fp32_full_step(H):
     assert rep["ref_std"] > 0.05
 
 
-@pytest.mark.parametrize("lens", [[0, 1, 15, 16, 17, 31, 32, 255, 256, 257, 600]])
+@pytest.mark.parametrize("lens", [[0, 1, 15, 16, 17, 31, 32, 62, 63, 64, 127, 128, 255, 256, 257, 510, 511, 512, 600, 767, 768, 1100]])
 def test_fp32_edge_lengths(H, lens):
-    """Empty cache, page boundaries, chunk boundaries (256) and a multi-chunk request."""
+    """Empty cache, page boundaries, small-chunk (64) and full-chunk (256) boundaries of the attention
+    work split, the first lengths that get a full chunk (n = L+1 >= 512), multi-chunk requests."""
     H.say(f"fp32 edge lengths {lens}")
     work = wl.make_workload("cfg1", batch=len(lens), seed=77)
     rng = np.random.default_rng(5)
@@ -70,6 +71,28 @@ def test_fp32_single_request_and_no_logits_output(H):
     fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, None, case.next, case.ws)
     torch.cuda.synchronize()
     assert int(case.next.cpu()[0]) == int(ref["next"][0])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_argmax_ties_take_the_lowest_index(H, dtype):
+    """LM head rows 0..99 are -v and all later rows +v: every request's logits are two exact plateaus,
+    so greedy decoding must return token 100 (v.h > 0) or token 0 (v.h < 0) on both sides."""
+    H.say(f"argmax ties {dtype}")
+    shape = wl.TINY if dtype == "f32" else wl.SMALL128
+    work = wl.make_workload("cfg1", shape=shape, dtype=dtype, batch=16, seed=91)
+    w = wl.make_weights(shape, dtype, "cuda", 92)
+    v = w["wlm"][0].clone()
+    w["wlm"][:100] = -v
+    w["wlm"][100:] = v
+    case = H.GpuCase(work, weights=w)
+    ref = H.run_oracle(case, list(range(work.batch)))
+    case.step()
+    got = case.next.cpu().numpy()
+    lg = case.logits.cpu().numpy()
+    assert set(np.unique(ref["next"])) <= {0, 100} and len(set(ref["next"])) == 2, "both plateaus should occur"
+    assert np.array_equal(got, ref["next"])
+    for i in range(work.batch):  # the plateaus are exact on the GPU as well: identical rows give identical logits
+        assert len(np.unique(lg[i, 100:])) == 1 and len(np.unique(lg[i, :100])) == 1
 
 
 def test_fp32_qsun_tiny(H):
