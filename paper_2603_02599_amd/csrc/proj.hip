@@ -45,8 +45,7 @@ void proj_kernel(ProjArgs a) {
     constexpr int KK = KS / 16;                // MFMA k-steps per stage
     constexpr int STAGE_UNITS = KK * MB * 64;  // 16-byte units of activations per stage
     constexpr int NT = NW * 64;
-    constexpr int UPT = STAGE_UNITS / NT;
-    static_assert(STAGE_UNITS % NT == 0, "stage must divide evenly over the workgroup");
+    constexpr int UPT = (STAGE_UNITS + NT - 1) / NT;  // the last round of a stage may be partial
     constexpr int WREGS = W4 ? KK / 4 : KK;    // 16-byte weight loads per lane per stage
 
     __shared__ u32x4 lds[NBUF][STAGE_UNITS];  // ring of staged activation tiles (prefetch distance NBUF-1)
@@ -88,7 +87,7 @@ void proj_kernel(ProjArgs a) {
     auto load_a = [&](int st) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i) {
-            const int u = i * NT + tid;
+            const int u = min(i * NT + tid, STAGE_UNITS - 1);  // past the stage: re-read its last unit, never stored
             const int kk = u / (MB * 64), rem = u % (MB * 64);
             const int m = rem >> 6;  // operand block: hi plane of row block m, or lo plane of row block m - MR
             const int gb = m < MR ? mb_off + m : a.mb_rows + mb_off + (m - MR);
@@ -99,7 +98,8 @@ void proj_kernel(ProjArgs a) {
     };
     auto store_a = [&](int buf, int st) {
 #pragma unroll
-        for (int i = 0; i < UPT; ++i) lds[buf][i * NT + tid] = areg[i];
+        for (int i = 0; i < UPT; ++i)
+            if (STAGE_UNITS % NT == 0 || i * NT + tid < STAGE_UNITS) lds[buf][i * NT + tid] = areg[i];
         if (W4 && ((st * KK) & 7) == 0 && tid < MR * 32) hs_lds[(((st * KK) >> 3) & 3) * MR * 32 + tid] = hreg;
     };
     auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
@@ -227,9 +227,8 @@ void proj_kernel(ProjArgs a) {
     }
 }
 
-template <int MB, int KS, bool W4>
+template <int MB, int KS, bool W4, int NW = 4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
-    constexpr int NW = 4;
     constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
     if (epilogue != EPI_STORE) return hipErrorInvalidValue;
@@ -239,15 +238,66 @@ static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int
 
 static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / splits; }
 
-int proj_pick_splits(const Mat& W, int rows, int max_splits) {
-    const int tiles = (W.N / 32 + 3) / 4, kch = W.K / 128;
-    const int target = 256;  // about one workgroup per CU; more splits cost more in the consumer than they gain
-    int s = (target + tiles - 1) / tiles;
-    s = min(s, max_splits);
-    s = min(s, max(1, kch / 2));
-    s = max(s, 1);
-    const int cps = chunks_per_split(kch, s);
-    return (kch + cps - 1) / cps;
+// Waves per workgroup (each wave owns 32 columns) and split-K factor.  A compute unit's share of
+// the HBM bandwidth does not grow with the number of workgroups it hosts, so the launch is only
+// as fast as the most loaded unit: the pair is chosen to spread the weight bytes evenly over the
+// 256 compute units (N = 6144 -> 6 waves x 8 splits, N = 28672 -> 7 waves x 2 splits, ...), with a
+// fixed charge per workgroup for filling and draining its pipeline.  Depends on the matrix and the
+// row-count class only.  Above 64 rows the kernels are bound by the matrix cores and keep 4 waves.
+struct ProjShape {
+    int nw, splits;
+};
+static long long proj_cost(int strips, int kch, int mtiles, int nw, int s) {
+    const int cps = chunks_per_split(kch, s), real_s = (kch + cps - 1) / cps;
+    const long long wgs = (long long)((strips + nw - 1) / nw) * real_s * mtiles;
+    const long long rounds = (wgs + 255) / 256;
+    return rounds * ((long long)nw * cps + 6) * 16 + real_s;  // ties: fewer splits
+}
+static ProjShape proj_pick(const Mat& W, int rows, int max_splits) {
+    const int strips = W.N / 32, kch = W.K / 128;
+    const int mb = atile_for_rows(rows).MB, mtiles = mb > 4 ? mb / 4 : 1;
+    const int smax = max(1, min(max_splits, kch / 2));
+    ProjShape best{4, 1};
+    long long best_cost = -1;
+    for (int nw = 4; nw <= (mb <= 2 ? 7 : 4); ++nw)
+        for (int s = 1; s <= smax; ++s) {
+            const long long c = proj_cost(strips, kch, mtiles, nw, s);
+            if (best_cost < 0 || c < best_cost) {
+                best_cost = c;
+                const int cps = chunks_per_split(kch, s);
+                best = ProjShape{nw, (kch + cps - 1) / cps};
+            }
+        }
+    return best;
+}
+
+int proj_pick_splits(const Mat& W, int rows, int max_splits) { return proj_pick(W, rows, max_splits).splits; }
+
+// the wave count that goes with a given split factor
+static int proj_pick_waves(const Mat& W, int rows, int splits) {
+    const int strips = W.N / 32, kch = W.K / 128;
+    const int mb = atile_for_rows(rows).MB, mtiles = mb > 4 ? mb / 4 : 1;
+    int best = 4;
+    long long best_cost = -1;
+    for (int nw = 4; nw <= (mb <= 2 ? 7 : 4); ++nw) {
+        const long long c = proj_cost(strips, kch, mtiles, nw, splits);
+        if (best_cost < 0 || c < best_cost) {
+            best_cost = c;
+            best = nw;
+        }
+    }
+    return best;
+}
+
+template <int MB, int KS, bool W4>
+static hipError_t launch_proj_nw(const ProjArgs& a, int nw, int epilogue, int splits, hipStream_t st) {
+    switch (nw) {
+    case 4: return launch_proj_t<MB, KS, W4, 4>(a, epilogue, splits, 1, st);
+    case 5: return launch_proj_t<MB, KS, W4, 5>(a, epilogue, splits, 1, st);
+    case 6: return launch_proj_t<MB, KS, W4, 6>(a, epilogue, splits, 1, st);
+    case 7: return launch_proj_t<MB, KS, W4, 7>(a, epilogue, splits, 1, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
@@ -280,10 +330,11 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     if (mb <= 2) {
         a.n_stages = kch;
         a.stages_per_split = cps;
-        if (mb == 1) return w4 ? launch_proj_t<2, 128, true>(a, p.epilogue, splits, 1, st)
-                               : launch_proj_t<2, 128, false>(a, p.epilogue, splits, 1, st);
-        return w4 ? launch_proj_t<4, 128, true>(a, p.epilogue, splits, 1, st)
-                  : launch_proj_t<4, 128, false>(a, p.epilogue, splits, 1, st);
+        const int nw = proj_pick_waves(W, p.rows, splits);
+        if (mb == 1) return w4 ? launch_proj_nw<2, 128, true>(a, nw, p.epilogue, splits, st)
+                               : launch_proj_nw<2, 128, false>(a, nw, p.epilogue, splits, st);
+        return w4 ? launch_proj_nw<4, 128, true>(a, nw, p.epilogue, splits, st)
+                  : launch_proj_nw<4, 128, false>(a, nw, p.epilogue, splits, st);
     }
     // more than 64 rows: 128-row tiles (8 operand blocks, the accumulator budget); 256 rows run as two
     // tiles.  The 4-bit kernel has the registers for 128-wide stages, the bf16 kernel has not.
