@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE reports 0.5 of the bytes read, WRITE_SIZE 1.0 of the bytes written.  Keyed by workload; the
 # summaries with the commands are under profiles/.  Workloads that were not counted report null.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2": (292854.7 / 0.5 + 9310.3 / 1.0) * 1024.0,
+    "cfg2": (298542.9 / 0.5 + 14060.5 / 1.0) * 1024.0,
 }
 
 
