@@ -38,7 +38,7 @@ struct ProjArgs {
 // as a hi and a lo bf16 plane (operand block m < MR is the hi plane of row block m, block MR+m
 // its lo plane); both are multiplied with the same weight fragment into the same accumulator.
 template <int MB, int KS, int NW, int EPI, bool W4, int NBUF>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB <= 4 ? 2 : 1, MB <= 4 ? 2 : 1)))
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void proj_kernel(ProjArgs a) {
     constexpr int MR = MB / 2;
     static_assert(MB % 2 == 0, "operand blocks come in hi/lo pairs");
@@ -105,15 +105,25 @@ void proj_kernel(ProjArgs a) {
     auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
         const bool first = (KS == 128) || ((st & 1) == 0);
         const bool last = (KS == 128) || ((st & 1) == 1);
-        // A operands are read from LDS one k-step ahead of the MFMAs that use them
-        u32x4 afr[2][MB];
+        // A operands are read from LDS one k-step ahead of the MFMAs that use them; the 128-row
+        // kernel reads them just in time instead: with the second fragment set it would not fit two
+        // waves per SIMD, and the second wave hides more latency than the early read
+        constexpr int AF = MB == 8 ? 1 : 2;
+        u32x4 afr[AF][MB];
+        if constexpr (AF == 2) {
 #pragma unroll
-        for (int m = 0; m < MB; ++m) afr[0][m] = lds[buf][m * 64 + lane];
+            for (int m = 0; m < MB; ++m) afr[0][m] = lds[buf][m * 64 + lane];
+        }
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            if (kk + 1 < KK) {
+            if constexpr (AF == 2) {
+                if (kk + 1 < KK) {
 #pragma unroll
-                for (int m = 0; m < MB; ++m) afr[(kk + 1) & 1][m] = lds[buf][((kk + 1) * MB + m) * 64 + lane];
+                    for (int m = 0; m < MB; ++m) afr[(kk + 1) & 1][m] = lds[buf][((kk + 1) * MB + m) * 64 + lane];
+                }
+            } else {
+#pragma unroll
+                for (int m = 0; m < MB; ++m) afr[0][m] = lds[buf][(kk * MB + m) * 64 + lane];
             }
             __builtin_amdgcn_sched_barrier(0);
             bf16x8 bfrag;
@@ -130,7 +140,7 @@ void proj_kernel(ProjArgs a) {
             for (int pl = 0; pl < 2; ++pl)  // hi plane, then lo plane, into the same accumulators
 #pragma unroll
                 for (int m = 0; m < MR; ++m) {
-                    const bf16x8 afrag = __builtin_bit_cast(bf16x8, afr[kk & 1][pl * MR + m]);
+                    const bf16x8 afrag = __builtin_bit_cast(bf16x8, afr[kk & (AF - 1)][pl * MR + m]);
                     if (W4) {
                         if (first && kk == 0 && pl == 0) {
                             f32x16 zero;
@@ -247,6 +257,20 @@ static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / s
 struct ProjShape {
     int nw, splits;
 };
+// Row tiling: operand blocks per workgroup (2 planes x 32-row blocks) and row tiles per launch.
+// Up to 64 rows one tile holds all rows.  Above, bf16 weights use 128-row tiles (every tile streams
+// the weights from HBM again); 4-bit weights are a quarter of the bytes and their kernel is bound by
+// the matrix cores, so they keep the 64-row tile, which fits two waves per SIMD with its group
+// accumulators.
+struct ProjTiling {
+    int mb, mtiles;
+};
+static ProjTiling proj_tiling(const Mat& W, int rows) {
+    const int mbr = atile_for_rows(rows).MB;  // 32-row blocks of the activation tiling: 1, 2, 4 or 8
+    if (mbr <= 2) return ProjTiling{2 * mbr, 1};
+    if (W.kind == MAT_W4_PACKED) return ProjTiling{4, mbr / 2};
+    return ProjTiling{8, mbr / 4};
+}
 static long long proj_cost(int strips, int kch, int mtiles, int nw, int s) {
     const int cps = chunks_per_split(kch, s), real_s = (kch + cps - 1) / cps;
     const long long wgs = (long long)((strips + nw - 1) / nw) * real_s * mtiles;
@@ -255,11 +279,12 @@ static long long proj_cost(int strips, int kch, int mtiles, int nw, int s) {
 }
 static ProjShape proj_pick(const Mat& W, int rows, int max_splits) {
     const int strips = W.N / 32, kch = W.K / 128;
-    const int mb = atile_for_rows(rows).MB, mtiles = mb > 4 ? mb / 4 : 1;
+    const ProjTiling t = proj_tiling(W, rows);
+    const int mtiles = t.mtiles;
     const int smax = max(1, min(max_splits, kch / 2));
     ProjShape best{4, 1};
     long long best_cost = -1;
-    for (int nw = 4; nw <= (mb <= 2 ? 7 : 4); ++nw)
+    for (int nw = 4; nw <= (t.mb <= 4 ? 7 : 4); ++nw)
         for (int s = 1; s <= smax; ++s) {
             const long long c = proj_cost(strips, kch, mtiles, nw, s);
             if (best_cost < 0 || c < best_cost) {
@@ -276,10 +301,11 @@ int proj_pick_splits(const Mat& W, int rows, int max_splits) { return proj_pick(
 // the wave count that goes with a given split factor
 static int proj_pick_waves(const Mat& W, int rows, int splits) {
     const int strips = W.N / 32, kch = W.K / 128;
-    const int mb = atile_for_rows(rows).MB, mtiles = mb > 4 ? mb / 4 : 1;
+    const ProjTiling t = proj_tiling(W, rows);
+    const int mtiles = t.mtiles;
     int best = 4;
     long long best_cost = -1;
-    for (int nw = 4; nw <= (mb <= 2 ? 7 : 4); ++nw) {
+    for (int nw = 4; nw <= (t.mb <= 4 ? 7 : 4); ++nw) {
         const long long c = proj_cost(strips, kch, mtiles, nw, splits);
         if (best_cost < 0 || c < best_cost) {
             best_cost = c;
@@ -290,12 +316,12 @@ static int proj_pick_waves(const Mat& W, int rows, int splits) {
 }
 
 template <int MB, int KS, bool W4>
-static hipError_t launch_proj_nw(const ProjArgs& a, int nw, int epilogue, int splits, hipStream_t st) {
+static hipError_t launch_proj_nw(const ProjArgs& a, int nw, int epilogue, int splits, int mtiles, hipStream_t st) {
     switch (nw) {
-    case 4: return launch_proj_t<MB, KS, W4, 4>(a, epilogue, splits, 1, st);
-    case 5: return launch_proj_t<MB, KS, W4, 5>(a, epilogue, splits, 1, st);
-    case 6: return launch_proj_t<MB, KS, W4, 6>(a, epilogue, splits, 1, st);
-    case 7: return launch_proj_t<MB, KS, W4, 7>(a, epilogue, splits, 1, st);
+    case 4: return launch_proj_t<MB, KS, W4, 4>(a, epilogue, splits, mtiles, st);
+    case 5: return launch_proj_t<MB, KS, W4, 5>(a, epilogue, splits, mtiles, st);
+    case 6: return launch_proj_t<MB, KS, W4, 6>(a, epilogue, splits, mtiles, st);
+    case 7: return launch_proj_t<MB, KS, W4, 7>(a, epilogue, splits, mtiles, st);
     }
     return hipErrorInvalidValue;
 }
@@ -322,30 +348,23 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     int splits = max(1, p.splits);
     const int cps = chunks_per_split(kch, splits);
     splits = (kch + cps - 1) / cps;
-    const int mb = at.MB;
     if (w4 && p.hsum == nullptr) return hipErrorInvalidValue;
-    // operand blocks = 2 * row blocks (hi and lo plane).  Up to 64 rows a stage is a whole 128-wide
-    // group: three 16 KB stages in LDS up to 32 rows, two 32 KB stages up to 64 rows (long stages
-    // amortise the workgroup barrier better than a third buffer does); above that 64-wide stages.
-    if (mb <= 2) {
+    const ProjTiling t = proj_tiling(W, p.rows);
+    // Up to 64-row tiles a stage is a whole 128-wide group: three 16 KB stages in LDS for 32-row tiles,
+    // two 32 KB stages for 64-row tiles (long stages amortise the workgroup barrier better than a
+    // third buffer does); the 128-row bf16 tile has 64-wide stages.
+    if (t.mb <= 4) {
         a.n_stages = kch;
         a.stages_per_split = cps;
         const int nw = proj_pick_waves(W, p.rows, splits);
-        if (mb == 1) return w4 ? launch_proj_nw<2, 128, true>(a, nw, p.epilogue, splits, st)
-                               : launch_proj_nw<2, 128, false>(a, nw, p.epilogue, splits, st);
-        return w4 ? launch_proj_nw<4, 128, true>(a, nw, p.epilogue, splits, st)
-                  : launch_proj_nw<4, 128, false>(a, nw, p.epilogue, splits, st);
-    }
-    // more than 64 rows: 128-row tiles (8 operand blocks, the accumulator budget); 256 rows run as two
-    // tiles.  The 4-bit kernel has the registers for 128-wide stages, the bf16 kernel has not.
-    if (w4) {
-        a.n_stages = kch;
-        a.stages_per_split = cps;
-        return launch_proj_t<8, 128, true>(a, p.epilogue, splits, mb / 4, st);
+        if (t.mb == 2) return w4 ? launch_proj_nw<2, 128, true>(a, nw, p.epilogue, splits, t.mtiles, st)
+                                 : launch_proj_nw<2, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
+        return w4 ? launch_proj_nw<4, 128, true>(a, nw, p.epilogue, splits, t.mtiles, st)
+                  : launch_proj_nw<4, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
     }
     a.n_stages = kch * 2;
     a.stages_per_split = cps * 2;
-    return launch_proj_t<8, 64, false>(a, p.epilogue, splits, mb / 4, st);
+    return launch_proj_t<8, 64, false>(a, p.epilogue, splits, t.mtiles, st);
 }
 
 // ---------------------------------------------------------------------------------
