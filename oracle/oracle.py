@@ -189,6 +189,51 @@ def decode_step(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_l
     return {"logits": logits, "next": nxt, "rowsums": rows, "attn": attn}
 
 
+def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_lens, model_ids, free_pages,
+               free_head: int, n_steps: int, page_tokens: int = 16, mode: int = 0, forced_tokens=None):
+    """Greedy decoding as the repeated application of the decode step (Section 3.1, Eq. 3 applied for
+    t = T+1, T+2, ...; every step extends each cache by one entry, Eq. 4), for a fixed set of requests.
+
+    After a step, a request's generated token becomes its next input and its length grows by one.  When
+    the position it will write next opens a new page (length % page_tokens == 0) and its table has no
+    page there yet, it takes the next unused entry of `free_pages`; requests are served in index order.
+    A request that finds the free list empty, or whose table is full, is frozen: its token is still
+    replaced, its length is not advanced, so it re-decodes the same position; bit 0 (free list empty)
+    or bit 1 (table full) of the returned status is set.
+
+    forced_tokens [n_steps, B], if given, replaces the fed-back tokens (teacher forcing); the step's own
+    argmax is still what is recorded.  Mutates pool, page_tables and seq_lens copies; returns a dict with
+    tokens [n_steps, B], the last step's logits, final page_tables, seq_lens, free_head, status."""
+    tokens = np.array(tokens, dtype=np.int32, copy=True)
+    tables = np.array(page_tables, dtype=np.int32, copy=True)
+    lens = np.array(seq_lens, dtype=np.int32, copy=True)
+    model_ids = np.ascontiguousarray(model_ids, dtype=np.int32)
+    free_pages = np.ascontiguousarray(free_pages, dtype=np.int32)
+    B, max_pages = tables.shape
+    out = np.empty((n_steps, B), dtype=np.int32)
+    status, head, logits = 0, int(free_head), None
+    for s in range(n_steps):
+        res = decode_step(cfg, params, pool, tokens, tables, lens, model_ids, mode=mode)
+        out[s] = res["next"]
+        logits = res["logits"]
+        tokens = np.array(out[s] if forced_tokens is None else forced_tokens[s], dtype=np.int32)
+        for i in range(B):
+            new_len = int(lens[i]) + 1
+            slot_page = new_len // page_tokens
+            if slot_page >= max_pages:
+                status |= 2
+                continue
+            if new_len % page_tokens == 0 and tables[i, slot_page] < 0:
+                if head >= len(free_pages):
+                    status |= 1
+                    continue
+                tables[i, slot_page] = free_pages[head]
+                head += 1
+            lens[i] = new_len
+    return {"tokens": out, "logits": logits, "page_tables": tables, "seq_lens": lens, "free_head": head,
+            "status": status}
+
+
 def decode_contig_f64(cfg: Cfg, params: Params, token: int, L: int, Kc: np.ndarray, Vc: np.ndarray,
                       round_kv: bool = False):
     """Kc, Vc: float64 [NL, cap, Hkv, d]; writes position L.  Returns (logits, next)."""
