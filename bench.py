@@ -93,6 +93,77 @@ def cpu_baseline(case, work, n_sample: int):
                       f"one oracle step took {dt:.1f} s; gcc -O2 -fopenmp, fp64"}
 
 
+def bench_run(args, sun, case, work, shape, desc, free_list):
+    """K steps of greedy decoding in one library call: tokens/s over the run and TPOT = time / K."""
+    import torch
+    d_free = torch.from_numpy(free_list).cuda()
+    d_head = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_out = max(args.steps, args.warmup, 1)
+    d_out = torch.empty((n_out, work.batch), dtype=torch.int32, device="cuda")
+    tok, tab, lens = case.tokens.clone(), case.tables.clone(), case.lens.clone()
+
+    def run(n, flags=0):
+        sun.sun_decode_run(case.pool, case.weights, n, tok, tab, lens, case.ids, d_free, d_head, d_status, d_out,
+                           case.logits, case.ws, flags=flags)
+
+    if args.warmup:
+        run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert int(d_status.cpu()[0]) == 0, "a request ran out of pages during the run"
+    ms_per_step = wall * 1e3 / args.steps
+    pn = min(8, args.steps)  # per-kernel event timing on the steps that follow the timed run
+    if not args.no_profile:
+        sun.sun_profile_reset()
+        run(pn, sun.SUN_PROFILE)
+        torch.cuda.synchronize()
+    # bytes: the caches grow by one token per request and step
+    start = work.seq_lens.astype(np.int64) + args.warmup
+    kv_tokens = sum(int((start + s + 1).sum()) for s in range(args.steps)) / args.steps
+    roof, kernels = None, {}
+    if not args.no_profile:
+        prof = sun.sun_profile_read()
+        sun.sun_profile_reset()
+        for k, v in prof.items():
+            if v["launches"]:
+                kernels[k] = {"avg_us": 1e3 * v["ms"] / v["launches"], "launches_per_step": v["launches"] // pn,
+                              "ms_per_step": v["ms"] / pn}
+        att = prof["attn_split"]
+        after = work.seq_lens.astype(np.int64) + args.warmup + args.steps
+        per_launch = sum(int((after + s + 1).sum()) for s in range(pn)) / pn * 2 * shape.n_kv_heads * shape.head_dim * 2
+        avg_s = att["ms"] / att["launches"] * 1e-3
+        roof = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": per_launch / avg_s / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
+                "traffic": None, "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
+
+    class _W:  # the average step of the run, for the byte count
+        batch = work.batch
+        kv_tokens_read = kv_tokens
+    alg = algorithmic_bytes(shape, _W, bool(args.quant), logits_out=False)
+    alg["total"] += work.batch * shape.vocab * 4 / args.steps  # logits are written by the last step only
+    out = {
+        "metric": "shared-decode tokens/sec", "value": work.batch / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "tpot_ms": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if not args.quant else "bf16 activations, 4-bit group-128 weights", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}; one sun_decode_run of {args.steps} steps after "
+                               f"{args.warmup} warm-up steps (greedy feedback, caches grow, pages from a free list)",
+                   "shape": shape.name, "batch": work.batch, "quant": args.quant, "mode": "run",
+                   "output_length": args.steps, "mean_kv_tokens_per_step": kv_tokens,
+                   "pages_taken": int(d_head.cpu()[0])},
+        "algorithmic_GB_per_step": alg["total"] / 1e9,
+        "step_GBps": alg["total"] / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": alg["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": roof, "kernels": kernels,
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +174,10 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--mode", default="step", choices=["step", "run"],
+                    help="step: K independent calls of the decode step on the same inputs (default). "
+                         "run: one sun_decode_run call of K steps with token feedback, growing caches and page "
+                         "allocation on the device (TPOT over an output length of K)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (known size) to calibrate FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -129,6 +204,17 @@ def main():
 
     work, desc = build_workload(args.workload)
     shape = work.shape
+    if args.mode == "run":
+        # room in the page tables for the tokens generated during warm-up and the timed run
+        grow = args.steps + args.warmup + 8  # + a short per-kernel timing pass after the timed run
+        cols = (int(work.seq_lens.max()) + grow) // 16 + 1
+        wide = np.full((work.batch, cols), -1, np.int32)
+        wide[:, :work.max_pages] = work.page_tables
+        referenced = np.zeros(work.n_pages, bool)
+        referenced[work.page_tables[work.page_tables >= 0]] = True
+        free_list = np.flatnonzero(~referenced).astype(np.int32)
+        assert len(free_list) >= work.batch * (grow // 16 + 1), "pool has too few spare pages for this output length"
+        work.page_tables = wide
     t_setup = time.perf_counter()
     case = H.GpuCase(work, quant_mode=args.quant)
     if args.quant:  # the dense projection sources are no longer needed on the device
@@ -144,6 +230,9 @@ def main():
         # seq_lens is held fixed so every step overwrites the same slot and moves identical bytes
         fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, case.logits, case.next, case.ws,
            seq_lens_host=host_lens, flags=flags)
+
+    if args.mode == "run":
+        return bench_run(args, sun, case, work, shape, desc, free_list)
 
     graph = None
     if args.graph:

@@ -235,6 +235,41 @@ int sun_qdecode_step(sun_kv_pool* pool, const sun_weights* weights, int batch,
                      float* logits_out, int32_t* next_tokens_out, void* workspace,
                      size_t workspace_bytes, void* stream, unsigned flags);
 
+/* ------------------------------------------------------------------ multi-step run */
+
+/*
+ * n_steps decode steps in a row for a fixed set of requests, enqueued on `stream` without any
+ * host synchronisation in between: the step of Eq. 3 applied repeatedly with greedy feedback,
+ * every step extending each cache by one entry (Eq. 4).  This is the loop whose per-step time
+ * the paper reports as TPOT (Appendix A.2).  `weights` may come from sun_weights_create or
+ * sun_qweights_create.
+ *
+ * After each step, on the device: token_ids[i] = the generated token; seq_lens[i] += 1; if
+ * the position the request writes next opens a page (seq_lens[i] % 16 == 0) that its table
+ * does not have (entry < 0), the entry is set to free_pages[*free_head] and *free_head
+ * advances; within a step requests are served in index order.  A request that finds the free
+ * list empty, or whose table has no column left, keeps its length (it decodes the same position
+ * again in the following steps, which is harmless) and bit 0 (list empty) or bit 1 (table full)
+ * of *run_status is set; *run_status is cleared at the start of the run.
+ *
+ *   token_ids   dev int32 [batch]             in: y_{t-1}; out: the last generated token
+ *   page_tables dev int32 [batch, max_pages]  in/out
+ *   seq_lens    dev int32 [batch]             in/out
+ *   free_pages  dev int32 [n_free]            pages no table references (read only)
+ *   free_head   dev int32 [1]                 in/out: first unused entry of free_pages
+ *   run_status  dev int32 [1]                 out
+ *   tokens_out  dev int32 [n_steps, batch]    the generated token of every step
+ *   logits_out  dev fp32 [batch, vocab] or NULL: logits of the last step
+ * Other arguments, preconditions and errors as for sun_decode_step; n_steps >= 1.  Under
+ * SUN_VALIDATE the inputs of the first step are checked as there, and free_pages[*free_head..]
+ * must lie in the pool, be distinct and not be referenced by any table (SUN_ERR_PAGE_RANGE).
+ */
+int sun_decode_run(sun_kv_pool* pool, const sun_weights* weights, int batch, int n_steps,
+                   int32_t* token_ids, int32_t* page_tables, int max_pages, int32_t* seq_lens,
+                   const int32_t* model_ids, const int32_t* free_pages, int n_free,
+                   int32_t* free_head, int32_t* run_status, int32_t* tokens_out, float* logits_out,
+                   void* workspace, size_t workspace_bytes, void* stream, unsigned flags);
+
 /* ------------------------------------------------------------------ single operations */
 
 /*

@@ -190,7 +190,8 @@ def decode_step(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_l
 
 
 def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_lens, model_ids, free_pages,
-               free_head: int, n_steps: int, page_tokens: int = 16, mode: int = 0, forced_tokens=None):
+               free_head: int, n_steps: int, page_tokens: int = 16, mode: int = 0, forced_tokens=None,
+               keep_logits: bool = False):
     """Greedy decoding as the repeated application of the decode step (Section 3.1, Eq. 3 applied for
     t = T+1, T+2, ...; every step extends each cache by one entry, Eq. 4), for a fixed set of requests.
 
@@ -203,7 +204,8 @@ def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_le
 
     forced_tokens [n_steps, B], if given, replaces the fed-back tokens (teacher forcing); the step's own
     argmax is still what is recorded.  Mutates pool, page_tables and seq_lens copies; returns a dict with
-    tokens [n_steps, B], the last step's logits, final page_tables, seq_lens, free_head, status."""
+    tokens [n_steps, B], the last step's logits (every step's, [n_steps, B, V], under keep_logits), final
+    page_tables, seq_lens, free_head, status."""
     tokens = np.array(tokens, dtype=np.int32, copy=True)
     tables = np.array(page_tables, dtype=np.int32, copy=True)
     lens = np.array(seq_lens, dtype=np.int32, copy=True)
@@ -211,11 +213,13 @@ def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_le
     free_pages = np.ascontiguousarray(free_pages, dtype=np.int32)
     B, max_pages = tables.shape
     out = np.empty((n_steps, B), dtype=np.int32)
-    status, head, logits = 0, int(free_head), None
+    status, head, logits, every = 0, int(free_head), None, []
     for s in range(n_steps):
         res = decode_step(cfg, params, pool, tokens, tables, lens, model_ids, mode=mode)
         out[s] = res["next"]
         logits = res["logits"]
+        if keep_logits:
+            every.append(logits)
         tokens = np.array(out[s] if forced_tokens is None else forced_tokens[s], dtype=np.int32)
         for i in range(B):
             new_len = int(lens[i]) + 1
@@ -230,6 +234,8 @@ def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_le
                 tables[i, slot_page] = free_pages[head]
                 head += 1
             lens[i] = new_len
+    if keep_logits:
+        logits = np.stack(every)
     return {"tokens": out, "logits": logits, "page_tables": tables, "seq_lens": lens, "free_head": head,
             "status": status}
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "sun_kv_pool_bytes", "sun_kv_pool_create", "sun_kv_pool_layout", "sun_kv_pool_destroy",
     "sun_weights_pack_bytes", "sun_weights_create", "sun_weights_destroy",
     "sun_qweights_pack_bytes", "sun_qweights_create", "sun_quantize_w4",
-    "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step",
+    "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step", "sun_decode_run",
     "sun_paged_attention", "sun_linear",
     "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
 ]
@@ -103,6 +103,9 @@ def lib() -> C.CDLL:
                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
         L.sun_decode_step.argtypes = step_args
         L.sun_qdecode_step.argtypes = step_args
+        L.sun_decode_run.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
         L.sun_paged_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sun_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -292,6 +295,19 @@ def sun_qdecode_step(pool, weights, token_ids, page_tables, seq_lens, model_ids,
                      workspace, seq_lens_host=None, stream=None, flags: int = 0):
     _step(lib().sun_qdecode_step, pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out,
           next_tokens_out, workspace, seq_lens_host, stream, flags)
+
+
+def sun_decode_run(pool, weights, n_steps: int, token_ids, page_tables, seq_lens, model_ids, free_pages, free_head,
+                   run_status, tokens_out, logits_out, workspace, stream=None, flags: int = 0):
+    """n_steps greedy steps in a row; token_ids, page_tables, seq_lens and free_head are updated on the device."""
+    batch, max_pages = page_tables.shape
+    n_free = int(free_pages.numel()) if free_pages is not None else 0
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().sun_decode_run(pool.handle if pool is not None else None,
+                                weights.handle if weights is not None else None, batch, n_steps, _p(token_ids),
+                                _p(page_tables), max_pages, _p(seq_lens), _p(model_ids), _p(free_pages), n_free,
+                                _p(free_head), _p(run_status), _p(tokens_out), _p(logits_out), _p(workspace), ws_bytes,
+                                _stream(stream), flags))
 
 
 def sun_paged_attention(pool, layer: int, q, page_tables, n_tokens, out, workspace, n_tokens_host=None, stream=None):

@@ -672,6 +672,51 @@ int sun_qdecode_step(sun_kv_pool* pool, const sun_weights* weights, int batch, c
                      logits_out, next_tokens_out, workspace, workspace_bytes, stream, flags);
 }
 
+// ---------------------------------------------------------------- multi-step run
+int sun_decode_run(sun_kv_pool* pool_, const sun_weights* weights_, int batch, int n_steps, int32_t* token_ids,
+                   int32_t* page_tables, int max_pages, int32_t* seq_lens, const int32_t* model_ids,
+                   const int32_t* free_pages, int n_free, int32_t* free_head, int32_t* run_status, int32_t* tokens_out,
+                   float* logits_out, void* workspace, size_t workspace_bytes, void* stream, unsigned flags) {
+    if (!pool_ || !weights_) return fail(SUN_ERR_NULL, "pool or weights is NULL");
+    if (!free_head || !run_status || !tokens_out) return fail(SUN_ERR_NULL, "free_head, run_status or tokens_out is NULL");
+    if (n_free < 0 || (n_free > 0 && !free_pages)) return fail(SUN_ERR_NULL, "free_pages is NULL but n_free > 0");
+    if (n_steps < 1) return fail(SUN_ERR_SHAPE, "n_steps must be >= 1");
+    const Weights& W = *(const Weights*)weights_;
+    if (flags & SUN_VALIDATE) {
+        const KvPool& pool = *(const KvPool*)pool_;
+        if (!token_ids || !page_tables || !seq_lens || !model_ids) return fail(SUN_ERR_NULL, "a required device pointer is NULL");
+        if (batch < 1 || batch > kMaxBatchTile || max_pages < 1) return fail(SUN_ERR_SHAPE, "bad batch or max_pages");
+        hipStream_t st = (hipStream_t)stream;
+        std::vector<int32_t> fp((size_t)n_free), tabs((size_t)batch * max_pages);
+        int32_t head = 0;
+        SUN_HIP_CHECK(hipMemcpyAsync(fp.data(), free_pages, fp.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(tabs.data(), page_tables, tabs.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(&head, free_head, 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipStreamSynchronize(st));
+        if (head < 0 || head > n_free) return fail(SUN_ERR_PAGE_RANGE, "free_head %d outside [0, %d]", head, n_free);
+        std::vector<char> used((size_t)pool.lay.n_pages, 0);
+        for (int32_t pg : tabs)
+            if (pg >= 0 && pg < pool.lay.n_pages) used[pg] = 1;
+        for (int i = head; i < n_free; ++i) {
+            const int32_t pg = fp[i];
+            if (pg < 0 || pg >= pool.lay.n_pages) return fail(SUN_ERR_PAGE_RANGE, "free_pages[%d] = %d outside the pool", i, pg);
+            if (used[pg]) return fail(SUN_ERR_PAGE_RANGE, "free_pages[%d] = %d is referenced by a page table or listed twice", i, pg);
+            used[pg] = 1;
+        }
+    }
+    for (int s = 0; s < n_steps; ++s) {
+        const bool last = s + 1 == n_steps;
+        // only the first step can be validated from the host: later inputs exist on the device only
+        const int rc = step_impl(pool_, weights_, W.quant, batch, token_ids, page_tables, max_pages, seq_lens, nullptr,
+                                 model_ids, last ? logits_out : nullptr, tokens_out + (size_t)s * batch, workspace,
+                                 workspace_bytes, stream, s == 0 ? flags : (flags & ~SUN_VALIDATE));
+        if (rc != SUN_OK) return rc;
+        SUN_HIP_CHECK(launch_advance(tokens_out + (size_t)s * batch, batch, max_pages, free_pages, n_free, token_ids,
+                                     page_tables, seq_lens, free_head, run_status, s == 0, (hipStream_t)stream));
+    }
+    return SUN_OK;
+}
+
 // ---------------------------------------------------------------- single operations
 int sun_paged_attention(sun_kv_pool* pool_, int layer, int batch, const float* q, const int32_t* page_tables,
                         int max_pages, const int32_t* n_tokens, const int32_t* n_tokens_host, float* out,

@@ -69,6 +69,10 @@ hipError_t launch_embed(const sun_model_cfg& cfg, const void* embed, const int32
 // h_f32: row-major fp32 or NULL; h_tiled: tiled bf16 or NULL; hsum: group sums or NULL.
 hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float* partial, int nparts, int ld_rows,
                                 const void* gain, int batch, float* h_f32, void* h_tiled, float* hsum, hipStream_t st);
+// Between two steps of a run: token feedback, length + 1, page allocation in request order.
+hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const int32_t* free_pages, int n_free,
+                          int32_t* token_ids, int32_t* page_tables, int32_t* seq_lens, int32_t* free_head,
+                          int32_t* status, bool clear_status, hipStream_t st);
 hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, int batch, float* table,
                              hipStream_t st);
 // qkv partial sums [nparts][ld_rows][Nqkv] -> rotated q fp32 [batch, Hq*d]; K,V (bf16) appended to the pool.

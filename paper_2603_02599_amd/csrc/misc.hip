@@ -393,6 +393,63 @@ hipError_t launch_argmax(const float* logits, int batch, int vocab, float* part_
     return hipGetLastError();
 }
 
+// ---------------- bookkeeping between the steps of a run ----------------
+// One workgroup.  Request b feeds its generated token back and grows by one position.  If that
+// position opens a page its table does not have yet, it takes the next unused entry of the free
+// list; requests are served in index order (an exclusive scan over the requests that need a page).
+// A request that finds the list empty, or whose table is full, keeps its length and re-decodes the
+// same position; status bit 0 / bit 1 records that.
+__global__ __launch_bounds__(1024) void advance_kernel(const int32_t* __restrict__ next, int batch, int max_pages,
+                                                       const int32_t* __restrict__ free_pages, int n_free,
+                                                       int32_t* __restrict__ token_ids, int32_t* __restrict__ page_tables,
+                                                       int32_t* __restrict__ seq_lens, int32_t* __restrict__ free_head,
+                                                       int32_t* __restrict__ status, int clear_status) {
+    __shared__ int scan[1024];
+    const int t = threadIdx.x;
+    if (clear_status && t == 0) *status = 0;  // ordered before the atomicOr below by the barriers in between
+    int new_len = 0, slot_page = 0, wants = 0, full = 0;
+    if (t < batch) {
+        token_ids[t] = next[t];
+        new_len = seq_lens[t] + 1;
+        slot_page = new_len / kPageTokens;
+        full = slot_page >= max_pages;
+        wants = !full && new_len % kPageTokens == 0 && page_tables[(size_t)t * max_pages + slot_page] < 0;
+    }
+    scan[t] = wants;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int v = t >= o ? scan[t - o] : 0;
+        __syncthreads();
+        scan[t] += v;
+        __syncthreads();
+    }
+    const int head = *free_head;
+    const int rank = scan[t] - wants;  // requests before this one that take a page
+    int flags = 0;
+    if (t < batch) {
+        if (full) {
+            flags = 2;
+        } else if (wants && head + rank >= n_free) {
+            flags = 1;
+        } else {
+            if (wants) page_tables[(size_t)t * max_pages + slot_page] = free_pages[head + rank];
+            seq_lens[t] = new_len;
+        }
+    }
+    if (flags) atomicOr(status, flags);
+    __syncthreads();  // every thread has read *free_head
+    if (t == 1023) *free_head = min(head + scan[1023], n_free);
+}
+
+hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const int32_t* free_pages, int n_free,
+                          int32_t* token_ids, int32_t* page_tables, int32_t* seq_lens, int32_t* free_head,
+                          int32_t* status, bool clear_status, hipStream_t st) {
+    if (batch > 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1024), 0, st, next, batch, max_pages, free_pages, n_free, token_ids,
+                       page_tables, seq_lens, free_head, status, clear_status ? 1 : 0);
+    return hipGetLastError();
+}
+
 // ---------------- layout helpers ----------------
 __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict__ x, int rows, int K, int mb,
                                                         u32x4* __restrict__ tiled, float* __restrict__ hsum) {

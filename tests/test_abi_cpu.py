@@ -131,6 +131,15 @@ def test_step_rejects_bad_arguments_before_enqueueing(lib):
     assert step(wsb=need - 1) == 4 and b"workspace" in lib.sun_last_error()
     assert step(ws=FAKE + 8) == 4
     assert step(fn=lib.sun_qdecode_step) == 2          # dense weights handed to the QSUN entry point
+
+    def run(pool=pool, w=w, batch=8, steps=3, tok=FAKE, head=FAKE, status=FAKE, out=FAKE, free=FAKE, n_free=4, wsb=need):
+        return lib.sun_decode_run(pool, w, batch, steps, tok, FAKE, 9, FAKE, FAKE, free, n_free, head, status, out, None,
+                                  FAKE, wsb, None, 0)
+
+    assert run(pool=None) == 1 and run(w=None) == 1 and run(head=None) == 1 and run(status=None) == 1
+    assert run(out=None) == 1 and run(free=None) == 1
+    assert run(steps=0) == 2 and run(batch=0) == 2 and run(n_free=-1) == 1
+    assert run(wsb=need - 1) == 4 and run(tok=None) == 1
     other = sun.make_cfg(wl.TINY_Q, "f32")
     rc, pool2 = _pool(lib, other)
     assert rc == 0 and step(pool=pool2) == 2           # pool and weights of different shapes
