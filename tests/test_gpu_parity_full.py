@@ -107,3 +107,67 @@ def test_cfg5_14b_shape_sampled(H):
         case, rep = _sampled_parity(H, work, sw, 3)
         del case, sw
         torch.cuda.empty_cache()
+
+
+def test_cfg2_batch64_run_of_three_steps_sampled(H, dense8b):
+    """sun_decode_run at the benchmark size: 3 steps of cfg2 with requests placed so that several cross a
+    page boundary.  Page bookkeeping for all 64 requests is checked against a host replay of the counting
+    argument; the oracle replays 6 sampled requests fed with the GPU's tokens."""
+    n_steps = 3
+    work = wl.make_workload("cfg2")
+    work.seq_lens = (work.seq_lens - work.seq_lens % 16 + np.arange(work.batch) % 16).astype(np.int32)  # all residues mod 16
+    rng = np.random.default_rng(work.seed + 9)
+    work.page_tables, work.n_pages = wl.deal_page_tables(work.seq_lens, rng)
+    B = work.batch
+    cols = (int(work.seq_lens.max()) + n_steps) // 16 + 1
+    wide = np.full((B, cols), -1, np.int32)
+    wide[:, :work.max_pages] = work.page_tables
+    referenced = np.zeros(work.n_pages, bool)
+    referenced[work.page_tables[work.page_tables >= 0]] = True
+    free = np.flatnonzero(~referenced).astype(np.int32)
+    # host replay: which request takes which free page at which step
+    expect, head, cur = wide.copy(), 0, work.seq_lens.copy()
+    for _ in range(n_steps):
+        for i in range(B):
+            cur[i] += 1
+            if cur[i] % 16 == 0:
+                expect[i, cur[i] // 16] = free[head]
+                head += 1
+    assert head >= 8, "the test should exercise page allocation"
+    work.page_tables = expect                      # the oracle sees the pages as already provided
+    case = H.GpuCase(work, shared=dense8b)
+    rows = sorted(set(_sample_rows(work, 4)) | {int(np.flatnonzero(work.seq_lens % 16 == 15)[0]),
+                                                 int(np.flatnonzero(work.seq_lens % 16 == 14)[0])})
+    H.say(f"cfg2 run of {n_steps} steps: oracle on rows {rows} (lengths {[int(work.seq_lens[r]) for r in rows]})")
+    before_host, opool, tabs, used = case.extract_pool(rows)
+    host = before_host  # the oracle pool aliases this array and mutates it
+    before = before_host.copy()
+    d_tab = torch.from_numpy(wide).cuda()
+    d_tok, d_len = case.tokens.clone(), case.lens.clone()
+    d_free = torch.from_numpy(free).cuda()
+    d_head = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_out = torch.empty((n_steps, B), dtype=torch.int32, device="cuda")
+    ws = torch.empty(sun.sun_workspace_bytes(case.cfg, B, cols), dtype=torch.uint8, device="cuda")
+    sun.sun_decode_run(case.pool, case.weights, n_steps, d_tok, d_tab, d_len, case.ids, d_free, d_head, d_status,
+                       d_out, case.logits, ws, flags=sun.SUN_VALIDATE)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_tab.cpu().numpy(), expect) and int(d_head.cpu()[0]) == head and int(d_status.cpu()[0]) == 0
+    assert np.array_equal(d_len.cpu().numpy(), work.seq_lens + n_steps)
+    got = d_out.cpu().numpy()
+    ref = H.orc.decode_run(H.orc.make_cfg(work.shape), case.oracle_params(), opool, work.tokens[rows], tabs,
+                           work.seq_lens[rows], work.model_ids[rows], np.zeros(0, np.int32), 0, n_steps,
+                           forced_tokens=got[:, rows], keep_logits=True)
+    near = []
+    for s in range(n_steps):
+        near += [(s, rows[i]) for i in H.check_next_tokens(got[s][rows], ref["logits"][s], 2e-2)]
+    last = case.logits.cpu().numpy()[rows]
+    H.say(f"   last-step logits {H.logits_report(last, ref['logits'][-1])}")
+    H.check_logits(last, ref["logits"][-1], "bf16")
+    st = H.layout_strides(case.lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
+    mask = np.zeros(before.size, dtype=bool)
+    for s in range(n_steps):
+        mask |= H.appended_mask(work.shape, st, before.size, tabs, work.seq_lens[rows] + s)
+    off, total = H.check_appended_kv(case.pool_pages_now(used), host, before, mask, "bf16")
+    H.say(f"   near-ties {near}; pages taken {head}; appended K/V off by >=1 bf16 ulp: {off} of {total}")
