@@ -169,6 +169,29 @@ def pool_elems(shape, n_pages: int, page_tokens: int = 16) -> int:
     return shape.n_layers * n_pages * 2 * shape.n_kv_heads * page_tokens * shape.head_dim
 
 
+def kv_ingest(base: np.ndarray, strides: Dict[str, int], k_src: np.ndarray, v_src: np.ndarray, first_pos: int,
+              page_table, page_tokens: int = 16) -> None:
+    """Places a cache computed elsewhere (Eq. 2: the prefill module's C_T for a prompt, or a later chunk of
+    it) into the pages a request owns: token t of the source becomes position first_pos + t, which lives in
+    slot (first_pos + t) % page_tokens of page page_table[(first_pos + t) // page_tokens].  k_src, v_src:
+    uint16 bf16 bit patterns [n_layers, n_tokens, n_kv_heads, head_dim]; base: the pool as a flat uint16
+    array, addressed through `strides` (element strides and offsets as in make_pool).  Nothing is converted:
+    a byte-exact scatter."""
+    assert k_src.dtype == np.uint16 and v_src.dtype == np.uint16 and k_src.shape == v_src.shape
+    nl, nt, hkv, d = k_src.shape
+    for l in range(nl):
+        for t in range(nt):
+            pos = first_pos + t
+            page, slot = int(page_table[pos // page_tokens]), pos % page_tokens
+            if page < 0:
+                raise ValueError(f"position {pos} has no page")
+            for h in range(hkv):
+                for kv, src in (("k", k_src), ("v", v_src)):
+                    o = (strides[kv + "_off"] + l * strides[kv + "_layer"] + page * strides[kv + "_page"] +
+                         h * strides[kv + "_head"] + slot * strides[kv + "_token"])
+                    base[o + np.arange(d) * strides[kv + "_dim"]] = src[l, t, h]
+
+
 def decode_step(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_lens, model_ids,
                 mode: int = 0, want_rowsums: bool = False, want_attn: bool = False):
     """Runs one decode step; mutates the pool (appends the new K/V).  Returns a dict."""

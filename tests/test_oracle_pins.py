@@ -144,12 +144,7 @@ def _prefill_into_pool(orc, shape, cfg, params, toks, n_pages, table, rng):
         _, K, V = orc.full_forward(cfg, params, toks, round_kv=True, want_kv=True)
         kb, vb = orc.bf16_bits(K), orc.bf16_bits(V)
         assert np.array_equal(orc.bf16_values(kb), K)  # already on the bf16 grid
-        for l in range(shape.n_layers):
-            for t in range(len(toks)):
-                for h in range(shape.n_kv_heads):
-                    o = l * st["k_layer"] + int(table[t // PT]) * st["k_page"] + h * st["k_head"] + (t % PT) * st["k_token"]
-                    base[st["k_off"] + o: st["k_off"] + o + shape.head_dim] = kb[l, t, h]
-                    base[st["v_off"] + o: st["v_off"] + o + shape.head_dim] = vb[l, t, h]
+        orc.kv_ingest(base, st, kb, vb, 0, table, PT)
     return base, pool
 
 
