@@ -174,6 +174,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--ingest-tokens", type=int, default=0,
+                    help="instead of decoding: time sun_kv_pool_ingest of one prompt cache of this many tokens "
+                         "(shape of --workload), K times; prints its own JSON line (tokens/s and GB/s read+written)")
     ap.add_argument("--mode", default="step", choices=["step", "run"],
                     help="step: K independent calls of the decode step on the same inputs (default). "
                          "run: one sun_decode_run call of K steps with token feedback, growing caches and page "
@@ -202,6 +205,36 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     import gpu_harness as H   # plumbing only (device buffers, handles); the oracle is used in cpu_baseline alone
 
+    if args.ingest_tokens > 0:
+        from paper_2603_02599_amd import workloads as wl
+        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
+        n = args.ingest_tokens
+        pages = (n + 15) // 16
+        cfg = sun.make_cfg(shape, "bf16")
+        mem = torch.empty(sun.sun_kv_pool_bytes(cfg, pages) // 2, dtype=torch.bfloat16, device="cuda")
+        pool = sun.sun_kv_pool_create(cfg, mem, 16, 1)
+        k = torch.randn((shape.n_layers, n, shape.n_kv_heads, shape.head_dim), device="cuda").to(torch.bfloat16)
+        v = torch.randn_like(k)
+        row = torch.randperm(pages, device="cuda").to(torch.int32)
+        for _ in range(args.warmup):
+            sun.sun_kv_pool_ingest(pool, 0, k, v, 0, row)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            sun.sun_kv_pool_ingest(pool, 0, k, v, 0, row)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        moved = 2.0 * 2 * k.numel() * 2   # K and V, read and written, 2 bytes each
+        print(json.dumps({"metric": "kv-ingest tokens/sec", "value": n / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                          "dtype": "bf16 (byte copy)", "data": "synthetic",
+                          "config": {"workload": f"one prompt cache of {n} tokens, {shape.name} shape, shuffled pages"},
+                          "roofline": {"bound": "hbm", "kernel": "kv_ingest_kernel", "achieved": moved / (ms * 1e-3) / 1e9,
+                                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                       "traffic": None, "bytes_per_launch": moved}}))
+        return
     work, desc = build_workload(args.workload)
     shape = work.shape
     if args.mode == "run":

@@ -108,6 +108,31 @@ int sun_kv_pool_create(const sun_model_cfg* cfg, void* dev_mem, size_t bytes, in
 int sun_kv_pool_layout(const sun_kv_pool* pool, sun_kv_layout* out);
 void sun_kv_pool_destroy(sun_kv_pool* pool);
 
+/*
+ * Places a cache produced elsewhere into the pages a request owns: the prompt's cache C_T that a
+ * task-specific prefill module computed (Eq. 2) and handed to this decode worker (Section 3.2.2,
+ * disaggregated serving), or a later chunk of it.  After the call the decode step can consume
+ * the request like any other (the cache of Eq. 4 is prompt KV followed by decode-generated KV).
+ *   model_id   source model that produced the cache; a tag: it is counted, never used for addressing
+ *   k_src, v_src  dev bf16 [n_layers, n_tokens, n_kv_heads, head_dim], contiguous, 16-byte aligned;
+ *              K already rotated, as the decode step stores it
+ *   first_pos  position of the source's token 0 in the request (0 for a whole prompt)
+ *   page_table dev int32 [max_pages], the request's row; entries first_pos/16 .. (first_pos+n_tokens-1)/16
+ *              must name pages of the pool that no other request writes
+ * A byte-exact scatter: only the n_tokens positions are written (a chunk may start or end inside a
+ * page).  Enqueued on `stream`.  Without SUN_VALIDATE a page id outside the pool skips that page;
+ * with it the row is copied to the host (synchronises) and checked: SUN_ERR_PAGE_RANGE.
+ * Errors: SUN_ERR_NULL, SUN_ERR_MODEL_ID, SUN_ERR_SEQ_LEN (n_tokens < 1, first_pos < 0, or the row is
+ * too short), SUN_ERR_SHAPE (misaligned source).
+ */
+int sun_kv_pool_ingest(sun_kv_pool* pool, int model_id, const void* k_src, const void* v_src,
+                       int n_tokens, int first_pos, const int32_t* page_table, int max_pages,
+                       void* stream, unsigned flags);
+
+/* Tokens ingested so far for one source model (host-side count; the pool itself is not partitioned
+ * by model).  Errors: SUN_ERR_NULL, SUN_ERR_MODEL_ID. */
+int sun_kv_pool_model_tokens(const sun_kv_pool* pool, int model_id, int64_t* tokens);
+
 /* ------------------------------------------------------------------ weights */
 
 /*

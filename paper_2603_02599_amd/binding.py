@@ -22,6 +22,7 @@ PROFILE_KINDS = ("attn_split", "attn_combine", "qkv_proj", "o_proj", "gate_up_pr
 
 EXPORTS = [
     "sun_kv_pool_bytes", "sun_kv_pool_create", "sun_kv_pool_layout", "sun_kv_pool_destroy",
+    "sun_kv_pool_ingest", "sun_kv_pool_model_tokens",
     "sun_weights_pack_bytes", "sun_weights_create", "sun_weights_destroy",
     "sun_qweights_pack_bytes", "sun_qweights_create", "sun_quantize_w4",
     "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step", "sun_decode_run",
@@ -98,6 +99,9 @@ def lib() -> C.CDLL:
                                           C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
         L.sun_quantize_w4.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sun_kv_pool_ingest.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
+                                         C.c_int, C.c_void_p, C.c_uint]
+        L.sun_kv_pool_model_tokens.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]
         L.sun_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
         step_args = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
@@ -295,6 +299,18 @@ def sun_qdecode_step(pool, weights, token_ids, page_tables, seq_lens, model_ids,
                      workspace, seq_lens_host=None, stream=None, flags: int = 0):
     _step(lib().sun_qdecode_step, pool, weights, token_ids, page_tables, seq_lens, model_ids, logits_out,
           next_tokens_out, workspace, seq_lens_host, stream, flags)
+
+
+def sun_kv_pool_ingest(pool, model_id: int, k_src, v_src, first_pos: int, page_table_row, stream=None, flags: int = 0):
+    """k_src, v_src: bf16 tensors [n_layers, n_tokens, n_kv_heads, head_dim]; page_table_row: int32 [max_pages]."""
+    _check(lib().sun_kv_pool_ingest(pool.handle, model_id, _p(k_src), _p(v_src), int(k_src.shape[1]), first_pos,
+                                    _p(page_table_row), int(page_table_row.numel()), _stream(stream), flags))
+
+
+def sun_kv_pool_model_tokens(pool, model_id: int) -> int:
+    n = C.c_int64()
+    _check(lib().sun_kv_pool_model_tokens(pool.handle, model_id, C.byref(n)))
+    return int(n.value)
 
 
 def sun_decode_run(pool, weights, n_steps: int, token_ids, page_tables, seq_lens, model_ids, free_pages, free_head,

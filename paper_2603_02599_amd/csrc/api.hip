@@ -222,6 +222,7 @@ int sun_kv_pool_create(const sun_model_cfg* cfg, void* dev_mem, size_t bytes, in
     p->base = (uint16_t*)dev_mem;
     p->lay = make_layout(*cfg, n_pages);
     p->n_source_models = n_source_models;
+    p->ingested.assign((size_t)n_source_models, 0);
     *out = (sun_kv_pool*)p;
     return SUN_OK;
 }
@@ -233,6 +234,42 @@ int sun_kv_pool_layout(const sun_kv_pool* pool, sun_kv_layout* out) {
 }
 
 void sun_kv_pool_destroy(sun_kv_pool* pool) { delete (KvPool*)pool; }
+
+int sun_kv_pool_ingest(sun_kv_pool* pool_, int model_id, const void* k_src, const void* v_src, int n_tokens,
+                       int first_pos, const int32_t* page_table, int max_pages, void* stream, unsigned flags) {
+    if (!pool_ || !k_src || !v_src || !page_table) return fail(SUN_ERR_NULL, "NULL argument");
+    KvPool& pool = *(KvPool*)pool_;
+    if (model_id < 0 || model_id >= pool.n_source_models)
+        return fail(SUN_ERR_MODEL_ID, "source-model id %d outside [0, %d)", model_id, pool.n_source_models);
+    if (n_tokens < 1 || first_pos < 0 || max_pages < 1) return fail(SUN_ERR_SEQ_LEN, "n_tokens must be >= 1, first_pos >= 0");
+    const long long last = (long long)first_pos + n_tokens - 1;
+    if (last / kPageTokens >= max_pages)
+        return fail(SUN_ERR_SEQ_LEN, "positions up to %lld need %lld page-table entries, the row has %d", last,
+                    last / kPageTokens + 1, max_pages);
+    if (((uintptr_t)k_src | (uintptr_t)v_src) % 16) return fail(SUN_ERR_SHAPE, "k_src and v_src must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    if (flags & SUN_VALIDATE) {
+        std::vector<int32_t> row((size_t)max_pages);
+        SUN_HIP_CHECK(hipMemcpyAsync(row.data(), page_table, row.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipStreamSynchronize(st));
+        for (long long lp = first_pos / kPageTokens; lp <= last / kPageTokens; ++lp)
+            if (row[lp] < 0 || row[lp] >= pool.lay.n_pages)
+                return fail(SUN_ERR_PAGE_RANGE, "page-table entry %lld = %d outside [0, %lld)", lp, row[lp],
+                            (long long)pool.lay.n_pages);
+    }
+    SUN_HIP_CHECK(launch_kv_ingest(pool, k_src, v_src, n_tokens, first_pos, page_table, st));
+    pool.ingested[model_id] += n_tokens;
+    return SUN_OK;
+}
+
+int sun_kv_pool_model_tokens(const sun_kv_pool* pool_, int model_id, int64_t* tokens) {
+    if (!pool_ || !tokens) return fail(SUN_ERR_NULL, "NULL argument");
+    const KvPool& pool = *(const KvPool*)pool_;
+    if (model_id < 0 || model_id >= pool.n_source_models)
+        return fail(SUN_ERR_MODEL_ID, "source-model id %d outside [0, %d)", model_id, pool.n_source_models);
+    *tokens = pool.ingested[model_id];
+    return SUN_OK;
+}
 
 // ---------------------------------------------------------------- weights
 static void mat_dims(const sun_model_cfg& c, int which, int& N, int& K) {

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/sun.h"
 
 namespace sun {
@@ -99,6 +101,7 @@ struct KvPool {
     uint16_t* base;
     sun_kv_layout lay;
     int n_source_models;
+    std::vector<int64_t> ingested;  // tokens ingested per source model (host side)
 };
 
 enum MatKind { MAT_NONE = 0, MAT_F32 = 1, MAT_BF16_PACKED = 2, MAT_W4_PACKED = 3, MAT_W4_LOGICAL = 4 };

@@ -69,6 +69,10 @@ hipError_t launch_embed(const sun_model_cfg& cfg, const void* embed, const int32
 // h_f32: row-major fp32 or NULL; h_tiled: tiled bf16 or NULL; hsum: group sums or NULL.
 hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float* partial, int nparts, int ld_rows,
                                 const void* gain, int batch, float* h_f32, void* h_tiled, float* hsum, hipStream_t st);
+// k_src, v_src: bf16 [n_layers][n_tokens][Hkv][d]; token t lands at position first_pos + t of the request whose
+// page-table row is given.
+hipError_t launch_kv_ingest(const KvPool& pool, const void* k_src, const void* v_src, int n_tokens, int first_pos,
+                            const int32_t* page_table, hipStream_t st);
 // Between two steps of a run: token feedback, length + 1, page allocation in request order.
 hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const int32_t* free_pages, int n_free,
                           int32_t* token_ids, int32_t* page_tables, int32_t* seq_lens, int32_t* free_head,

@@ -393,6 +393,83 @@ hipError_t launch_argmax(const float* logits, int batch, int vocab, float* part_
     return hipGetLastError();
 }
 
+// ---------------- KV ingest: a contiguous cache into a request's pages ----------------
+// One workgroup per (logical page, kv head, layer).  Source [layer][token][head][dim] bf16; token t is
+// position first_pos + t.  K rows are copied 16 bytes at a time; V goes through an LDS tile because the
+// pool keeps it transposed ([dim][token]).  Only the positions of the source are written, so a chunk can
+// be appended to a partly filled page.  A page id outside the pool skips the page.
+struct IngestArgs {
+    uint16_t* kbase;  // pool base + k_off
+    uint16_t* vbase;
+    int64_t k_layer, k_page, k_head, v_layer, v_page, v_head;
+    const uint16_t* k_src;
+    const uint16_t* v_src;
+    const int32_t* page_table;
+    int n_tokens, first_pos, Hkv, D, n_pages;
+};
+
+__global__ __launch_bounds__(256) void kv_ingest_kernel(IngestArgs a) {
+    __shared__ uint16_t tile[kPageTokens][128 + 8];
+    const int lp = a.first_pos / kPageTokens + blockIdx.x, h = blockIdx.y, l = blockIdx.z, tid = threadIdx.x;
+    const int page = a.page_table[lp];
+    if (page < 0 || page >= a.n_pages) return;
+    const int p0 = lp * kPageTokens;
+    const int s_lo = max(a.first_pos - p0, 0), s_hi = min(a.first_pos + a.n_tokens - p0, kPageTokens);  // valid slots
+    const int D = a.D, cpt = D / 8;                                                                    // 16-byte chunks per token
+    uint16_t* kd = a.kbase + l * a.k_layer + page * a.k_page + h * a.k_head;
+    uint16_t* vd = a.vbase + l * a.v_layer + page * a.v_page + h * a.v_head;
+    for (int idx = tid; idx < kPageTokens * cpt; idx += 256) {
+        const int s = idx / cpt, c = idx % cpt;
+        if (s < s_lo || s >= s_hi) continue;
+        const size_t so = (((size_t)l * a.n_tokens + (p0 + s - a.first_pos)) * a.Hkv + h) * D + c * 8;
+        *reinterpret_cast<u32x4*>(kd + s * D + c * 8) = *reinterpret_cast<const u32x4*>(a.k_src + so);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(a.v_src + so);
+        *reinterpret_cast<u32x4*>(&tile[s][c * 8]) = v;
+    }
+    __syncthreads();
+    // V^T: thread <-> (dim, half of the page's 16 slots)
+    for (int idx = tid; idx < D * 2; idx += 256) {
+        const int dim = idx >> 1, half = idx & 1, s0 = half * 8;
+        if (s0 >= s_lo && s0 + 8 <= s_hi) {
+            uint16_t e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = tile[s0 + j][dim];
+            u32x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = (uint32_t)e[2 * j] | ((uint32_t)e[2 * j + 1] << 16);
+            *reinterpret_cast<u32x4*>(vd + dim * kPageTokens + s0) = o;
+        } else {
+            for (int j = 0; j < 8; ++j)
+                if (s0 + j >= s_lo && s0 + j < s_hi) vd[dim * kPageTokens + s0 + j] = tile[s0 + j][dim];
+        }
+    }
+}
+
+hipError_t launch_kv_ingest(const KvPool& pool, const void* k_src, const void* v_src, int n_tokens, int first_pos,
+                            const int32_t* page_table, hipStream_t st) {
+    const sun_model_cfg& c = pool.cfg;
+    const sun_kv_layout& L = pool.lay;
+    if (L.k_dim != 1 || L.k_token != c.head_dim || L.v_token != 1 || L.v_dim != kPageTokens || c.head_dim > 128 ||
+        c.head_dim % 8)
+        return hipErrorInvalidValue;
+    IngestArgs a{};
+    a.kbase = pool.base + L.k_off;
+    a.vbase = pool.base + L.v_off;
+    a.k_layer = L.k_layer; a.k_page = L.k_page; a.k_head = L.k_head;
+    a.v_layer = L.v_layer; a.v_page = L.v_page; a.v_head = L.v_head;
+    a.k_src = (const uint16_t*)k_src;
+    a.v_src = (const uint16_t*)v_src;
+    a.page_table = page_table;
+    a.n_tokens = n_tokens;
+    a.first_pos = first_pos;
+    a.Hkv = c.n_kv_heads;
+    a.D = c.head_dim;
+    a.n_pages = (int)L.n_pages;
+    const int pages = (first_pos + n_tokens - 1) / kPageTokens - first_pos / kPageTokens + 1;
+    hipLaunchKernelGGL(kv_ingest_kernel, dim3(pages, c.n_kv_heads, c.n_layers), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // ---------------- bookkeeping between the steps of a run ----------------
 // One workgroup.  Request b feeds its generated token back and grows by one position.  If that
 // position opens a page its table does not have yet, it takes the next unused entry of the free

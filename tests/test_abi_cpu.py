@@ -151,6 +151,16 @@ def test_step_rejects_bad_arguments_before_enqueueing(lib):
 def test_single_op_argument_checks(lib):
     cfg = sun.make_cfg(wl.TINY, "f32")
     rc, pool = _pool(lib, cfg)
+    ing = lib.sun_kv_pool_ingest
+    assert ing(None, 0, FAKE, FAKE, 4, 0, FAKE, 2, None, 0) == 1 and ing(pool, 0, None, FAKE, 4, 0, FAKE, 2, None, 0) == 1
+    assert ing(pool, 0, FAKE, FAKE, 4, 0, None, 2, None, 0) == 1
+    assert ing(pool, -1, FAKE, FAKE, 4, 0, FAKE, 2, None, 0) == 7 and ing(pool, 99, FAKE, FAKE, 4, 0, FAKE, 2, None, 0) == 7
+    assert ing(pool, 0, FAKE, FAKE, 0, 0, FAKE, 2, None, 0) == 6 and ing(pool, 0, FAKE, FAKE, 4, -1, FAKE, 2, None, 0) == 6
+    assert ing(pool, 0, FAKE, FAKE, 4, 30, FAKE, 2, None, 0) == 6      # positions 30..33 need a third table entry
+    assert ing(pool, 0, FAKE + 2, FAKE, 4, 0, FAKE, 2, None, 0) == 2   # misaligned source
+    n = C.c_int64(-1)
+    assert lib.sun_kv_pool_model_tokens(pool, 0, C.byref(n)) == 0 and n.value == 0
+    assert lib.sun_kv_pool_model_tokens(pool, 0, None) == 1 and lib.sun_kv_pool_model_tokens(pool, 7, C.byref(n)) == 7
     assert lib.sun_paged_attention(pool, 5, 1, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == 2
     assert lib.sun_paged_attention(pool, 0, 1, None, FAKE, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == 1
     assert lib.sun_paged_attention(pool, 0, 1, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, 16, None) == 4
