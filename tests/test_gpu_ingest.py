@@ -99,3 +99,53 @@ def test_decode_step_consumes_an_ingested_prompt(H):
     got = case.logits.cpu().numpy()[0]
     assert np.abs(got - logits[L]).max() <= 1e-4, f"max abs {np.abs(got - logits[L]).max():.3e}"
     assert int(case.next.cpu()[0]) == int(np.argmax(logits[L]))
+
+
+def test_shared_decode_over_caches_from_different_prefill_models(H):
+    """A miniature of the method (Section 3.2.1): three task-specific prefill models (perturbed copies of the
+    base weights, standing in for prefill-only tuning) compute the prompt caches of five requests on the CPU
+    (Eq. 2, the oracle's causal forward); the GPU ingests them into one pool and decodes all requests in one
+    batch with the single frozen decode module (Eq. 3).  Logits, tokens and appended cache entries must match
+    the oracle's decode step over the same pool."""
+    H.say("prefill by 3 perturbed models -> ingest -> shared decode")
+    shape = wl.TINY
+    lens = np.array([5, 16, 33, 70, 129], np.int32)
+    work = wl.make_workload("cfg1", batch=len(lens), n_models=3, seed=64)
+    work.seq_lens = lens
+    rng = np.random.default_rng(65)
+    work.page_tables, work.n_pages = wl.deal_page_tables(lens, rng)
+    work.model_ids = np.array([0, 1, 2, 1, 0], np.int32)
+    case = H.GpuCase(work)
+    base_w = H.weights_to_np(case.w)
+    ocfg = H.orc.make_cfg(shape)
+    prefill_params = []
+    for m in range(3):          # theta_p^(m) = theta + delta_m on every matrix (the decode module stays theta)
+        wm = {k: ([a + 0.01 * rng.standard_normal(a.shape).astype(np.float32) if a.ndim == 2 else a for a in v]
+                  if isinstance(v, list) else (v + 0.01 * rng.standard_normal(v.shape).astype(np.float32) if v.ndim == 2 else v))
+              for k, v in base_w.items()}
+        prefill_params.append((wm, H.orc.params_from_arrays(wm)))
+    for i, L in enumerate(lens):
+        prompt = rng.integers(0, shape.vocab, size=int(L)).astype(np.int32)
+        _, K, V = H.orc.full_forward(ocfg, prefill_params[work.model_ids[i]][1], prompt, round_kv=True, want_kv=True)
+        kb = torch.from_numpy(H.orc.bf16_bits(K).view(np.int16)).cuda().view(torch.bfloat16).contiguous()
+        vb = torch.from_numpy(H.orc.bf16_bits(V).view(np.int16)).cuda().view(torch.bfloat16).contiguous()
+        sun.sun_kv_pool_ingest(case.pool, int(work.model_ids[i]), kb, vb, 0, case.tables[i].contiguous(),
+                               flags=sun.SUN_VALIDATE)
+    torch.cuda.synchronize()
+    assert [sun.sun_kv_pool_model_tokens(case.pool, m) for m in range(3)] == [5 + 129, 16 + 70, 33]
+    rows = list(range(len(lens)))
+    before_host, _, tabs, used = case.extract_pool(rows)
+    ref = H.run_oracle(case, rows)                     # the oracle decodes from the pool the GPU ingested
+    case.step(flags=sun.SUN_VALIDATE)
+    got = case.logits.cpu().numpy()
+    assert np.abs(got - ref["logits"]).max() <= 1e-4
+    assert np.array_equal(case.next.cpu().numpy(), ref["next"])
+    st = H.layout_strides(case.lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
+    mask = H.appended_mask(shape, st, before_host.size, tabs, lens)
+    H.check_appended_kv(case.pool_pages_now(used), ref["pool_after"], before_host, mask, "f32")
+    # and the caches really differ by source model: the same prompt prefilled by two models gives different K
+    p = rng.integers(0, shape.vocab, size=8).astype(np.int32)
+    _, K0, _ = H.orc.full_forward(ocfg, prefill_params[0][1], p, round_kv=True, want_kv=True)
+    _, K1, _ = H.orc.full_forward(ocfg, prefill_params[1][1], p, round_kv=True, want_kv=True)
+    assert np.abs(K0 - K1).max() > 1e-3
