@@ -162,8 +162,9 @@ class KvPool:
         return sun_kv_pool_layout(self)
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().sun_kv_pool_destroy(self.handle)
+        # at interpreter shutdown the module globals may already be gone; the handle is host memory only
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.sun_kv_pool_destroy(self.handle)
             self.handle = None
 
 
@@ -190,8 +191,8 @@ class Weights:
         self.handle, self.keep, self.quant = handle, keep, quant
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().sun_weights_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.sun_weights_destroy(self.handle)
             self.handle = None
 
 
