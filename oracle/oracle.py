@@ -32,7 +32,9 @@ class Cfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
                 ("vocab", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double),
-                ("act_bf16", C.c_int32), ("pad_", C.c_int32)]
+                ("act_bf16", C.c_int32), ("qk_norm", C.c_int32), ("rope_scaling", C.c_int32),
+                ("rope_orig_max", C.c_int32), ("rope_factor", C.c_double), ("rope_low_freq", C.c_double),
+                ("rope_high_freq", C.c_double)]
 
 
 class Mat(C.Structure):
@@ -80,8 +82,11 @@ def _ptr(a: Optional[np.ndarray]):
 def make_cfg(shape, act_bf16: bool = False) -> Cfg:
     """shape: any object with the Shape fields (n_layers, hidden, ...).  act_bf16 selects the
     16-bit configuration, in which every projection consumes bf16-rounded activations."""
+    rs = getattr(shape, "rope_scaling", None)  # (factor, low_freq_factor, high_freq_factor, original_max_position)
     return Cfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
-               shape.ffn, shape.vocab, float(shape.rms_eps), float(shape.rope_base), int(act_bf16), 0)
+               shape.ffn, shape.vocab, float(shape.rms_eps), float(shape.rope_base), int(act_bf16),
+               int(bool(getattr(shape, "qk_norm", False))), 1 if rs else 0, int(rs[3]) if rs else 0,
+               float(rs[0]) if rs else 1.0, float(rs[1]) if rs else 1.0, float(rs[2]) if rs else 1.0)
 
 
 _KIND = {np.dtype(np.float32): F32, np.dtype(np.uint16): BF16, np.dtype(np.float64): F64}
@@ -109,7 +114,7 @@ class Params:
 
     def __init__(self, n_layers: int):
         self.n_layers = n_layers
-        self.mats = (Mat * (3 + 9 * n_layers))()
+        self.mats = (Mat * (3 + PER_LAYER * n_layers))()
         self.keep: List[object] = []
 
     def set(self, idx: int, m: Mat, *arrays):
@@ -118,6 +123,8 @@ class Params:
 
 
 LAYER_KEYS = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
+HEAD_NORM_KEYS = ("qn", "kn")   # gains of the optional q/k head norm, length head_dim; absent -> ones (unused)
+PER_LAYER = len(LAYER_KEYS) + len(HEAD_NORM_KEYS)
 QUANT_KEYS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd")
 
 
@@ -134,11 +141,14 @@ def params_from_arrays(w: Dict[str, object], quant: Optional[Dict[str, list]] = 
             if quant is not None and k in quant:
                 q, s, z = quant[k][l]
                 cols = w[k][l].shape[1]
-                p.set(1 + 9 * l + j, w4_mat(q, s, z, cols, group), q, s, z)
+                p.set(1 + PER_LAYER * l + j, w4_mat(q, s, z, cols, group), q, s, z)
             else:
-                p.set(1 + 9 * l + j, dense_mat(w[k][l]), w[k][l])
-    p.set(1 + 9 * nl, dense_mat(w["gf"]), w["gf"])
-    p.set(2 + 9 * nl, dense_mat(w["wlm"]), w["wlm"])
+                p.set(1 + PER_LAYER * l + j, dense_mat(w[k][l]), w[k][l])
+        for j, k in enumerate(HEAD_NORM_KEYS):
+            g = w[k][l] if k in w else np.ones(1, dtype=np.float64)
+            p.set(1 + PER_LAYER * l + len(LAYER_KEYS) + j, dense_mat(g), g)
+    p.set(1 + PER_LAYER * nl, dense_mat(w["gf"]), w["gf"])
+    p.set(2 + PER_LAYER * nl, dense_mat(w["wlm"]), w["wlm"])
     return p
 
 
@@ -305,6 +315,11 @@ def rope(u: np.ndarray, pos: int, base: float) -> np.ndarray:
     out = np.array(u, dtype=np.float64, copy=True)
     lib().orc_rope(_ptr(out), C.c_int(out.shape[0]), C.c_int64(pos), C.c_double(base))
     return out
+
+
+def rope_freq(cfg: Cfg, j: int) -> float:
+    lib().orc_rope_freq.restype = C.c_double
+    return float(lib().orc_rope_freq(C.byref(cfg), C.c_int(j)))
 
 
 def silu(z: float) -> float:

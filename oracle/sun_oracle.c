@@ -57,7 +57,11 @@ typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
     double rms_eps, rope_base;
     int32_t act_bf16; /* 16-bit configuration: the input of every projection is a bf16 value */
-    int32_t pad_;
+    int32_t qk_norm;  /* backbone option (Qwen3 class): RMSNorm over head_dim on every q and k head, with its
+                         own gain per layer, applied before the rotation */
+    int32_t rope_scaling;  /* backbone option (LLaMA-3.1 class): 0 = none, 1 = frequency-dependent scaling */
+    int32_t rope_orig_max; /* original context length of the scaling rule */
+    double rope_factor, rope_low_freq, rope_high_freq;
 } orc_cfg;
 
 /* One parameter tensor, row-major [rows, cols]; y = M x contracts over cols. */
@@ -71,9 +75,9 @@ typedef struct {
     const uint16_t *z;   /* ORC_W4: fp16 zero points, same shape */
 } orc_mat;
 
-/* Parameter table: mats[0]=E, then 9 per layer (g1,Wq,Wk,Wv,Wo,g2,Wg,Wu,Wd),
- * then g_f, W_lm. */
-enum { M_G1 = 0, M_WQ, M_WK, M_WV, M_WO, M_G2, M_WG, M_WU, M_WD, M_PER_LAYER };
+/* Parameter table: mats[0]=E, then 11 per layer (g1,Wq,Wk,Wv,Wo,g2,Wg,Wu,Wd and the
+ * head-norm gains qn, kn of length head_dim, read only under qk_norm), then g_f, W_lm. */
+enum { M_G1 = 0, M_WQ, M_WK, M_WV, M_WO, M_G2, M_WG, M_WU, M_WD, M_QN, M_KN, M_PER_LAYER };
 #define MAT_E(m) (&(m)[0])
 #define MAT_L(m, l, w) (&(m)[1 + (l) * M_PER_LAYER + (w)])
 #define MAT_GF(m, nl) (&(m)[1 + (nl) * M_PER_LAYER])
@@ -209,17 +213,45 @@ static void rmsnorm(const orc_mat *g, const double *x, int n, double eps, double
     for (int j = 0; j < n; ++j) h[j] = x[j] * r * mat_get(g, 0, j);
 }
 
+/* Rotation frequency of pair j: base^(-2j/d), and under the LLaMA-3.1 rule rescaled by wavelength:
+ * pairs whose wavelength is below orig/high_freq keep their frequency, pairs above orig/low_freq
+ * are slowed by `factor`, and in between the two are blended linearly in orig/wavelength. */
+static double rope_freq(const orc_cfg *c, int j) {
+    const double pi = 3.14159265358979323846;
+    double f = pow(c->rope_base, -2.0 * j / c->head_dim);
+    if (c->rope_scaling != 1) return f;
+    double wavelen = 2.0 * pi / f, orig = (double)c->rope_orig_max;
+    if (wavelen < orig / c->rope_high_freq) return f;
+    if (wavelen > orig / c->rope_low_freq) return f / c->rope_factor;
+    double smooth = (orig / wavelen - c->rope_low_freq) / (c->rope_high_freq - c->rope_low_freq);
+    return (1.0 - smooth) * f / c->rope_factor + smooth * f;
+}
+
 /* Rotary embedding of one head vector u[d] at 0-based position pos; pairs
- * (j, j+d/2), theta_j = base^(-2j/d). */
-static void rope(double *u, int d, int64_t pos, double base) {
-    int half = d / 2;
+ * (j, j+d/2), theta_j = rope_freq(j). */
+static void rope(const orc_cfg *cf, double *u, int64_t pos) {
+    int d = cf->head_dim, half = d / 2;
     for (int j = 0; j < half; ++j) {
-        double theta = pow(base, -2.0 * j / d);
+        double theta = rope_freq(cf, j);
         double ang = (double)pos * theta;
         double c = (double)(float)cos(ang), s = (double)(float)sin(ang);
         double a = u[j], b = u[j + half];
         u[j] = a * c - b * s;
         u[j + half] = b * c + a * s;
+    }
+}
+
+/* q and k heads of one position: optional head norm, then the rotation at pos */
+static void norm_and_rotate(const orc_cfg *c, const orc_mat *mats, int l, double *q, double *k, int64_t pos) {
+    const int d = c->head_dim;
+    double tmp[1024];
+    for (int h = 0; h < c->n_q_heads + c->n_kv_heads; ++h) {
+        double *u = h < c->n_q_heads ? q + (size_t)h * d : k + (size_t)(h - c->n_q_heads) * d;
+        if (c->qk_norm) {
+            rmsnorm(MAT_L(mats, l, h < c->n_q_heads ? M_QN : M_KN), u, d, c->rms_eps, tmp);
+            memcpy(u, tmp, sizeof(double) * d);
+        }
+        rope(c, u, pos);
     }
 }
 
@@ -390,8 +422,7 @@ int orc_decode_step(const orc_cfg *c, const orc_mat *mats, const orc_pool *pool,
             const int64_t L = seq_lens[b], n = L + 1;
             const int32_t *pt = page_tables + (size_t)b * max_pages;
             double *q = Q + (size_t)b * QD, *k = K + (size_t)b * KD, *v = Vv + (size_t)b * KD;
-            for (int h = 0; h < Hq; ++h) rope(q + h * d, d, L, c->rope_base);
-            for (int h = 0; h < Hkv; ++h) rope(k + h * d, d, L, c->rope_base);
+            norm_and_rotate(c, mats, l, q, k, L);
             /* append: slot L of the request's cache, bf16 storage */
             for (int h = 0; h < Hkv; ++h) {
                 uint16_t *kd = pool_k(pool, l, pt[L / P], h, (int)(L % P));
@@ -472,8 +503,7 @@ int orc_decode_contig_f64(const orc_cfg *c, const orc_mat *mats, int32_t token, 
         linear(MAT_L(mats, l, M_WQ), Hn, 1, q);
         linear(MAT_L(mats, l, M_WK), Hn, 1, k);
         linear(MAT_L(mats, l, M_WV), Hn, 1, v);
-        for (int h = 0; h < Hq; ++h) rope(q + h * d, d, L, c->rope_base);
-        for (int h = 0; h < Hkv; ++h) rope(k + h * d, d, L, c->rope_base);
+        norm_and_rotate(c, mats, l, q, k, L);
         double *Kl = Kc + (size_t)l * cap * KD, *Vl = Vc + (size_t)l * cap * KD;
         for (int j = 0; j < KD; ++j) {
             Kl[(size_t)L * KD + j] = round_kv ? bf16_to_double(double_to_bf16(k[j])) : k[j];
@@ -515,8 +545,7 @@ int orc_full_forward(const orc_cfg *c, const orc_mat *mats, int T, const int32_t
         linear(MAT_L(mats, l, M_WK), Hn, T, K);
         linear(MAT_L(mats, l, M_WV), Hn, T, V);
         for (int t = 0; t < T; ++t) {
-            for (int h = 0; h < Hq; ++h) rope(Q + (size_t)t * QD + h * d, d, t, c->rope_base);
-            for (int h = 0; h < Hkv; ++h) rope(K + (size_t)t * KD + h * d, d, t, c->rope_base);
+            norm_and_rotate(c, mats, l, Q + (size_t)t * QD, K + (size_t)t * KD, t);
         }
         if (round_kv)
             for (size_t i = 0; i < (size_t)T * KD; ++i) {
@@ -556,7 +585,15 @@ void orc_rmsnorm(const double *x, const double *g, int n, double eps, double *h)
     orc_mat gm = {ORC_F64, 1, n, 0, g, NULL, NULL, NULL};
     rmsnorm(&gm, x, n, eps, h);
 }
-void orc_rope(double *u, int d, int64_t pos, double base) { rope(u, d, pos, base); }
+void orc_rope(double *u, int d, int64_t pos, double base) {
+    orc_cfg c;
+    memset(&c, 0, sizeof c);
+    c.head_dim = d;
+    c.rope_base = base;
+    rope(&c, u, pos);
+}
+void orc_rope_cfg(const orc_cfg *c, double *u, int64_t pos) { rope(c, u, pos); }
+double orc_rope_freq(const orc_cfg *c, int j) { return rope_freq(c, j); }
 double orc_silu(double z) { return silu(z); }
 void orc_linear(const orc_mat *m, const double *X, int B, double *Y) { linear(m, X, B, Y); }
 int32_t orc_argmax(const double *v, int n) { return argmax_lowest(v, n); }

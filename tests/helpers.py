@@ -17,6 +17,8 @@ class MiniShape:
     vocab: int = 64
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    qk_norm: bool = False                 # RMSNorm over head_dim on q and k heads before the rotation
+    rope_scaling: tuple = None            # (factor, low_freq_factor, high_freq_factor, original_max_position)
 
 
 def random_weights(shape, rng, dtype=np.float64, std=0.3, gains_random=True):
@@ -44,6 +46,9 @@ def random_weights(shape, rng, dtype=np.float64, std=0.3, gains_random=True):
         w["wd"].append(mat(shape.hidden, shape.ffn))
     w["gf"] = gain()
     w["wlm"] = mat(shape.vocab, shape.hidden)
+    if getattr(shape, "qk_norm", False):
+        w["qn"] = [np.ascontiguousarray((1.0 + 0.2 * rng.normal(size=shape.head_dim)).astype(dtype)) for _ in range(shape.n_layers)]
+        w["kn"] = [np.ascontiguousarray((1.0 + 0.2 * rng.normal(size=shape.head_dim)).astype(dtype)) for _ in range(shape.n_layers)]
     return w
 
 
