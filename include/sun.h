@@ -71,6 +71,16 @@ typedef struct sun_model_cfg {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
     float rms_eps, rope_base;
     int32_t act_dtype;
+    /* Options of the backbone families the paper evaluates (Section 4.1); all zero = plain block. */
+    int32_t qk_norm;       /* Qwen3 class: RMSNorm over head_dim (eps = rms_eps, own gain per layer) on every
+                              q and k head before the rotation; needs q_norm / k_norm in the weight table */
+    int32_t rope_scaling;  /* LLaMA-3.1 class: 1 = rotation frequencies rescaled by wavelength: pairs with
+                              wavelength < rope_original_max_position / rope_high_freq_factor keep their
+                              frequency, those above rope_original_max_position / rope_low_freq_factor are
+                              divided by rope_factor, in between the two are blended linearly in
+                              rope_original_max_position / wavelength */
+    int32_t rope_original_max_position;
+    float rope_factor, rope_low_freq_factor, rope_high_freq_factor;
 } sun_model_cfg;
 
 /* ------------------------------------------------------------------ KV pool */
@@ -155,6 +165,8 @@ typedef struct sun_weight_ptrs {
     const void* const* wd;
     const void* gf;
     const void* wlm;
+    const void* const* q_norm; /* per layer [head_dim]; read only if cfg.qk_norm, else may be NULL */
+    const void* const* k_norm;
 } sun_weight_ptrs;
 
 typedef struct sun_weights sun_weights;
@@ -198,6 +210,8 @@ typedef struct sun_qweight_ptrs {
     const sun_qmat* wd;
     const void* gf;
     const void* wlm;
+    const void* const* q_norm; /* as in sun_weight_ptrs */
+    const void* const* k_norm;
 } sun_qweight_ptrs;
 
 size_t sun_qweights_pack_bytes(const sun_model_cfg* cfg, int group);

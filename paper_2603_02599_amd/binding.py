@@ -40,7 +40,9 @@ class SunError(RuntimeError):
 class ModelCfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
-                ("rope_base", C.c_float), ("act_dtype", C.c_int32)]
+                ("rope_base", C.c_float), ("act_dtype", C.c_int32), ("qk_norm", C.c_int32), ("rope_scaling", C.c_int32),
+                ("rope_original_max_position", C.c_int32), ("rope_factor", C.c_float),
+                ("rope_low_freq_factor", C.c_float), ("rope_high_freq_factor", C.c_float)]
 
 
 class KvLayout(C.Structure):
@@ -54,7 +56,7 @@ class KvLayout(C.Structure):
 class WeightPtrs(C.Structure):
     _fields_ = [("embed", C.c_void_p)] + [(k, C.POINTER(C.c_void_p)) for k in
                                           ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")] + \
-               [("gf", C.c_void_p), ("wlm", C.c_void_p)]
+               [("gf", C.c_void_p), ("wlm", C.c_void_p), ("q_norm", C.POINTER(C.c_void_p)), ("k_norm", C.POINTER(C.c_void_p))]
 
 
 class QMat(C.Structure):
@@ -66,7 +68,8 @@ class QWeightPtrs(C.Structure):
                 ("wq", C.POINTER(QMat)), ("wk", C.POINTER(QMat)), ("wv", C.POINTER(QMat)), ("wo", C.POINTER(QMat)),
                 ("g2", C.POINTER(C.c_void_p)),
                 ("wg", C.POINTER(QMat)), ("wu", C.POINTER(QMat)), ("wd", C.POINTER(QMat)),
-                ("gf", C.c_void_p), ("wlm", C.c_void_p)]
+                ("gf", C.c_void_p), ("wlm", C.c_void_p),
+                ("q_norm", C.POINTER(C.c_void_p)), ("k_norm", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -141,10 +144,14 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_cfg(shape, act_dtype: str) -> ModelCfg:
-    """shape: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base."""
+    """shape: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base and
+    optionally qk_norm (bool) and rope_scaling = (factor, low_freq_factor, high_freq_factor, original_max_position)."""
+    rs = getattr(shape, "rope_scaling", None)
     return ModelCfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                     shape.vocab, float(shape.rms_eps), float(shape.rope_base),
-                    {"f32": SUN_F32, "bf16": SUN_BF16}[act_dtype])
+                    {"f32": SUN_F32, "bf16": SUN_BF16}[act_dtype], int(bool(getattr(shape, "qk_norm", False))),
+                    1 if rs else 0, int(rs[3]) if rs else 0, float(rs[0]) if rs else 0.0, float(rs[1]) if rs else 0.0,
+                    float(rs[2]) if rs else 0.0)
 
 
 # ------------------------------------------------------------------ pool
@@ -201,6 +208,15 @@ def _ptr_array(tensors: Sequence[torch.Tensor]):
     return arr
 
 
+def _set_head_norms(ptrs, w, cfg: ModelCfg, keep: List[object]):
+    if not cfg.qk_norm:
+        return
+    for field, key in (("q_norm", "qn"), ("k_norm", "kn")):
+        arr = _ptr_array(w[key])
+        keep.extend([arr, w[key]])
+        setattr(ptrs, field, C.cast(arr, C.POINTER(C.c_void_p)))
+
+
 def sun_weights_pack_bytes(cfg: ModelCfg) -> int:
     return int(lib().sun_weights_pack_bytes(C.byref(cfg)))
 
@@ -215,6 +231,7 @@ def sun_weights_create(cfg: ModelCfg, w: Dict[str, object], stream=None, keep_so
         keep.append(arr)
         setattr(ptrs, k, C.cast(arr, C.POINTER(C.c_void_p)))
     ptrs.gf, ptrs.wlm = w["gf"].data_ptr(), w["wlm"].data_ptr()
+    _set_head_norms(ptrs, w, cfg, keep)
     nbytes = sun_weights_pack_bytes(cfg)
     pack = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=w["embed"].device) if cfg.act_dtype == SUN_BF16 else None
     out = C.c_void_p()
@@ -223,7 +240,7 @@ def sun_weights_create(cfg: ModelCfg, w: Dict[str, object], stream=None, keep_so
     if keep_sources or cfg.act_dtype == SUN_F32:
         keep.append(w)
     else:
-        keep.extend([w["embed"], w["g1"], w["g2"], w["gf"]])
+        keep.extend([w["embed"], w["g1"], w["g2"], w["gf"], w.get("qn"), w.get("kn")])
     return Weights(out.value, keep, False)
 
 
@@ -247,6 +264,7 @@ def sun_qweights_create(cfg: ModelCfg, w: Dict[str, object], quant: Dict[str, li
         keep.append(arr)
         setattr(ptrs, k, C.cast(arr, C.POINTER(QMat)))
     ptrs.gf, ptrs.wlm = w["gf"].data_ptr(), w["wlm"].data_ptr()
+    _set_head_norms(ptrs, w, cfg, keep)
     nbytes = sun_qweights_pack_bytes(cfg, group)
     pack = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=w["embed"].device) if cfg.act_dtype == SUN_BF16 else None
     out = C.c_void_p()

@@ -46,12 +46,21 @@ static int check_cfg(const sun_model_cfg* c) {
     } else if (c->act_dtype != SUN_F32) {
         return fail(SUN_ERR_SHAPE, "act_dtype must be SUN_F32 or SUN_BF16");
     }
+    if (c->qk_norm != 0 && c->qk_norm != 1) return fail(SUN_ERR_SHAPE, "qk_norm must be 0 or 1");
+    if (c->rope_scaling != 0 && c->rope_scaling != 1) return fail(SUN_ERR_SHAPE, "rope_scaling must be 0 or 1");
+    if (c->rope_scaling == 1 && (!(c->rope_factor > 0.f) || !(c->rope_low_freq_factor > 0.f) ||
+                                 !(c->rope_high_freq_factor > c->rope_low_freq_factor) || c->rope_original_max_position < 1))
+        return fail(SUN_ERR_SHAPE, "rope scaling needs factor > 0, 0 < low_freq_factor < high_freq_factor, original length >= 1");
     return SUN_OK;
 }
 
 static bool same_shape(const sun_model_cfg& a, const sun_model_cfg& b) {
     return a.n_layers == b.n_layers && a.hidden == b.hidden && a.n_q_heads == b.n_q_heads &&
-           a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.ffn == b.ffn && a.vocab == b.vocab;
+           a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.ffn == b.ffn && a.vocab == b.vocab &&
+           a.qk_norm == b.qk_norm && a.rope_scaling == b.rope_scaling &&
+           (a.rope_scaling == 0 || (a.rope_original_max_position == b.rope_original_max_position &&
+                                    a.rope_factor == b.rope_factor && a.rope_low_freq_factor == b.rope_low_freq_factor &&
+                                    a.rope_high_freq_factor == b.rope_high_freq_factor));
 }
 
 static sun_kv_layout make_layout(const sun_model_cfg& c, int64_t n_pages) {
@@ -346,6 +355,10 @@ int sun_weights_create(const sun_model_cfg* cfg, const sun_weight_ptrs* d, void*
     if (!d || !d->embed || !d->gf || !d->wlm) return fail(SUN_ERR_NULL, "weight table or one of embed/gf/wlm is NULL");
     const void* const* const arrs[] = {d->g1, d->wq, d->wk, d->wv, d->wo, d->g2, d->wg, d->wu, d->wd};
     if (int rc = check_ptr_arrays(arrs, 9, cfg->n_layers)) return rc;
+    if (cfg->qk_norm) {
+        const void* const* const narrs[] = {d->q_norm, d->k_norm};
+        if (int rc = check_ptr_arrays(narrs, 2, cfg->n_layers)) return rc;
+    }
     const sun_model_cfg& c = *cfg;
     const bool bf = c.act_dtype == SUN_BF16;
     if (bf) {
@@ -385,6 +398,10 @@ int sun_weights_create(const sun_model_cfg* cfg, const sun_weight_ptrs* d, void*
         LayerW& L = w->layers[l];
         L.g1 = d->g1[l];
         L.g2 = d->g2[l];
+        if (c.qk_norm) {
+            L.qn = d->q_norm[l];
+            L.kn = d->k_norm[l];
+        }
         pack(L.qkv, 0, d->wq[l], d->wk[l], d->wv[l], QD, KD, KD, 3, 0);
         pack(L.o, 1, d->wo[l], nullptr, nullptr, c.hidden, 0, 0, 1, 0);
         pack(L.gu, 2, d->wg[l], d->wu[l], nullptr, c.ffn, c.ffn, 0, 2, bf ? 1 : 0);
@@ -409,6 +426,10 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
     if (!d || !d->embed || !d->gf || !d->wlm) return fail(SUN_ERR_NULL, "weight table or one of embed/gf/wlm is NULL");
     const void* const* const arrs[] = {d->g1, d->g2};
     if (int rc = check_ptr_arrays(arrs, 2, cfg->n_layers)) return rc;
+    if (cfg->qk_norm) {
+        const void* const* const narrs[] = {d->q_norm, d->k_norm};
+        if (int rc = check_ptr_arrays(narrs, 2, cfg->n_layers)) return rc;
+    }
     const sun_qmat* const qarrs[] = {d->wq, d->wk, d->wv, d->wo, d->wg, d->wu, d->wd};
     for (auto qa : qarrs) {
         if (!qa) return fail(SUN_ERR_NULL, "a per-layer quantised matrix array is NULL");
@@ -461,6 +482,10 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
         LayerW& L = w->layers[l];
         L.g1 = d->g1[l];
         L.g2 = d->g2[l];
+        if (c.qk_norm) {
+            L.qn = d->q_norm[l];
+            L.kn = d->k_norm[l];
+        }
         pack(L.qkv, 0, &d->wq[l], &d->wk[l], &d->wv[l], QD, KD, KD, 3, 0);
         pack(L.o, 1, &d->wo[l], nullptr, nullptr, c.hidden, 0, 0, 1, 0);
         pack(L.gu, 2, &d->wg[l], &d->wu[l], nullptr, c.ffn, c.ffn, 0, 2, bf ? 1 : 0);
@@ -614,7 +639,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             {
                 ProfScope p(prof, 7, st);
                 SUN_HIP_CHECK(launch_rope_append(pool, l, ws.part, sq, batch, ws.table, seq_lens, page_tables, max_pages,
-                                                 batch, ws.q, st));
+                                                 batch, ws.q, L.qn, L.kn, st));
             }
         } else {
             ProfScope p(prof, 7, st);
@@ -622,7 +647,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             else SUN_HIP_CHECK(launch_residual_norm(c, ws.x, nullptr, 0, batch, L.g1, batch, ws.h32, nullptr, nullptr, st));
             SUN_HIP_CHECK(launch_proj_f32(L.qkv, ws.h32, batch, ws.qkv32, st));
             SUN_HIP_CHECK(launch_rope_append(pool, l, ws.qkv32, 1, batch, ws.table, seq_lens, page_tables, max_pages,
-                                             batch, ws.q, st));
+                                             batch, ws.q, L.qn, L.kn, st));
         }
         {
             ProfScope p(prof, 0, st);

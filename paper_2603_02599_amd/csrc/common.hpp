@@ -124,6 +124,8 @@ struct Mat {
 struct LayerW {
     const void* g1;
     const void* g2;
+    const void* qn = nullptr;  // head-norm gains [head_dim], only with cfg.qk_norm
+    const void* kn = nullptr;
     Mat qkv, o, gu, down;
 };
 

@@ -154,13 +154,30 @@ hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float*
     return hipGetLastError();
 }
 
-// ---------------- rotary table: cos/sin of pos * base^(-2j/d), angle in double ----------------
+// ---------------- rotary table: cos/sin of pos * theta_j, angle in double ----------------
+// theta_j = base^(-2j/d); with the wavelength-dependent scaling rule of the LLaMA-3.1 class (scaling = 1) it
+// is kept, divided by `factor`, or blended between the two, depending on where 2*pi/theta_j lies relative to
+// orig/high_freq and orig/low_freq.
+struct RopeScale {
+    int scaling, orig_max;
+    double factor, low_freq, high_freq;
+};
+
 __global__ __launch_bounds__(64) void rope_table_kernel(const int32_t* __restrict__ seq_lens, int d, double base,
-                                                        float* __restrict__ table) {
+                                                        RopeScale rs, float* __restrict__ table) {
     const int b = blockIdx.x;
     const double pos = (double)seq_lens[b];
     for (int j = threadIdx.x; j < d / 2; j += 64) {
-        const double theta = pow(base, -2.0 * (double)j / (double)d);
+        double theta = pow(base, -2.0 * (double)j / (double)d);
+        if (rs.scaling == 1) {
+            const double wavelen = 2.0 * 3.14159265358979323846 / theta, orig = (double)rs.orig_max;
+            if (wavelen > orig / rs.low_freq) {
+                theta = theta / rs.factor;
+            } else if (wavelen >= orig / rs.high_freq) {
+                const double smooth = (orig / wavelen - rs.low_freq) / (rs.high_freq - rs.low_freq);
+                theta = (1.0 - smooth) * theta / rs.factor + smooth * theta;
+            }
+        }
         const double ang = pos * theta;
         table[((size_t)b * (d / 2) + j) * 2] = (float)cos(ang);
         table[((size_t)b * (d / 2) + j) * 2 + 1] = (float)sin(ang);
@@ -169,7 +186,9 @@ __global__ __launch_bounds__(64) void rope_table_kernel(const int32_t* __restric
 
 hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, int batch, float* table,
                              hipStream_t st) {
-    hipLaunchKernelGGL(rope_table_kernel, dim3(batch), dim3(64), 0, st, seq_lens, cfg.head_dim, (double)cfg.rope_base,
+    const RopeScale rs{cfg.rope_scaling, cfg.rope_original_max_position, (double)cfg.rope_factor,
+                       (double)cfg.rope_low_freq_factor, (double)cfg.rope_high_freq_factor};
+    hipLaunchKernelGGL(rope_table_kernel, dim3(batch), dim3(64), 0, st, seq_lens, cfg.head_dim, (double)cfg.rope_base, rs,
                        table);
     return hipGetLastError();
 }
@@ -185,6 +204,10 @@ struct RopeArgs {
     uint16_t* pool;
     int64_t k_base, k_page, k_head, k_token, k_dim, v_base, v_page, v_head, v_token, v_dim;
     int nparts, ld_rows, Hq, Hkv, D, max_pages, n_pages;
+    const void* qn;  // head-norm gains [D] for q and k heads, or NULL (no head norm)
+    const void* kn;
+    int gain_bf16;
+    float eps;
 };
 
 __global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
@@ -196,37 +219,53 @@ __global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
     const int slot = L % kPageTokens;
     const float* src = a.qkv + (size_t)b * Nqkv + (size_t)hh * D;
     const size_t pstride = (size_t)a.ld_rows * Nqkv;
-    for (int j = threadIdx.x; j < half; j += 64) {
-        float lo = 0.f, hi = 0.f;
+    // head_dim <= 128: lane j owns elements j and j + D/2; lanes past D/2 carry zeros through the norm
+    const int j = threadIdx.x;
+    const bool act = j < half;
+    float lo = 0.f, hi = 0.f;
+    if (act) {
         for (int s = 0; s < a.nparts; ++s) {
             lo += src[s * pstride + j];
             hi += src[s * pstride + j + half];
         }
-        if (hh < a.Hq + a.Hkv) {
-            const float c = a.table[((size_t)b * half + j) * 2], sn = a.table[((size_t)b * half + j) * 2 + 1];
-            const float rl = lo * c - hi * sn, rh = hi * c + lo * sn;
-            lo = rl;
-            hi = rh;
+    }
+    if (a.qn && hh < a.Hq + a.Hkv) {  // RMSNorm over the head's D elements (uniform branch: all lanes take part)
+        const float ss = wave_sum(lo * lo + hi * hi);
+        const float r = 1.0f / sqrtf(ss / (float)D + a.eps);
+        if (act) {
+            const void* g = hh < a.Hq ? a.qn : a.kn;
+            const float gl = a.gain_bf16 ? bf16_bits_to_f32(((const uint16_t*)g)[j]) : ((const float*)g)[j];
+            const float gh = a.gain_bf16 ? bf16_bits_to_f32(((const uint16_t*)g)[j + half]) : ((const float*)g)[j + half];
+            lo = lo * r * gl;
+            hi = hi * r * gh;
         }
-        if (hh < a.Hq) {
-            a.q_out[((size_t)b * a.Hq + hh) * D + j] = lo;
-            a.q_out[((size_t)b * a.Hq + hh) * D + j + half] = hi;
-        } else if (hh < a.Hq + a.Hkv) {
-            uint16_t* kd = a.pool + a.k_base + (int64_t)page * a.k_page + (int64_t)(hh - a.Hq) * a.k_head + slot * a.k_token;
-            kd[j * a.k_dim] = f32_to_bf16_bits(lo);
-            kd[(j + half) * a.k_dim] = f32_to_bf16_bits(hi);
-        } else {
-            uint16_t* vd = a.pool + a.v_base + (int64_t)page * a.v_page + (int64_t)(hh - a.Hq - a.Hkv) * a.v_head + slot * a.v_token;
-            vd[j * a.v_dim] = f32_to_bf16_bits(lo);
-            vd[(j + half) * a.v_dim] = f32_to_bf16_bits(hi);
-        }
+    }
+    if (!act) return;
+    if (hh < a.Hq + a.Hkv) {
+        const float c = a.table[((size_t)b * half + j) * 2], sn = a.table[((size_t)b * half + j) * 2 + 1];
+        const float rl = lo * c - hi * sn, rh = hi * c + lo * sn;
+        lo = rl;
+        hi = rh;
+    }
+    if (hh < a.Hq) {
+        a.q_out[((size_t)b * a.Hq + hh) * D + j] = lo;
+        a.q_out[((size_t)b * a.Hq + hh) * D + j + half] = hi;
+    } else if (hh < a.Hq + a.Hkv) {
+        uint16_t* kd = a.pool + a.k_base + (int64_t)page * a.k_page + (int64_t)(hh - a.Hq) * a.k_head + slot * a.k_token;
+        kd[j * a.k_dim] = f32_to_bf16_bits(lo);
+        kd[(j + half) * a.k_dim] = f32_to_bf16_bits(hi);
+    } else {
+        uint16_t* vd = a.pool + a.v_base + (int64_t)page * a.v_page + (int64_t)(hh - a.Hq - a.Hkv) * a.v_head + slot * a.v_token;
+        vd[j * a.v_dim] = f32_to_bf16_bits(lo);
+        vd[(j + half) * a.v_dim] = f32_to_bf16_bits(hi);
     }
 }
 
 hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, int nparts, int ld_rows,
                               const float* table, const int32_t* seq_lens, const int32_t* page_tables, int max_pages,
-                              int batch, float* q_out, hipStream_t st) {
+                              int batch, float* q_out, const void* q_norm, const void* k_norm, hipStream_t st) {
     const sun_model_cfg& c = pool.cfg;
+    if (c.head_dim > 128) return hipErrorInvalidValue;
     const sun_kv_layout& L = pool.lay;
     RopeArgs a{};
     a.qkv = qkv;
@@ -252,6 +291,11 @@ hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, i
     a.D = c.head_dim;
     a.max_pages = max_pages;
     a.n_pages = (int)L.n_pages;
+    a.qn = c.qk_norm ? q_norm : nullptr;
+    a.kn = c.qk_norm ? k_norm : nullptr;
+    a.gain_bf16 = c.act_dtype == SUN_BF16;
+    a.eps = c.rms_eps;
+    if (c.qk_norm && (!q_norm || !k_norm)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(rope_append_kernel, dim3(c.n_q_heads + 2 * c.n_kv_heads, batch), dim3(64), 0, st, a);
     return hipGetLastError();
 }

@@ -36,6 +36,8 @@ class Shape:
     vocab: int
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    qk_norm: bool = False              # Qwen3-class option: RMSNorm over head_dim on q and k heads
+    rope_scaling: Optional[tuple] = None  # LLaMA-3.1-class option: (factor, low_freq, high_freq, original_max_position)
 
     @property
     def q_dim(self) -> int:
@@ -58,6 +60,10 @@ class Shape:
 TINY = Shape("tiny", 2, 256, 4, 2, 64, 688, 1024)
 # Tiny shape whose FFN width is a multiple of the 128-wide quantisation group.
 TINY_Q = Shape("tiny_q", 2, 256, 4, 2, 64, 768, 1024)
+# The tiny and small shapes with the backbone options of the paper's model families switched on.
+TINY_QWEN = Shape("tiny_qwen", 2, 256, 4, 2, 64, 768, 1024, rms_eps=1e-6, rope_base=1000000.0, qk_norm=True)
+SMALL_LLAMA31 = Shape("small_llama31", 2, 512, 8, 2, 128, 1024, 2048, rope_base=500000.0,
+                      rope_scaling=(8.0, 1.0, 4.0, 256))
 # A second small shape with head_dim 128 and GQA ratio 4 (the 8B head geometry).
 SMALL128 = Shape("small128", 2, 512, 8, 2, 128, 1024, 2048)
 # Small shape with the 14B head geometry (GQA ratio 5, head_dim 128).
@@ -65,7 +71,7 @@ SMALL_G5 = Shape("small_g5", 2, 1280, 10, 2, 128, 1024, 2048)
 LLAMA_8B = Shape("llama8b", 32, 4096, 32, 8, 128, 14336, 128256)
 QWEN_14B = Shape("qwen14b", 48, 5120, 40, 8, 128, 13824, 152064)
 
-SHAPES = {s.name: s for s in (TINY, TINY_Q, SMALL128, SMALL_G5, LLAMA_8B, QWEN_14B)}
+SHAPES = {s.name: s for s in (TINY, TINY_Q, TINY_QWEN, SMALL128, SMALL_LLAMA31, SMALL_G5, LLAMA_8B, QWEN_14B)}
 
 
 def zipf_probs(n_models: int, s: float) -> np.ndarray:
@@ -201,6 +207,13 @@ def make_weights(shape: Shape, dtype: str, device: str, seed: int,
         w["wd"].append(mat(shape.hidden, shape.ffn))
     w["gf"] = torch.ones(shape.hidden, dtype=dt, device=device)
     w["wlm"] = mat(shape.vocab, shape.hidden)
+    if shape.qk_norm:  # head-norm gains: 1 + N(0, 0.1^2), so that a dropped or swapped gain shows
+        def head_gain():
+            g = torch.empty(shape.head_dim, dtype=torch.float32, device=device).normal_(1.0, 0.1, generator=g_)
+            return g.to(dt)
+        g_ = g
+        w["qn"] = [head_gain() for _ in range(nl)]
+        w["kn"] = [head_gain() for _ in range(nl)]
     return w
 
 

@@ -231,8 +231,10 @@ def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
 
 def check_appended_kv(gpu_after: np.ndarray, orc_after: np.ndarray, before: np.ndarray, mask: np.ndarray, dtype: str):
     """Eq. 4: only the predicted slots change.  fp32 path: values equal the oracle's bf16
-    rounding up to 1 bf16 ulp (an fp32 and an fp64 projection can round apart); bf16 path:
-    within the logits tolerance.  Returns (#elements off by one ulp, #elements written)."""
+    rounding up to 1 bf16 ulp (an fp32 and an fp64 projection can round apart), or, for an element
+    that cancels to nearly zero, where one bf16 ulp is smaller than the fp32 accumulation error of
+    the projection that produced it, up to 2e-6 absolute; bf16 path: within the logits tolerance.
+    Returns (#elements off by one ulp or more, #elements written)."""
     assert np.array_equal(gpu_after[~mask], before[~mask]), "GPU wrote outside the appended slots"
     assert np.array_equal(orc_after[~mask], before[~mask])
     a, b = gpu_after[mask].astype(np.int32), orc_after[mask].astype(np.int32)
@@ -241,10 +243,11 @@ def check_appended_kv(gpu_after: np.ndarray, orc_after: np.ndarray, before: np.n
         return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
 
     ulp = np.abs(ordered(a) - ordered(b))
+    ga, oa = bf16_to_f64(gpu_after[mask]), bf16_to_f64(orc_after[mask])
     if dtype == "f32":
-        assert ulp.max() <= 1, f"appended K/V differs by {ulp.max()} bf16 ulps"
+        bad = (ulp > 1) & (np.abs(ga - oa) > 2e-6)
+        assert not bad.any(), f"appended K/V differs by {ulp[bad].max()} bf16 ulps ({np.abs(ga - oa)[bad].max():.2e})"
     else:
-        ga, oa = bf16_to_f64(gpu_after[mask]), bf16_to_f64(orc_after[mask])
         worst = float((np.abs(ga - oa) - (2e-2 + 1e-2 * np.abs(oa))).max())
         assert worst <= 0, f"appended K/V exceeds the bf16 tolerance by {worst:.3e}"
     return int((ulp >= 1).sum()), int(mask.sum())

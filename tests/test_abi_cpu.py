@@ -30,10 +30,19 @@ def test_every_declared_symbol_is_exported(lib):
     assert b"gfx950" in lib.sun_version()
 
 
-def test_struct_sizes_match_the_header():
-    assert C.sizeof(sun.ModelCfg) == 40
-    assert C.sizeof(sun.KvLayout) == 8 + 8 + 12 * 8 + 8
-    assert C.sizeof(sun.QMat) == 24
+def test_struct_sizes_match_the_header(tmp_path):
+    """The ctypes mirrors against the header itself: a C program that includes sun.h prints the sizes."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "sun.h"\nint main(void) { printf("%zu %zu %zu %zu %zu\\n", '
+                   'sizeof(sun_model_cfg), sizeof(sun_kv_layout), sizeof(sun_qmat), sizeof(sun_weight_ptrs), '
+                   'sizeof(sun_qweight_ptrs)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c11", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    sizes = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert sizes == [C.sizeof(sun.ModelCfg), C.sizeof(sun.KvLayout), C.sizeof(sun.QMat), C.sizeof(sun.WeightPtrs),
+                     C.sizeof(sun.QWeightPtrs)]
+    assert C.sizeof(sun.ModelCfg) == 64 and C.sizeof(sun.KvLayout) == 8 + 8 + 12 * 8 + 8 and C.sizeof(sun.QMat) == 24
 
 
 FAKE = 0x7F0000000000  # aligned, never dereferenced: these calls fail (or only store it) before any GPU work

@@ -312,3 +312,53 @@ def test_validation_errors(H):
         case.step(flags=sun.SUN_VALIDATE, tokens=torch.full_like(case.tokens, -1))
     assert e.value.status == 9
     case.step(flags=sun.SUN_VALIDATE)   # and the good call still works afterwards
+
+
+# ------------------------------------------------------------------ backbone options of the paper's model families
+def test_fp32_head_norm_option(H):
+    """Qwen3-class block: RMSNorm over head_dim on q and k heads before the rotation (rms_eps 1e-6, base 1e6)."""
+    H.say("fp32 tiny with q/k head norm")
+    work = wl.make_workload("cfg1", shape=wl.TINY_QWEN, seed=95)
+    rep = _full_step_parity(H, H.GpuCase(work))
+    # the option is live: the same inputs through the plain block give different logits
+    import dataclasses
+    plain = dataclasses.replace(wl.TINY_QWEN, qk_norm=False)
+    work2 = wl.make_workload("cfg1", shape=plain, seed=95)
+    c1, c2 = H.GpuCase(work), H.GpuCase(work2)
+    c1.step()
+    c2.step()
+    assert (c1.logits - c2.logits).abs().max() > 1e-3
+
+
+@pytest.mark.parametrize("quant", [None, "asym"])
+def test_bf16_head_norm_option(H, quant):
+    import dataclasses
+    shape = dataclasses.replace(wl.SMALL128, name="small128_qknorm", qk_norm=True, rms_eps=1e-6)
+    H.say(f"bf16 small128 with q/k head norm, quant={quant}")
+    work = wl.make_workload("cfg2", shape=shape, batch=24, lo=20, hi=700, seed=96)
+    _full_step_parity(H, H.GpuCase(work, quant_mode=quant))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scaled_rotary_option(H, dtype):
+    """LLaMA-3.1-class rotary scaling (factor 8, low 1, high 4) with a short original length (256), so that at
+    these positions (up to 2000) kept, blended and slowed pairs all occur."""
+    H.say(f"{dtype} small with scaled rotary frequencies")
+    work = wl.make_workload("cfg2", shape=wl.SMALL_LLAMA31, dtype=dtype, batch=12, lo=300, hi=2000, seed=97)
+    rep = _full_step_parity(H, H.GpuCase(work))
+    import dataclasses
+    plain = dataclasses.replace(wl.SMALL_LLAMA31, rope_scaling=None)
+    c1 = H.GpuCase(work)
+    c2 = H.GpuCase(wl.make_workload("cfg2", shape=plain, dtype=dtype, batch=12, lo=300, hi=2000, seed=97))
+    c1.step()
+    c2.step()
+    assert (c1.logits - c2.logits).abs().max() > 1e-3
+
+
+def test_tied_embeddings(H):
+    """Small models of the Qwen3 family tie the LM head to the embedding: the same pointer serves as both."""
+    H.say("fp32 tiny, lm_head tied to the embedding")
+    work = wl.make_workload("cfg1", seed=98)
+    w = wl.make_weights(wl.TINY, "f32", "cuda", 99)
+    w["wlm"] = w["embed"]
+    _full_step_parity(H, H.GpuCase(work, weights=w))
