@@ -1,5 +1,6 @@
 """Test-side plumbing for GPU parity: builds one workload on the GPU, mirrors exactly the
-bytes the GPU consumes into the CPU oracle, and compares.  Imports the oracle (tests only)."""
+bytes the GPU consumes into the CPU oracle, and compares.  The oracle is imported on first use only, so that
+bench.py can share the case-building code without touching it outside its cpu_baseline leg."""
 from __future__ import annotations
 
 import sys
@@ -8,9 +9,21 @@ from typing import Dict, Optional, Sequence
 import numpy as np
 import torch
 
-from oracle import oracle as orc
 from paper_2603_02599_amd import binding as sun
 from paper_2603_02599_amd import workloads as wl
+
+
+def _orc():
+    """The CPU oracle, imported on first use: building GPU cases (which bench.py also does) does not touch it."""
+    from oracle import oracle as o
+    return o
+
+
+def __getattr__(name):  # H.orc for the tests
+    if name == "orc":
+        return _orc()
+    raise AttributeError(name)
+
 
 DEV = "cuda:0"
 
@@ -72,7 +85,7 @@ class SharedWeights:
                     if k not in wnp:
                         wnp[k] = [np.empty((0, 2 * trip[0].shape[1]), np.float32) for trip in v]
             self._keep = (wnp, qnp)
-            self._params = orc.params_from_arrays(wnp, qnp)
+            self._params = _orc().params_from_arrays(wnp, qnp)
         return self._params
 
 
@@ -132,7 +145,7 @@ class GpuCase:
         if self.quant is not None:
             qnp = {k: [tuple(to_np(t) for t in trip) for trip in v] for k, v in self.quant.items()}
         self._keep = (wnp, qnp)
-        return orc.params_from_arrays(wnp, qnp)
+        return _orc().params_from_arrays(wnp, qnp)
 
     def extract_pool(self, rows: Sequence[int]):
         """Copies only the pages the given requests reference into a compact host pool with
@@ -150,7 +163,7 @@ class GpuCase:
         host = to_np(small).reshape(-1).copy()
         st = layout_strides(lay)
         st["k_layer"] = st["v_layer"] = len(used) * page_elems
-        pool = orc.make_pool(host, len(used), 16, st)
+        pool = _orc().make_pool(host, len(used), 16, st)
         return host, pool, new_tabs, used
 
     def pool_pages_now(self, used: np.ndarray) -> np.ndarray:
@@ -167,11 +180,11 @@ def run_oracle(case: GpuCase, rows: Sequence[int], params=None, tokens=None, len
     rows = list(rows)
     host, pool, tabs, used = case.extract_pool(rows)
     params = params if params is not None else case.oracle_params()
-    ocfg = orc.make_cfg(work.shape)
+    ocfg = _orc().make_cfg(work.shape)
     toks = (work.tokens if tokens is None else tokens)[rows]
     ln = (work.seq_lens if lens is None else lens)[rows]
     mi = (work.model_ids if ids is None else ids)[rows]
-    res = orc.decode_step(ocfg, params, pool, toks, tabs, ln, mi, **kw)
+    res = _orc().decode_step(ocfg, params, pool, toks, tabs, ln, mi, **kw)
     res["pool_after"] = host
     res["used_pages"] = used
     return res
