@@ -177,6 +177,9 @@ def main():
     ap.add_argument("--ingest-tokens", type=int, default=0,
                     help="instead of decoding: time sun_kv_pool_ingest of one prompt cache of this many tokens "
                          "(shape of --workload), K times; prints its own JSON line (tokens/s and GB/s read+written)")
+    ap.add_argument("--prefill-tokens", type=int, default=0,
+                    help="instead of decoding: time sun_prefill of one prompt of this many tokens (shape of "
+                         "--workload, bf16), K times; prints its own JSON line (prompt tokens/s)")
     ap.add_argument("--mode", default="step", choices=["step", "run"],
                     help="step: K independent calls of the decode step on the same inputs (default). "
                          "run: one sun_decode_run call of K steps with token feedback, growing caches and page "
@@ -234,6 +237,37 @@ def main():
                           "roofline": {"bound": "hbm", "kernel": "kv_ingest_kernel", "achieved": moved / (ms * 1e-3) / 1e9,
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                        "traffic": None, "bytes_per_launch": moved}}))
+        return
+    if args.prefill_tokens > 0:
+        from paper_2603_02599_amd import workloads as wl
+        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
+        n = args.prefill_tokens
+        pages = n // 16 + 1
+        cfg = sun.make_cfg(shape, "bf16")
+        mem = torch.empty(sun.sun_kv_pool_bytes(cfg, pages) // 2, dtype=torch.bfloat16, device="cuda")
+        pool = sun.sun_kv_pool_create(cfg, mem, 16, 1)
+        w = wl.make_weights(shape, "bf16", "cuda", 11)
+        weights = sun.sun_weights_create(cfg, w)
+        toks = torch.randint(0, shape.vocab, (n,), device="cuda", dtype=torch.int32)
+        row = torch.randperm(pages, device="cuda").to(torch.int32)
+        ws = torch.empty(sun.sun_prefill_workspace_bytes(cfg, n, pages), dtype=torch.uint8, device="cuda")
+        logits = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+        nxt = torch.empty(1, dtype=torch.int32, device="cuda")
+        for _ in range(args.warmup):
+            sun.sun_prefill(pool, weights, toks, row, 0, 0, logits, nxt, ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            sun.sun_prefill(pool, weights, toks, row, 0, 0, logits, nxt, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"metric": "prefill prompt tokens/sec", "value": n / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                          "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"one prompt of {n} tokens, {shape.name} shape, shuffled pages, "
+                                                 "through the decode step's kernels in blocks of 256 rows"}}))
         return
     work, desc = build_workload(args.workload)
     shape = work.shape

@@ -309,6 +309,42 @@ int sun_decode_run(sun_kv_pool* pool, const sun_weights* weights, int batch, int
                    int32_t* free_head, int32_t* run_status, int32_t* tokens_out, float* logits_out,
                    void* workspace, size_t workspace_bytes, void* stream, unsigned flags);
 
+/* ------------------------------------------------------------------ prefill */
+
+/* Bytes of device workspace a prefill of n_tokens positions with max_pages page-table columns needs. */
+size_t sun_prefill_workspace_bytes(const sun_model_cfg* cfg, int n_tokens, int max_pages);
+
+/*
+ * The prefill module of Eq. 2 for one request, enqueued on `stream`: the causal forward of
+ * `weights` (the task-specific theta_p of Section 3.2.1, or the base model) over n_tokens prompt
+ * tokens at positions first_pos .. first_pos + n_tokens - 1.  It writes the K/V of those positions
+ * into the request's pages in every layer (the prompt part C_X of Eq. 4) and returns the
+ * distribution of the first generated token.  Positions 0 .. first_pos - 1 must already be cached
+ * (first_pos > 0 continues a prompt that was prefilled in pieces); the result does not depend on
+ * how a prompt is cut into pieces.
+ *
+ * It runs through the decode step's own kernels: the prompt is taken in blocks of up to 256
+ * positions, row r of a block being the decode step of position first + r over the shared page
+ * table, so it is exact but not tuned for long prompts (attention reads the cache once per row).
+ *
+ *   token_ids   dev int32 [n_tokens]
+ *   page_table  dev int32 [max_pages]   the request's row; entries 0 .. (first_pos+n_tokens-1)/16
+ *                                       must be valid pages that no other request writes
+ *   model_id    source-model tag; n_tokens is added to that model's count in the pool
+ *   logits_out  dev fp32 [vocab] or NULL: logits after the last prompt token
+ *   next_token_out dev int32 [1] or NULL: their greedy argmax
+ *   workspace   dev, 256-byte aligned, >= sun_prefill_workspace_bytes(cfg, n_tokens, max_pages)
+ * `weights` must come from sun_weights_create (the prefill side stays in full precision, also
+ * when decode is quantised: Section 3.3) and have the pool's shape.
+ * Errors: SUN_ERR_NULL, SUN_ERR_SHAPE (also for 4-bit weights), SUN_ERR_MODEL_ID, SUN_ERR_SEQ_LEN (n_tokens < 1,
+ * first_pos < 0, positions beyond the table), SUN_ERR_WORKSPACE; under SUN_VALIDATE also
+ * SUN_ERR_PAGE_RANGE and SUN_ERR_TOKEN.
+ */
+int sun_prefill(sun_kv_pool* pool, const sun_weights* weights, int n_tokens, const int32_t* token_ids,
+                const int32_t* page_table, int max_pages, int first_pos, int model_id,
+                float* logits_out, int32_t* next_token_out, void* workspace, size_t workspace_bytes,
+                void* stream, unsigned flags);
+
 /* ------------------------------------------------------------------ single operations */
 
 /*

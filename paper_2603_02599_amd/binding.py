@@ -26,6 +26,7 @@ EXPORTS = [
     "sun_weights_pack_bytes", "sun_weights_create", "sun_weights_destroy",
     "sun_qweights_pack_bytes", "sun_qweights_create", "sun_quantize_w4",
     "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step", "sun_decode_run",
+    "sun_prefill_workspace_bytes", "sun_prefill",
     "sun_paged_attention", "sun_linear",
     "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
 ]
@@ -84,7 +85,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.sun_last_error.restype = C.c_char_p
         L.sun_version.restype = C.c_char_p
-        for f in ("sun_kv_pool_bytes", "sun_weights_pack_bytes", "sun_qweights_pack_bytes", "sun_workspace_bytes"):
+        for f in ("sun_kv_pool_bytes", "sun_weights_pack_bytes", "sun_qweights_pack_bytes", "sun_workspace_bytes",
+                  "sun_prefill_workspace_bytes"):
             getattr(L, f).restype = C.c_size_t
         L.sun_kv_pool_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int64, C.c_int]
         L.sun_kv_pool_create.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_size_t, C.c_int, C.c_int,
@@ -113,6 +115,9 @@ def lib() -> C.CDLL:
         L.sun_decode_run.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
+        L.sun_prefill_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
+        L.sun_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
         L.sun_paged_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sun_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -343,6 +348,22 @@ def sun_decode_run(pool, weights, n_steps: int, token_ids, page_tables, seq_lens
                                 _p(page_tables), max_pages, _p(seq_lens), _p(model_ids), _p(free_pages), n_free,
                                 _p(free_head), _p(run_status), _p(tokens_out), _p(logits_out), _p(workspace), ws_bytes,
                                 _stream(stream), flags))
+
+
+def sun_prefill_workspace_bytes(cfg: ModelCfg, n_tokens: int, max_pages: int) -> int:
+    return int(lib().sun_prefill_workspace_bytes(C.byref(cfg), n_tokens, max_pages))
+
+
+def sun_prefill(pool, weights, token_ids, page_table_row, first_pos: int, model_id: int, logits_out, next_token_out,
+                workspace, stream=None, flags: int = 0):
+    """Causal forward of `weights` over the prompt tokens (int32 [n_tokens]) of one request; fills its pages."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    n_tokens = int(token_ids.numel()) if token_ids is not None else 0
+    max_pages = int(page_table_row.numel()) if page_table_row is not None else 0
+    _check(lib().sun_prefill(pool.handle if pool is not None else None,
+                             weights.handle if weights is not None else None, n_tokens, _p(token_ids),
+                             _p(page_table_row), max_pages, first_pos, model_id, _p(logits_out), _p(next_token_out),
+                             _p(workspace), ws_bytes, _stream(stream), flags))
 
 
 def sun_paged_attention(pool, layer: int, q, page_tables, n_tokens, out, workspace, n_tokens_host=None, stream=None):

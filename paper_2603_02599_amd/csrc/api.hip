@@ -587,7 +587,8 @@ static int total_chunks_from_host(const int32_t* host, int len_plus, int batch) 
 static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_quant, int batch,
                      const int32_t* token_ids, const int32_t* page_tables, int max_pages, const int32_t* seq_lens,
                      const int32_t* seq_lens_host, const int32_t* model_ids, float* logits_out,
-                     int32_t* next_tokens_out, void* workspace, size_t workspace_bytes, void* stream, unsigned flags) {
+                     int32_t* next_tokens_out, void* workspace, size_t workspace_bytes, void* stream, unsigned flags,
+                     bool with_head = true) {
     if (!pool_ || !weights_) return fail(SUN_ERR_NULL, "pool or weights is NULL");
     if (!token_ids || !page_tables || !seq_lens || !model_ids || !next_tokens_out || !workspace)
         return fail(SUN_ERR_NULL, "a required device pointer is NULL");
@@ -697,6 +698,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             SUN_HIP_CHECK(launch_proj_f32(L.down, ws.u32, batch, ws.o32, st));
         }
     }
+    if (!with_head) return SUN_OK;  // a caller that only wants the cache entries (all but the last prefill block)
     {
         ProfScope p(prof, 7, st);
         if (bf) SUN_HIP_CHECK(launch_residual_norm(c, ws.x, ws.part, down_parts, batch, W.gf, batch, nullptr, ws.hA, nullptr, st));
@@ -751,7 +753,7 @@ int sun_decode_run(sun_kv_pool* pool_, const sun_weights* weights_, int batch, i
         hipStream_t st = (hipStream_t)stream;
         std::vector<int32_t> fp((size_t)n_free), tabs((size_t)batch * max_pages);
         int32_t head = 0;
-        SUN_HIP_CHECK(hipMemcpyAsync(fp.data(), free_pages, fp.size() * 4, hipMemcpyDeviceToHost, st));
+        if (n_free) SUN_HIP_CHECK(hipMemcpyAsync(fp.data(), free_pages, fp.size() * 4, hipMemcpyDeviceToHost, st));
         SUN_HIP_CHECK(hipMemcpyAsync(tabs.data(), page_tables, tabs.size() * 4, hipMemcpyDeviceToHost, st));
         SUN_HIP_CHECK(hipMemcpyAsync(&head, free_head, 4, hipMemcpyDeviceToHost, st));
         SUN_HIP_CHECK(hipStreamSynchronize(st));
@@ -776,6 +778,98 @@ int sun_decode_run(sun_kv_pool* pool_, const sun_weights* weights_, int batch, i
         SUN_HIP_CHECK(launch_advance(tokens_out + (size_t)s * batch, batch, max_pages, free_pages, n_free, token_ids,
                                      page_tables, seq_lens, free_head, run_status, s == 0, (hipStream_t)stream));
     }
+    return SUN_OK;
+}
+
+// ---------------------------------------------------------------- prefill
+// Extra device memory of a prefill behind the step's workspace: per-row page tables, lengths,
+// model ids and next tokens of one block of rows.
+struct PrefillExtra {
+    int32_t *tables, *lens, *ids, *next;
+    size_t bytes;
+};
+
+static PrefillExtra carve_prefill(int rows, int max_pages, char* base) {
+    PrefillExtra e{};
+    size_t off = 0;
+    auto take = [&](size_t n) {
+        char* p = base ? base + off : nullptr;
+        off += align_up(n);
+        return (int32_t*)p;
+    };
+    e.tables = take((size_t)rows * max_pages * 4);
+    e.lens = take((size_t)rows * 4);
+    e.ids = take((size_t)rows * 4);
+    e.next = take((size_t)rows * 4);
+    e.bytes = off;
+    return e;
+}
+
+size_t sun_prefill_workspace_bytes(const sun_model_cfg* cfg, int n_tokens, int max_pages) {
+    if (!cfg || n_tokens < 1 || max_pages < 1 || check_cfg(cfg) != SUN_OK) return 0;
+    const int rows = std::min(n_tokens, kMaxBatchTile);
+    return carve(*cfg, rows, max_pages, nullptr).bytes + carve_prefill(rows, max_pages, nullptr).bytes;
+}
+
+int sun_prefill(sun_kv_pool* pool_, const sun_weights* weights_, int n_tokens, const int32_t* token_ids,
+                const int32_t* page_table, int max_pages, int first_pos, int model_id, float* logits_out,
+                int32_t* next_token_out, void* workspace, size_t workspace_bytes, void* stream, unsigned flags) {
+    if (!pool_ || !weights_) return fail(SUN_ERR_NULL, "pool or weights is NULL");
+    if (!token_ids || !page_table || !workspace) return fail(SUN_ERR_NULL, "a required device pointer is NULL");
+    KvPool& pool = *(KvPool*)pool_;
+    const Weights& W = *(const Weights*)weights_;
+    const sun_model_cfg& c = W.cfg;
+    if (!same_shape(c, pool.cfg)) return fail(SUN_ERR_SHAPE, "pool and weights were created for different shapes");
+    if (W.quant) return fail(SUN_ERR_SHAPE, "prefill runs in full precision: weights must come from sun_weights_create");
+    if (model_id < 0 || model_id >= pool.n_source_models)
+        return fail(SUN_ERR_MODEL_ID, "source-model id %d outside [0, %d)", model_id, pool.n_source_models);
+    if (n_tokens < 1 || first_pos < 0 || max_pages < 1) return fail(SUN_ERR_SEQ_LEN, "n_tokens must be >= 1, first_pos >= 0");
+    const long long last = (long long)first_pos + n_tokens - 1;
+    if (last / kPageTokens >= max_pages)
+        return fail(SUN_ERR_SEQ_LEN, "positions up to %lld need %lld page-table entries, the row has %d", last,
+                    last / kPageTokens + 1, max_pages);
+    if ((uintptr_t)workspace % 256) return fail(SUN_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    const int rows_max = std::min(n_tokens, kMaxBatchTile);
+    const size_t step_bytes = carve(c, rows_max, max_pages, nullptr).bytes;
+    const PrefillExtra ex = carve_prefill(rows_max, max_pages, (char*)workspace + step_bytes);
+    if (step_bytes + ex.bytes > workspace_bytes)
+        return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, prefill needs %zu", workspace_bytes, step_bytes + ex.bytes);
+    hipStream_t st = (hipStream_t)stream;
+    if (flags & SUN_VALIDATE) {
+        std::vector<int32_t> row((size_t)max_pages), tok((size_t)n_tokens);
+        SUN_HIP_CHECK(hipMemcpyAsync(row.data(), page_table, row.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(tok.data(), token_ids, tok.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipStreamSynchronize(st));
+        for (long long lp = 0; lp <= last / kPageTokens; ++lp)
+            if (row[lp] < 0 || row[lp] >= pool.lay.n_pages)
+                return fail(SUN_ERR_PAGE_RANGE, "page-table entry %lld = %d outside [0, %lld)", lp, row[lp],
+                            (long long)pool.lay.n_pages);
+        for (int i = 0; i < n_tokens; ++i)
+            if (tok[i] < 0 || tok[i] >= c.vocab)
+                return fail(SUN_ERR_TOKEN, "prompt token %d: id %d outside [0, %d)", i, tok[i], c.vocab);
+    }
+    // Row r of a block is the decode step of position first + r over the one page table: its
+    // attention spans positions 0..first + r, and the K/V of all rows of the block are in the
+    // pool before the block's attention starts, which is the causal forward of Eq. 2.
+    const unsigned step_flags = flags & ~SUN_VALIDATE;
+    for (int done = 0; done < n_tokens; done += kMaxBatchTile) {
+        const int rows = std::min(n_tokens - done, kMaxBatchTile);
+        const bool last_block = done + rows == n_tokens;
+        SUN_HIP_CHECK(launch_prefill_rows(page_table, max_pages, first_pos + done, model_id, rows, ex.tables, ex.lens, ex.ids, st));
+        const int rc = step_impl(pool_, weights_, false, rows, token_ids + done, ex.tables, max_pages, ex.lens, nullptr,
+                                 ex.ids, nullptr, ex.next, workspace, step_bytes, stream, step_flags,
+                                 last_block && (logits_out || next_token_out));
+        if (rc != SUN_OK) return rc;
+        if (last_block) {
+            const Workspace ws = carve(c, rows, max_pages, (char*)workspace);
+            if (logits_out)
+                SUN_HIP_CHECK(hipMemcpyAsync(logits_out, ws.logits + (size_t)(rows - 1) * c.vocab, (size_t)c.vocab * 4,
+                                             hipMemcpyDeviceToDevice, st));
+            if (next_token_out)
+                SUN_HIP_CHECK(hipMemcpyAsync(next_token_out, ex.next + rows - 1, 4, hipMemcpyDeviceToDevice, st));
+        }
+    }
+    pool.ingested[model_id] += n_tokens;
     return SUN_OK;
 }
 

@@ -77,6 +77,10 @@ hipError_t launch_kv_ingest(const KvPool& pool, const void* k_src, const void* v
 hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const int32_t* free_pages, int n_free,
                           int32_t* token_ids, int32_t* page_tables, int32_t* seq_lens, int32_t* free_head,
                           int32_t* status, bool clear_status, hipStream_t st);
+// Per-row inputs of one block of a prefill: row r gets a copy of the request's page-table row, length
+// first_pos + r and the source-model id.
+hipError_t launch_prefill_rows(const int32_t* page_table, int max_pages, int first_pos, int model_id, int rows,
+                               int32_t* tables, int32_t* lens, int32_t* ids, hipStream_t st);
 hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, int batch, float* table,
                              hipStream_t st);
 // qkv partial sums [nparts][ld_rows][Nqkv] -> rotated q fp32 [batch, Hq*d]; K,V (bf16) appended to the pool.

@@ -514,6 +514,25 @@ hipError_t launch_kv_ingest(const KvPool& pool, const void* k_src, const void* v
     return hipGetLastError();
 }
 
+// ---------------- per-row inputs of a prefill block ----------------
+__global__ __launch_bounds__(256) void prefill_rows_kernel(const int32_t* __restrict__ page_table, int max_pages,
+                                                           int first_pos, int model_id, int32_t* __restrict__ tables,
+                                                           int32_t* __restrict__ lens, int32_t* __restrict__ ids) {
+    const int r = blockIdx.x;
+    for (int c = threadIdx.x; c < max_pages; c += 256) tables[(size_t)r * max_pages + c] = page_table[c];
+    if (threadIdx.x == 0) {
+        lens[r] = first_pos + r;
+        ids[r] = model_id;
+    }
+}
+
+hipError_t launch_prefill_rows(const int32_t* page_table, int max_pages, int first_pos, int model_id, int rows,
+                               int32_t* tables, int32_t* lens, int32_t* ids, hipStream_t st) {
+    hipLaunchKernelGGL(prefill_rows_kernel, dim3(rows), dim3(256), 0, st, page_table, max_pages, first_pos, model_id,
+                       tables, lens, ids);
+    return hipGetLastError();
+}
+
 // ---------------- bookkeeping between the steps of a run ----------------
 // One workgroup.  Request b feeds its generated token back and grows by one position.  If that
 // position opens a page its table does not have yet, it takes the next unused entry of the free

@@ -149,9 +149,20 @@ def test_step_rejects_bad_arguments_before_enqueueing(lib):
     assert run(out=None) == 1 and run(free=None) == 1
     assert run(steps=0) == 2 and run(batch=0) == 2 and run(n_free=-1) == 1
     assert run(wsb=need - 1) == 4 and run(tok=None) == 1
+    pneed = lib.sun_prefill_workspace_bytes(C.byref(cfg), 40, 9)
+    assert pneed > lib.sun_workspace_bytes(C.byref(cfg), 40, 9) and lib.sun_prefill_workspace_bytes(C.byref(cfg), 0, 9) == 0
+
+    def prefill(pool=pool, w=w, n=40, tok=FAKE, pt=FAKE, mp=9, first=0, mid=0, ws=FAKE, wsb=pneed):
+        return lib.sun_prefill(pool, w, n, tok, pt, mp, first, mid, None, None, ws, wsb, None, 0)
+
+    assert prefill(pool=None) == 1 and prefill(w=None) == 1 and prefill(tok=None) == 1 and prefill(pt=None) == 1
+    assert prefill(ws=None) == 1 and prefill(mid=-1) == 7 and prefill(mid=3) == 7
+    assert prefill(n=0) == 6 and prefill(first=-1) == 6 and prefill(first=9 * 16 - 39) == 6   # last position needs a 10th page
+    assert prefill(wsb=pneed - 1) == 4 and prefill(ws=FAKE + 8) == 4
     other = sun.make_cfg(wl.TINY_Q, "f32")
     rc, pool2 = _pool(lib, other)
     assert rc == 0 and step(pool=pool2) == 2           # pool and weights of different shapes
+    assert prefill(pool=pool2) == 2
     lib.sun_kv_pool_destroy(pool2)
     lib.sun_weights_destroy(w)
     lib.sun_kv_pool_destroy(pool)
