@@ -273,6 +273,126 @@ def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_le
             "status": status}
 
 
+def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, n_steps: int, waiting, ring_pages,
+              idle_page: int, eos_id: int = -1, page_tokens: int = 16, mode: int = 0, forced_tokens=None,
+              state=None, keep_logits: bool = False):
+    """A decode worker that admits and retires requests between steps (the continuous batching of
+    Section 2.1.1): `slots` batch rows, each idle or occupied by one request, the decode step of Eq. 3
+    over the occupied rows every iteration, and between iterations, in this order and in row order
+    within each:
+      1. an occupied row records its token and has one token less to generate; it is finished when none
+         is left or the token is eos_id;
+      2. finished rows retire: their pages go to the tail of the list of free pages (column order) and
+         the row becomes idle;
+      3. the others feed their token back and grow by one position, taking the page at the head of the
+         free list when the next position opens a page their table lacks;
+      4. idle rows take waiting requests first in, first out, while the head of the queue fits: the
+         pages it may still need, (len + budget - 1) // page_tokens + 1 minus those its table holds,
+         must be free beyond what the rows already admitted may still need.  A budget running past the
+         table is cut to fit (status bit 1).
+    Idle rows are not decoded here: a request's tokens depend on nothing but its own cache and input.
+
+    waiting: list of dicts {req, token, table (int32 [max_pages]), len, model, budget}, already prefilled.
+    forced_tokens [n_steps, slots], if given, is taken as the token of every occupied row instead of the
+    row's own argmax (recorded, tested against eos_id and fed back), so that a replay follows another
+    implementation through a near-tie; the row's own logits are kept for the comparison.  state: the dict a
+    previous call returned (continues it) or None (all rows idle, then admission, before the first step).
+    Returns the state dict: rows, ring (list, head first), counters, plus tokens/reqs [n_steps, slots]
+    (-1 for idle rows) and the logits of every step under keep_logits (rows of idle slots are NaN)."""
+    if state is None:
+        st = {"req": [-1] * slots, "left": [0] * slots, "token": [0] * slots, "len": [0] * slots,
+              "model": [0] * slots, "tables": np.full((slots, max_pages), -1, np.int32),
+              "ring": [int(p) for p in ring_pages], "whead": 0, "status": 0, "retired": 0, "admitted": 0,
+              "generated": 0, "steps": 0}
+        st["tables"][:, 0] = idle_page
+    else:
+        st = {k: (v.copy() if isinstance(v, np.ndarray) else (list(v) if isinstance(v, list) else v))
+              for k, v in state.items() if k not in ("tokens", "reqs", "logits")}
+
+    def held(row):
+        return int((np.asarray(row) >= 0).sum())
+
+    def admit():
+        outstanding = sum(max(0, (st["len"][i] + st["left"][i] - 1) // page_tokens + 1 - held(st["tables"][i]))
+                          for i in range(slots) if st["req"][i] >= 0)
+        avail = len(st["ring"]) - outstanding
+        for i in range(slots):
+            if st["req"][i] >= 0:
+                continue
+            if st["whead"] >= len(waiting):
+                break
+            w = waiting[st["whead"]]
+            budget = int(w["budget"])
+            room = max_pages * page_tokens - int(w["len"])
+            cut = budget > room
+            budget = max(1, min(budget, room))
+            need = max(0, (int(w["len"]) + budget - 1) // page_tokens + 1 - held(w["table"]))
+            if need > avail:
+                break                      # the head of the queue blocks those behind it
+            avail -= need
+            if cut:
+                st["status"] |= 2
+            st["req"][i], st["left"][i], st["token"][i] = int(w["req"]), budget, int(w["token"])
+            st["len"][i], st["model"][i] = int(w["len"]), int(w["model"])
+            st["tables"][i] = np.asarray(w["table"], np.int32)
+            st["whead"] += 1
+            st["admitted"] += 1
+
+    if state is None:
+        admit()
+    toks_out = np.full((n_steps, slots), -1, np.int32)
+    reqs_out = np.full((n_steps, slots), -1, np.int32)
+    every = []
+    for s in range(n_steps):
+        rows = [i for i in range(slots) if st["req"][i] >= 0]
+        lg_all = np.full((slots, cfg.vocab), np.nan)
+        nxt = {}
+        if rows:
+            res = decode_step(cfg, params, pool, np.array([st["token"][i] for i in rows], np.int32),
+                              st["tables"][rows], np.array([st["len"][i] for i in rows], np.int32),
+                              np.array([st["model"][i] for i in rows], np.int32), mode=mode)
+            for j, i in enumerate(rows):
+                nxt[i] = int(res["next"][j])
+                lg_all[i] = res["logits"][j]
+        if keep_logits:
+            every.append(lg_all)
+        finished = []
+        for i in rows:                                   # 1
+            tok = nxt[i] if forced_tokens is None else int(forced_tokens[s][i])
+            toks_out[s, i], reqs_out[s, i] = tok, st["req"][i]
+            st["left"][i] -= 1
+            st["generated"] += 1
+            st["token"][i] = tok
+            if st["left"][i] == 0 or tok == eos_id:
+                finished.append(i)
+        for i in finished:                               # 2
+            st["ring"].extend(int(p) for p in st["tables"][i] if p >= 0)
+            st["tables"][i] = -1
+            st["tables"][i, 0] = idle_page
+            st["req"][i], st["left"][i], st["token"][i], st["len"][i], st["model"][i] = -1, 0, 0, 0, 0
+            st["retired"] += 1
+        for i in rows:                                   # 3
+            if i in finished:
+                continue
+            new_len = st["len"][i] + 1
+            col = new_len // page_tokens
+            if col >= max_pages:
+                st["status"] |= 2
+                continue
+            if new_len % page_tokens == 0 and st["tables"][i, col] < 0:
+                if not st["ring"]:
+                    st["status"] |= 1
+                    continue
+                st["tables"][i, col] = st["ring"].pop(0)
+            st["len"][i] = new_len
+        admit()                                          # 4
+        st["steps"] += 1
+    st["tokens"], st["reqs"] = toks_out, reqs_out
+    if keep_logits:
+        st["logits"] = np.stack(every) if every else None
+    return st
+
+
 def decode_contig_f64(cfg: Cfg, params: Params, token: int, L: int, Kc: np.ndarray, Vc: np.ndarray,
                       round_kv: bool = False):
     """Kc, Vc: float64 [NL, cap, Hkv, d]; writes position L.  Returns (logits, next)."""
