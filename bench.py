@@ -164,6 +164,73 @@ def bench_run(args, sun, case, work, shape, desc, free_list):
     print(json.dumps(out))
 
 
+def bench_serve(args, sun, H):
+    """K iterations of continuous batching in one library call: the rows of the --workload batch are kept
+    busy from a queue of prefilled requests that retire at their output budget and are replaced on the
+    device; tokens/s counts generated tokens only (idle rows count for nothing)."""
+    import torch
+    base, desc = build_workload(args.workload)
+    shape, slots = base.shape, base.batch
+    rng = np.random.default_rng(2025)
+    n_wait = 3 * slots
+    total_steps = args.warmup + args.steps
+    lens = rng.choice(base.seq_lens, size=n_wait).astype(np.int32)            # the workload's own length mix
+    budgets = rng.integers(max(2, total_steps // 4), max(3, total_steps) + 1, size=n_wait).astype(np.int32)
+    cols = int(lens.max() + budgets.max()) // 16 + 1
+    have = lens // 16 + 1
+    ring_n = slots * (int(budgets.max()) // 16 + 2)
+    n_pages = 1 + int(have.sum()) + ring_n
+    perm = rng.permutation(n_pages).astype(np.int32)
+    tables = np.full((n_wait, cols), -1, np.int32)
+    o = 1
+    for r in range(n_wait):
+        tables[r, :have[r]] = perm[o:o + have[r]]
+        o += int(have[r])
+    work = base
+    work.page_tables, work.n_pages = np.full((slots, cols), -1, np.int32), n_pages
+    t_setup = time.perf_counter()
+    case = H.GpuCase(work, quant_mode=args.quant)
+    if args.quant:
+        for k in sun.QUANT_KEYS:
+            case.w[k] = None
+    waiting = {"req": np.arange(n_wait, dtype=np.int32), "token": rng.integers(0, shape.vocab, size=n_wait).astype(np.int32),
+               "tables": tables, "lens": lens, "model": rng.integers(0, work.n_models, size=n_wait).astype(np.int32),
+               "budget": budgets}
+    state = sun.ServeTensors(slots, cols, waiting, perm[o:].tolist(), n_pages, int(perm[0]))
+    ws = torch.empty(sun.sun_serve_workspace_bytes(case.cfg, slots, cols), dtype=torch.uint8, device="cuda")
+    n_out = max(args.steps, args.warmup, 1)
+    toks = torch.empty((n_out, slots), dtype=torch.int32, device="cuda")
+    reqs = torch.empty((n_out, slots), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    print(f"[bench] setup {time.perf_counter() - t_setup:.1f} s; pool {n_pages} pages, {n_wait} requests waiting",
+          file=sys.stderr, flush=True)
+    sun.sun_decode_serve(case.pool, case.weights, max(args.warmup, 1), state, toks, reqs, None, ws,
+                         flags=sun.SUN_VALIDATE | sun.SUN_SERVE_RESET)
+    torch.cuda.synchronize()
+    c0 = state.counters.cpu().tolist()
+    t0 = time.perf_counter()
+    sun.sun_decode_serve(case.pool, case.weights, args.steps, state, toks, reqs, None, ws)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    c1 = state.counters.cpu().tolist()
+    assert c1[3] == 0, f"status {c1[3]}"
+    gen = c1[6] - c0[6]
+    ms_per_step = wall * 1e3 / args.steps
+    print(json.dumps({
+        "metric": "shared-decode tokens/sec", "value": gen / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": max(args.warmup, 1), "ms_per_step": ms_per_step, "tpot_ms": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if not args.quant else "bf16 activations, 4-bit group-128 weights", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}; continuous batching: one sun_decode_serve call of {args.steps} "
+                               f"iterations over {slots} rows fed from {n_wait} prefilled requests (lengths drawn from the "
+                               f"workload's, output budgets U[{int(budgets.min())},{int(budgets.max())}]), retirement, page "
+                               "return and admission on the device",
+                   "shape": shape.name, "rows": slots, "quant": args.quant, "mode": "serve",
+                   "tokens_generated": gen, "row_occupancy": gen / (args.steps * slots),
+                   "admitted": c1[5] - c0[5], "retired": c1[4] - c0[4], "still_waiting": n_wait - c1[0]},
+        "roofline": None, "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -180,10 +247,12 @@ def main():
     ap.add_argument("--prefill-tokens", type=int, default=0,
                     help="instead of decoding: time sun_prefill of one prompt of this many tokens (shape of "
                          "--workload, bf16), K times; prints its own JSON line (prompt tokens/s)")
-    ap.add_argument("--mode", default="step", choices=["step", "run"],
+    ap.add_argument("--mode", default="step", choices=["step", "run", "serve"],
                     help="step: K independent calls of the decode step on the same inputs (default). "
                          "run: one sun_decode_run call of K steps with token feedback, growing caches and page "
-                         "allocation on the device (TPOT over an output length of K)")
+                         "allocation on the device (TPOT over an output length of K). "
+                         "serve: one sun_decode_serve call of K iterations: rows retire at their output budget and "
+                         "take waiting requests, on the device (continuous batching)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (known size) to calibrate FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -269,6 +338,8 @@ def main():
                           "config": {"workload": f"one prompt of {n} tokens, {shape.name} shape, shuffled pages, "
                                                  "through the decode step's kernels in blocks of 256 rows"}}))
         return
+    if args.mode == "serve":
+        return bench_serve(args, sun, H)
     work, desc = build_workload(args.workload)
     shape = work.shape
     if args.mode == "run":

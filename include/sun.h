@@ -54,7 +54,9 @@ enum { SUN_F32 = 0, SUN_BF16 = 1 };
 enum {
     SUN_VALIDATE = 1u, /* copy token ids, lengths, page tables and model ids to the host
                           (synchronises the stream) and check them before enqueueing */
-    SUN_PROFILE = 2u   /* record HIP events around each kernel class; see sun_profile_read */
+    SUN_PROFILE = 2u,  /* record HIP events around each kernel class; see sun_profile_read */
+    SUN_SERVE_RESET = 4u /* sun_decode_serve only: before the first iteration make every row idle
+                            and admit from the queue */
 };
 
 /*
@@ -308,6 +310,91 @@ int sun_decode_run(sun_kv_pool* pool, const sun_weights* weights, int batch, int
                    const int32_t* model_ids, const int32_t* free_pages, int n_free,
                    int32_t* free_head, int32_t* run_status, int32_t* tokens_out, float* logits_out,
                    void* workspace, size_t workspace_bytes, void* stream, unsigned flags);
+
+/* ------------------------------------------------------------------ continuous batching */
+
+/*
+ * State of a decode worker that admits and retires requests between steps (the continuous
+ * batching of Section 2.1.1) entirely on the device.  All pointers are device memory owned by
+ * the caller; the struct itself is read on the host.  `slots` batch rows are decoded every
+ * step; a row is either occupied by a request or idle.
+ *
+ * Rows (in/out, kept between calls):
+ *   token_ids, seq_lens, model_ids  int32 [slots]; page_tables int32 [slots, max_pages]
+ *   slot_req   int32 [slots]  id of the request in the row, -1 = idle
+ *   slot_left  int32 [slots]  tokens the request may still generate (>= 1 while occupied)
+ * Waiting requests (read only), already prefilled: their caches are in the pool under the
+ * pages their table row lists.  Served first in, first out, starting at counters[0]:
+ *   w_req, w_token, w_lens, w_model, w_budget int32 [n_wait]; w_tables int32 [n_wait, max_pages]
+ *   (w_token: the first input token; w_lens: positions cached; w_budget >= 1: tokens to generate)
+ * Pages: `ring` int32 [ring_cap] is a circular list of pages no table references; entries
+ *   counters[1] .. counters[2]-1 (indices modulo ring_cap) are valid.  ring_cap must be at
+ *   least the number of pages that can ever be free at once (the pool's page count is enough).
+ *   `idle_page` is one page set aside for idle rows: it is in no table and not in the ring.
+ * counters int32 [8] (in/out): 0 first unserved waiting request, 1 ring head (take),
+ *   2 ring tail (put), 3 status bits, 4 requests retired, 5 requests admitted,
+ *   6 tokens generated, 7 steps run.  Heads and tails only grow.
+ * eos_id: a request also ends when it generates this token (-1: never).
+ *
+ * One iteration = one decode step over all rows (idle rows decode token 0 at position 0 of
+ * idle_page; what they produce is dropped), then, in this order and in row order within each:
+ *  1. every occupied row records its token and has one token less left; it is finished if
+ *     none is left or the token is eos_id;
+ *  2. finished rows retire: the pages of their table, in column order, go to the ring's
+ *     tail, and the row becomes idle;
+ *  3. the other occupied rows feed their token back and grow by one position; a row whose
+ *     next position opens a page its table lacks takes the page at the ring's head;
+ *  4. idle rows take waiting requests, first in first out, as long as the head of the queue
+ *     fits: a request is admitted only if the pages it may still need,
+ *     floor((len + budget - 1) / 16) + 1 minus the pages its table row holds, are available
+ *     in the ring beyond what the rows already admitted may still need.  So an admitted
+ *     request never waits for a page, and a request that does not fit blocks those behind it
+ *     until pages come back.  A budget that would run past the table (max_pages * 16
+ *     positions) is cut to fit and status bit 1 is set.
+ * Status bit 0: step 3 found the ring empty (possible only if rows were placed by hand without
+ * enough pages; the row then keeps its length, as in sun_decode_run).
+ */
+typedef struct sun_serve_state {
+    int32_t* token_ids;
+    int32_t* page_tables;
+    int32_t* seq_lens;
+    int32_t* model_ids;
+    int32_t* slot_req;
+    int32_t* slot_left;
+    const int32_t* w_req;
+    const int32_t* w_token;
+    const int32_t* w_tables;
+    const int32_t* w_lens;
+    const int32_t* w_model;
+    const int32_t* w_budget;
+    int32_t* ring;
+    int32_t* counters;
+    int32_t n_wait;
+    int32_t ring_cap;
+    int32_t idle_page;
+    int32_t eos_id;
+} sun_serve_state;
+
+/* Bytes of device workspace sun_decode_serve needs for `slots` rows. */
+size_t sun_serve_workspace_bytes(const sun_model_cfg* cfg, int slots, int max_pages);
+
+/*
+ * n_steps iterations of the loop above, enqueued on `stream` with no host synchronisation in
+ * between.  `weights` may come from sun_weights_create or sun_qweights_create.
+ *   tokens_out dev int32 [n_steps, slots]: the token each row generated, -1 for an idle row
+ *   req_out    dev int32 [n_steps, slots]: the request that generated it, -1 for an idle row
+ *   logits_out dev fp32 [slots, vocab] or NULL: logits of the last step
+ * With SUN_SERVE_RESET the rows' arrays need not be initialised (counters must be: zero for a
+ * fresh start, with counters[2] = number of pages in the ring).  Without it the call continues
+ * from the state a previous call left; two calls of n and m steps equal one of n + m.
+ * Errors: SUN_ERR_NULL, SUN_ERR_SHAPE (slots outside [1, 256], n_steps < 1, n_wait < 0,
+ * ring_cap < 1, shapes), SUN_ERR_WORKSPACE; under SUN_VALIDATE also SUN_ERR_PAGE_RANGE
+ * (idle_page, ring entries or waiting tables outside the pool, a page listed twice),
+ * SUN_ERR_SEQ_LEN, SUN_ERR_TOKEN, SUN_ERR_MODEL_ID for waiting requests not yet served.
+ */
+int sun_decode_serve(sun_kv_pool* pool, const sun_weights* weights, int slots, int max_pages, int n_steps,
+                     const sun_serve_state* state, int32_t* tokens_out, int32_t* req_out, float* logits_out,
+                     void* workspace, size_t workspace_bytes, void* stream, unsigned flags);
 
 /* ------------------------------------------------------------------ prefill */
 

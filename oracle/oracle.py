@@ -298,7 +298,7 @@ def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, 
     implementation through a near-tie; the row's own logits are kept for the comparison.  state: the dict a
     previous call returned (continues it) or None (all rows idle, then admission, before the first step).
     Returns the state dict: rows, ring (list, head first), counters, plus tokens/reqs [n_steps, slots]
-    (-1 for idle rows) and the logits of every step under keep_logits (rows of idle slots are NaN)."""
+    (-1 for idle rows), writes (the (page, slot) every decoded row appended to, Eq. 4) and the logits of every step under keep_logits (rows of idle slots are NaN)."""
     if state is None:
         st = {"req": [-1] * slots, "left": [0] * slots, "token": [0] * slots, "len": [0] * slots,
               "model": [0] * slots, "tables": np.full((slots, max_pages), -1, np.int32),
@@ -307,7 +307,7 @@ def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, 
         st["tables"][:, 0] = idle_page
     else:
         st = {k: (v.copy() if isinstance(v, np.ndarray) else (list(v) if isinstance(v, list) else v))
-              for k, v in state.items() if k not in ("tokens", "reqs", "logits")}
+              for k, v in state.items() if k not in ("tokens", "reqs", "logits", "writes")}
 
     def held(row):
         return int((np.asarray(row) >= 0).sum())
@@ -342,9 +342,10 @@ def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, 
         admit()
     toks_out = np.full((n_steps, slots), -1, np.int32)
     reqs_out = np.full((n_steps, slots), -1, np.int32)
-    every = []
+    every, writes = [], []
     for s in range(n_steps):
         rows = [i for i in range(slots) if st["req"][i] >= 0]
+        writes += [(int(st["tables"][i, st["len"][i] // page_tokens]), st["len"][i] % page_tokens) for i in rows]
         lg_all = np.full((slots, cfg.vocab), np.nan)
         nxt = {}
         if rows:
@@ -387,7 +388,7 @@ def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, 
             st["len"][i] = new_len
         admit()                                          # 4
         st["steps"] += 1
-    st["tokens"], st["reqs"] = toks_out, reqs_out
+    st["tokens"], st["reqs"], st["writes"] = toks_out, reqs_out, writes
     if keep_logits:
         st["logits"] = np.stack(every) if every else None
     return st

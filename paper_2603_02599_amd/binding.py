@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SUN_LIB_PATH", os.path.join(_HERE, "libsun.so"))  # override: another build of libsun
 
 SUN_F32, SUN_BF16 = 0, 1
-SUN_VALIDATE, SUN_PROFILE = 1, 2
+SUN_VALIDATE, SUN_PROFILE, SUN_SERVE_RESET = 1, 2, 4
 STATUS = {0: "SUN_OK", 1: "SUN_ERR_NULL", 2: "SUN_ERR_SHAPE", 3: "SUN_ERR_POOL_SIZE", 4: "SUN_ERR_WORKSPACE",
           5: "SUN_ERR_PAGE_RANGE", 6: "SUN_ERR_SEQ_LEN", 7: "SUN_ERR_MODEL_ID", 8: "SUN_ERR_HIP", 9: "SUN_ERR_TOKEN"}
 PROFILE_KINDS = ("attn_split", "attn_combine", "qkv_proj", "o_proj", "gate_up_proj", "down_proj", "lm_head", "other")
@@ -26,10 +26,17 @@ EXPORTS = [
     "sun_weights_pack_bytes", "sun_weights_create", "sun_weights_destroy",
     "sun_qweights_pack_bytes", "sun_qweights_create", "sun_quantize_w4",
     "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step", "sun_decode_run",
-    "sun_prefill_workspace_bytes", "sun_prefill",
+    "sun_prefill_workspace_bytes", "sun_prefill", "sun_serve_workspace_bytes", "sun_decode_serve",
     "sun_paged_attention", "sun_linear",
     "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
 ]
+
+
+class ServeState(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("token_ids", "page_tables", "seq_lens", "model_ids", "slot_req", "slot_left",
+                                          "w_req", "w_token", "w_tables", "w_lens", "w_model", "w_budget", "ring",
+                                          "counters")] + \
+               [(n, C.c_int32) for n in ("n_wait", "ring_cap", "idle_page", "eos_id")]
 
 
 class SunError(RuntimeError):
@@ -86,7 +93,7 @@ def lib() -> C.CDLL:
         L.sun_last_error.restype = C.c_char_p
         L.sun_version.restype = C.c_char_p
         for f in ("sun_kv_pool_bytes", "sun_weights_pack_bytes", "sun_qweights_pack_bytes", "sun_workspace_bytes",
-                  "sun_prefill_workspace_bytes"):
+                  "sun_prefill_workspace_bytes", "sun_serve_workspace_bytes"):
             getattr(L, f).restype = C.c_size_t
         L.sun_kv_pool_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int64, C.c_int]
         L.sun_kv_pool_create.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_size_t, C.c_int, C.c_int,
@@ -115,6 +122,9 @@ def lib() -> C.CDLL:
         L.sun_decode_run.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
+        L.sun_serve_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
+        L.sun_decode_serve.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(ServeState),
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
         L.sun_prefill_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
         L.sun_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
@@ -348,6 +358,56 @@ def sun_decode_run(pool, weights, n_steps: int, token_ids, page_tables, seq_lens
                                 _p(page_tables), max_pages, _p(seq_lens), _p(model_ids), _p(free_pages), n_free,
                                 _p(free_head), _p(run_status), _p(tokens_out), _p(logits_out), _p(workspace), ws_bytes,
                                 _stream(stream), flags))
+
+
+def sun_serve_workspace_bytes(cfg: ModelCfg, slots: int, max_pages: int) -> int:
+    return int(lib().sun_serve_workspace_bytes(C.byref(cfg), slots, max_pages))
+
+
+class ServeTensors:
+    """Device tensors of a continuous-batching decode worker (the fields of sun_serve_state), kept alive
+    together with the struct handed to the library."""
+
+    def __init__(self, slots: int, max_pages: int, waiting, ring_pages, ring_cap: int, idle_page: int,
+                 eos_id: int = -1, device="cuda"):
+        import torch
+        i32 = dict(dtype=torch.int32, device=device)
+        self.slots, self.max_pages = slots, max_pages
+        self.token_ids = torch.zeros(slots, **i32)
+        self.page_tables = torch.full((slots, max_pages), -1, **i32)
+        self.seq_lens = torch.zeros(slots, **i32)
+        self.model_ids = torch.zeros(slots, **i32)
+        self.slot_req = torch.full((slots,), -1, **i32)
+        self.slot_left = torch.zeros(slots, **i32)
+        n = len(waiting["req"])
+        self.n_wait = n
+        self.w = {k: torch.as_tensor(waiting[k], dtype=torch.int32).to(device).contiguous()
+                  for k in ("req", "token", "tables", "lens", "model", "budget")}
+        assert self.w["tables"].shape == (n, max_pages) or n == 0
+        ring = torch.zeros(ring_cap, **i32)
+        ring[:len(ring_pages)] = torch.as_tensor(ring_pages, dtype=torch.int32)
+        self.ring, self.ring_cap = ring, ring_cap
+        self.counters = torch.zeros(8, **i32)
+        self.counters[2] = len(ring_pages)
+        self.idle_page, self.eos_id = idle_page, eos_id
+
+    def struct(self) -> "ServeState":
+        s = ServeState()
+        for name in ("token_ids", "page_tables", "seq_lens", "model_ids", "slot_req", "slot_left", "ring", "counters"):
+            setattr(s, name, _p(getattr(self, name)))
+        for k in ("req", "token", "tables", "lens", "model", "budget"):
+            setattr(s, "w_" + k, _p(self.w[k]) if self.n_wait else None)
+        s.n_wait, s.ring_cap, s.idle_page, s.eos_id = self.n_wait, self.ring_cap, self.idle_page, self.eos_id
+        return s
+
+
+def sun_decode_serve(pool, weights, n_steps: int, state: ServeTensors, tokens_out, req_out, logits_out, workspace,
+                     stream=None, flags: int = 0):
+    """n_steps iterations of decode + retire/advance/admit on the device; `state` is updated in place."""
+    st = state.struct()
+    _check(lib().sun_decode_serve(pool.handle, weights.handle, state.slots, state.max_pages, n_steps, C.byref(st),
+                                  _p(tokens_out), _p(req_out), _p(logits_out), _p(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream), flags))
 
 
 def sun_prefill_workspace_bytes(cfg: ModelCfg, n_tokens: int, max_pages: int) -> int:

@@ -781,6 +781,116 @@ int sun_decode_run(sun_kv_pool* pool_, const sun_weights* weights_, int batch, i
     return SUN_OK;
 }
 
+// ---------------------------------------------------------------- continuous batching
+static int validate_serve(const KvPool& pool, const sun_serve_state& s, int slots, int max_pages, bool reset,
+                          hipStream_t st) {
+    const int64_t n_pages = pool.lay.n_pages;
+    if (s.idle_page < 0 || s.idle_page >= n_pages)
+        return fail(SUN_ERR_PAGE_RANGE, "idle_page %d outside [0, %lld)", s.idle_page, (long long)n_pages);
+    int32_t cnt[8];
+    SUN_HIP_CHECK(hipMemcpyAsync(cnt, s.counters, sizeof cnt, hipMemcpyDeviceToHost, st));
+    SUN_HIP_CHECK(hipStreamSynchronize(st));
+    const int whead = cnt[0], head = cnt[1], tail = cnt[2];
+    if (whead < 0 || whead > s.n_wait) return fail(SUN_ERR_SHAPE, "counters[0] = %d outside [0, n_wait]", whead);
+    if (head < 0 || tail < head || tail - head > s.ring_cap)
+        return fail(SUN_ERR_PAGE_RANGE, "ring head %d / tail %d do not fit a ring of %d", head, tail, s.ring_cap);
+    const int n_ring = tail - head, n_q = s.n_wait - whead;
+    std::vector<int32_t> ring((size_t)s.ring_cap), wt((size_t)n_q * max_pages), wl(n_q), wtok(n_q), wm(n_q), wb(n_q);
+    SUN_HIP_CHECK(hipMemcpyAsync(ring.data(), s.ring, ring.size() * 4, hipMemcpyDeviceToHost, st));
+    if (n_q) {
+        SUN_HIP_CHECK(hipMemcpyAsync(wt.data(), s.w_tables + (size_t)whead * max_pages, wt.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(wl.data(), s.w_lens + whead, n_q * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(wtok.data(), s.w_token + whead, n_q * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(wm.data(), s.w_model + whead, n_q * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(wb.data(), s.w_budget + whead, n_q * 4, hipMemcpyDeviceToHost, st));
+    }
+    std::vector<int32_t> rows, rreq;
+    if (!reset) {
+        rows.resize((size_t)slots * max_pages);
+        rreq.resize(slots);
+        SUN_HIP_CHECK(hipMemcpyAsync(rows.data(), s.page_tables, rows.size() * 4, hipMemcpyDeviceToHost, st));
+        SUN_HIP_CHECK(hipMemcpyAsync(rreq.data(), s.slot_req, slots * 4, hipMemcpyDeviceToHost, st));
+    }
+    SUN_HIP_CHECK(hipStreamSynchronize(st));
+    std::vector<char> used((size_t)n_pages, 0);
+    used[s.idle_page] = 1;
+    auto claim = [&](int32_t pg, const char* what, int idx) -> int {
+        if (pg < 0 || pg >= n_pages) return fail(SUN_ERR_PAGE_RANGE, "%s %d: page %d outside the pool", what, idx, pg);
+        if (used[pg]) return fail(SUN_ERR_PAGE_RANGE, "%s %d: page %d is listed twice (or is the idle page)", what, idx, pg);
+        used[pg] = 1;
+        return SUN_OK;
+    };
+    for (int i = 0; i < n_ring; ++i)
+        if (int rc = claim(ring[(size_t)((unsigned)(head + i) % (unsigned)s.ring_cap)], "ring entry", i)) return rc;
+    for (int q = 0; q < n_q; ++q) {
+        if (wtok[q] < 0 || wtok[q] >= pool.cfg.vocab) return fail(SUN_ERR_TOKEN, "waiting request %d: token %d", whead + q, wtok[q]);
+        if (wm[q] < 0 || wm[q] >= pool.n_source_models) return fail(SUN_ERR_MODEL_ID, "waiting request %d: model id %d", whead + q, wm[q]);
+        if (wl[q] < 0 || wl[q] / kPageTokens >= max_pages || wb[q] < 1)
+            return fail(SUN_ERR_SEQ_LEN, "waiting request %d: length %d / budget %d do not fit", whead + q, wl[q], wb[q]);
+        for (int c = 0; c < max_pages; ++c) {
+            const int32_t pg = wt[(size_t)q * max_pages + c];
+            if (pg < 0) {
+                if (c <= wl[q] / kPageTokens)
+                    return fail(SUN_ERR_PAGE_RANGE, "waiting request %d: no page for position %d", whead + q, c * kPageTokens);
+                continue;
+            }
+            if (int rc = claim(pg, "waiting request", whead + q)) return rc;
+        }
+    }
+    for (int i = 0; i < (reset ? 0 : slots); ++i) {
+        if (rreq[i] < 0) continue;
+        for (int c = 0; c < max_pages; ++c)
+            if (rows[(size_t)i * max_pages + c] >= 0)
+                if (int rc = claim(rows[(size_t)i * max_pages + c], "row", i)) return rc;
+    }
+    return SUN_OK;
+}
+
+size_t sun_serve_workspace_bytes(const sun_model_cfg* cfg, int slots, int max_pages) {
+    const size_t step = sun_workspace_bytes(cfg, slots, max_pages);
+    return step ? step + align_up((size_t)slots * 4) : 0;
+}
+
+int sun_decode_serve(sun_kv_pool* pool_, const sun_weights* weights_, int slots, int max_pages, int n_steps,
+                     const sun_serve_state* state, int32_t* tokens_out, int32_t* req_out, float* logits_out,
+                     void* workspace, size_t workspace_bytes, void* stream, unsigned flags) {
+    if (!pool_ || !weights_ || !state) return fail(SUN_ERR_NULL, "pool, weights or state is NULL");
+    const sun_serve_state& s = *state;
+    if (!s.token_ids || !s.page_tables || !s.seq_lens || !s.model_ids || !s.slot_req || !s.slot_left || !s.ring ||
+        !s.counters || !tokens_out || !req_out || !workspace)
+        return fail(SUN_ERR_NULL, "a required device pointer is NULL");
+    if (s.n_wait < 0 || (s.n_wait > 0 && (!s.w_req || !s.w_token || !s.w_tables || !s.w_lens || !s.w_model || !s.w_budget)))
+        return fail(s.n_wait < 0 ? SUN_ERR_SHAPE : SUN_ERR_NULL, "waiting queue: n_wait < 0 or a NULL array");
+    if (slots < 1 || slots > kMaxBatchTile || max_pages < 1 || n_steps < 1 || s.ring_cap < 1)
+        return fail(SUN_ERR_SHAPE, "slots must be in [1, %d], max_pages, n_steps and ring_cap >= 1", kMaxBatchTile);
+    KvPool& pool = *(KvPool*)pool_;
+    const Weights& W = *(const Weights*)weights_;
+    if (!same_shape(W.cfg, pool.cfg)) return fail(SUN_ERR_SHAPE, "pool and weights were created for different shapes");
+    if ((uintptr_t)workspace % 256) return fail(SUN_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    const size_t step_bytes = carve(W.cfg, slots, max_pages, nullptr).bytes;
+    const size_t next_bytes = align_up((size_t)slots * 4);
+    if (step_bytes + next_bytes > workspace_bytes)
+        return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, serving needs %zu", workspace_bytes, step_bytes + next_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const bool reset = flags & SUN_SERVE_RESET;
+    if (flags & SUN_VALIDATE)
+        if (int rc = validate_serve(pool, s, slots, max_pages, reset, st)) return rc;
+    int32_t* next = (int32_t*)((char*)workspace + step_bytes);
+    ServeArgs a{s.token_ids, s.page_tables, s.seq_lens, s.model_ids, s.slot_req, s.slot_left, s.w_req, s.w_token,
+                s.w_tables, s.w_lens, s.w_model, s.w_budget, s.ring, s.counters, s.n_wait, s.ring_cap, s.idle_page,
+                s.eos_id, slots, max_pages};
+    if (reset) SUN_HIP_CHECK(launch_serve(a, nullptr, nullptr, nullptr, true, false, st));
+    const unsigned step_flags = flags & SUN_PROFILE;
+    for (int i = 0; i < n_steps; ++i) {
+        const bool last = i + 1 == n_steps;
+        const int rc = step_impl(pool_, weights_, W.quant, slots, s.token_ids, s.page_tables, max_pages, s.seq_lens, nullptr,
+                                 s.model_ids, last ? logits_out : nullptr, next, workspace, step_bytes, stream, step_flags);
+        if (rc != SUN_OK) return rc;
+        SUN_HIP_CHECK(launch_serve(a, next, tokens_out + (size_t)i * slots, req_out + (size_t)i * slots, false, true, st));
+    }
+    return SUN_OK;
+}
+
 // ---------------------------------------------------------------- prefill
 // Extra device memory of a prefill behind the step's workspace: per-row page tables, lengths,
 // model ids and next tokens of one block of rows.

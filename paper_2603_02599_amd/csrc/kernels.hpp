@@ -81,6 +81,16 @@ hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const i
 // first_pos + r and the source-model id.
 hipError_t launch_prefill_rows(const int32_t* page_table, int max_pages, int first_pos, int model_id, int rows,
                                int32_t* tables, int32_t* lens, int32_t* ids, hipStream_t st);
+// Rows, waiting queue and page ring of a decode worker with continuous batching (sun_serve_state plus sizes).
+struct ServeArgs {
+    int32_t *token_ids, *page_tables, *seq_lens, *model_ids, *slot_req, *slot_left;
+    const int32_t *w_req, *w_token, *w_tables, *w_lens, *w_model, *w_budget;
+    int32_t *ring, *counters;
+    int n_wait, ring_cap, idle_page, eos_id, slots, max_pages;
+};
+// Between two steps (advance) and/or before the first (reset): record tokens, retire, grow, admit.
+hipError_t launch_serve(const ServeArgs& a, const int32_t* next, int32_t* tokens_out, int32_t* req_out, bool reset,
+                        bool advance, hipStream_t st);
 hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, int batch, float* table,
                              hipStream_t st);
 // qkv partial sums [nparts][ld_rows][Nqkv] -> rotated q fp32 [batch, Hq*d]; K,V (bf16) appended to the pool.

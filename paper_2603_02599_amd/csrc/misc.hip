@@ -590,6 +590,161 @@ hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const i
     return hipGetLastError();
 }
 
+// ---------------- continuous batching: retire, advance, admit between two steps ----------------
+// One workgroup of 256 threads, thread t owns row t.  All orders are row order (exclusive scans), so the
+// result does not depend on scheduling.  The phases follow the declaration of sun_decode_serve.
+__device__ __forceinline__ int block_scan_excl(int v, int* sc, int& total) {
+    const int t = threadIdx.x;
+    __syncthreads();  // sc may still be read from the previous scan
+    sc[t] = v;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        const int u = t >= o ? sc[t - o] : 0;
+        __syncthreads();
+        sc[t] += u;
+        __syncthreads();
+    }
+    total = sc[255];
+    return sc[t] - v;
+}
+
+__device__ __forceinline__ int pages_held(const int32_t* row, int max_pages) {
+    int n = 0;
+    for (int c = 0; c < max_pages; ++c) n += row[c] >= 0;
+    return n;
+}
+
+__global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* __restrict__ next,
+                                                    int32_t* __restrict__ tokens_out, int32_t* __restrict__ req_out,
+                                                    int do_reset, int do_advance) {
+    __shared__ int sc[256];
+    const int t = threadIdx.x;
+    const bool row = t < a.slots;
+    int whead = a.counters[0], head = a.counters[1], tail = a.counters[2];
+    int32_t* tab = a.page_tables + (size_t)(row ? t : 0) * a.max_pages;
+    int req = -1, left = 0, len = 0, status = 0, retired = 0, generated = 0;
+    if (row && !do_reset) {
+        req = a.slot_req[t];
+        left = a.slot_left[t];
+        len = a.seq_lens[t];
+    }
+    bool occ = req >= 0;
+    bool clear = row && do_reset;  // rows to be written as idle
+    if (do_advance) {
+        const int tok = row ? next[t] : 0;
+        if (row) {
+            tokens_out[t] = occ ? tok : -1;
+            req_out[t] = req;
+        }
+        bool fin = false;
+        if (occ) {
+            left -= 1;
+            generated = 1;
+            fin = left == 0 || tok == a.eos_id;
+        }
+        // retire: pages to the ring's tail, rows in order, columns in order
+        int give_total;
+        const int give = (occ && fin) ? pages_held(tab, a.max_pages) : 0;
+        const int off = block_scan_excl(give, sc, give_total);
+        if (occ && fin) {
+            int j = 0;
+            for (int c = 0; c < a.max_pages; ++c)
+                if (tab[c] >= 0) a.ring[(unsigned)(tail + off + j++) % (unsigned)a.ring_cap] = tab[c];
+            retired = 1;
+            clear = true;
+        }
+        tail += give_total;
+        __syncthreads();  // the ring entries written above may be taken below
+        // advance the others
+        const bool cont = occ && !fin;
+        const int new_len = len + 1, col = new_len / kPageTokens;
+        const int wants = cont && col < a.max_pages && new_len % kPageTokens == 0 && tab[col] < 0;
+        int want_total;
+        const int rank = block_scan_excl(wants, sc, want_total);
+        if (cont) {
+            if (col >= a.max_pages) {
+                status |= 2;
+            } else if (wants && head + rank >= tail) {
+                status |= 1;
+            } else {
+                if (wants) tab[col] = a.ring[(unsigned)(head + rank) % (unsigned)a.ring_cap];
+                len = new_len;
+            }
+            a.token_ids[t] = tok;
+            a.slot_left[t] = left;
+            a.seq_lens[t] = len;
+        }
+        head = min(head + want_total, tail);
+        if (fin) occ = false;
+    }
+    if (do_reset) occ = false;
+    if (clear) {
+        for (int c = 0; c < a.max_pages; ++c) tab[c] = c == 0 ? a.idle_page : -1;
+        a.token_ids[t] = 0;
+        a.seq_lens[t] = 0;
+        a.model_ids[t] = 0;
+        a.slot_req[t] = -1;
+        a.slot_left[t] = 0;
+    }
+    // admission
+    int out_total, idle_total, need_total, ok_total;
+    const int outst = occ ? max(0, (len + left - 1) / kPageTokens + 1 - pages_held(tab, a.max_pages)) : 0;
+    block_scan_excl(outst, sc, out_total);
+    const int avail = (tail - head) - out_total;
+    const bool idle = row && !occ;
+    const int idle_rank = block_scan_excl(idle ? 1 : 0, sc, idle_total);
+    const int ncand = max(0, min(idle_total, a.n_wait - whead));
+    auto cut_budget = [&](int q, bool& cut) {
+        const int room = a.max_pages * kPageTokens - a.w_lens[q];
+        const int b = a.w_budget[q];
+        cut = b > room;
+        return max(1, min(b, room));
+    };
+    int need = 0;
+    if (t < ncand) {
+        const int q = whead + t;
+        bool cut;
+        const int b = cut_budget(q, cut);
+        need = max(0, (a.w_lens[q] + b - 1) / kPageTokens + 1 - pages_held(a.w_tables + (size_t)q * a.max_pages, a.max_pages));
+    }
+    const int before = block_scan_excl(need, sc, need_total);
+    // candidate t is admitted if it and all before it fit (needs are >= 0, so the admitted ones are a prefix)
+    const int ok = t < ncand && before + need <= avail;
+    block_scan_excl(ok, sc, ok_total);
+    if (idle && idle_rank < ok_total) {
+        const int q = whead + idle_rank;
+        bool cut;
+        const int b = cut_budget(q, cut);
+        if (cut) status |= 2;
+        for (int c = 0; c < a.max_pages; ++c) tab[c] = a.w_tables[(size_t)q * a.max_pages + c];
+        a.token_ids[t] = a.w_token[q];
+        a.seq_lens[t] = a.w_lens[q];
+        a.model_ids[t] = a.w_model[q];
+        a.slot_req[t] = a.w_req[q];
+        a.slot_left[t] = b;
+    }
+    int ret_total, gen_total;
+    block_scan_excl(retired, sc, ret_total);
+    block_scan_excl(generated, sc, gen_total);
+    if (status) atomicOr(&a.counters[3], status);
+    if (t == 0) {
+        a.counters[0] = whead + ok_total;
+        a.counters[1] = head;
+        a.counters[2] = tail;
+        a.counters[4] += ret_total;
+        a.counters[5] += ok_total;
+        a.counters[6] += gen_total;
+        a.counters[7] += do_advance;
+    }
+}
+
+hipError_t launch_serve(const ServeArgs& a, const int32_t* next, int32_t* tokens_out, int32_t* req_out, bool reset,
+                        bool advance, hipStream_t st) {
+    if (a.slots < 1 || a.slots > 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(serve_kernel, dim3(1), dim3(256), 0, st, a, next, tokens_out, req_out, reset ? 1 : 0, advance ? 1 : 0);
+    return hipGetLastError();
+}
+
 // ---------------- layout helpers ----------------
 __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict__ x, int rows, int K, int mb,
                                                         u32x4* __restrict__ tiled, float* __restrict__ hsum) {

@@ -34,14 +34,14 @@ def test_struct_sizes_match_the_header(tmp_path):
     """The ctypes mirrors against the header itself: a C program that includes sun.h prints the sizes."""
     import subprocess
     src = tmp_path / "sizes.c"
-    src.write_text('#include <stdio.h>\n#include "sun.h"\nint main(void) { printf("%zu %zu %zu %zu %zu\\n", '
+    src.write_text('#include <stdio.h>\n#include "sun.h"\nint main(void) { printf("%zu %zu %zu %zu %zu %zu\\n", '
                    'sizeof(sun_model_cfg), sizeof(sun_kv_layout), sizeof(sun_qmat), sizeof(sun_weight_ptrs), '
-                   'sizeof(sun_qweight_ptrs)); return 0; }\n')
+                   'sizeof(sun_qweight_ptrs), sizeof(sun_serve_state)); return 0; }\n')
     exe = tmp_path / "sizes"
     subprocess.run(["gcc", "-std=c11", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
     sizes = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert sizes == [C.sizeof(sun.ModelCfg), C.sizeof(sun.KvLayout), C.sizeof(sun.QMat), C.sizeof(sun.WeightPtrs),
-                     C.sizeof(sun.QWeightPtrs)]
+                     C.sizeof(sun.QWeightPtrs), C.sizeof(sun.ServeState)]
     assert C.sizeof(sun.ModelCfg) == 64 and C.sizeof(sun.KvLayout) == 8 + 8 + 12 * 8 + 8 and C.sizeof(sun.QMat) == 24
 
 
@@ -159,10 +159,27 @@ def test_step_rejects_bad_arguments_before_enqueueing(lib):
     assert prefill(ws=None) == 1 and prefill(mid=-1) == 7 and prefill(mid=3) == 7
     assert prefill(n=0) == 6 and prefill(first=-1) == 6 and prefill(first=9 * 16 - 39) == 6   # last position needs a 10th page
     assert prefill(wsb=pneed - 1) == 4 and prefill(ws=FAKE + 8) == 4
+    sneed = lib.sun_serve_workspace_bytes(C.byref(cfg), 8, 9)
+    assert sneed > need
+
+    def serve(pool=pool, w=w, slots=8, mp=9, steps=2, wsb=sneed, ws=FAKE, out=FAKE, **fields):
+        st = sun.ServeState()
+        for name, _ in sun.ServeState._fields_[:14]:
+            setattr(st, name, FAKE)
+        st.n_wait, st.ring_cap, st.idle_page, st.eos_id = 3, 16, 0, -1
+        for k, v in fields.items():
+            setattr(st, k, v)
+        return lib.sun_decode_serve(pool, w, slots, mp, steps, C.byref(st), out, FAKE, None, ws, wsb, None, 0)
+
+    assert serve(pool=None) == 1 and serve(w=None) == 1 and serve(out=None) == 1 and serve(ws=None) == 1
+    assert serve(ring=None) == 1 and serve(counters=None) == 1 and serve(slot_left=None) == 1 and serve(w_budget=None) == 1
+    assert lib.sun_decode_serve(pool, w, 8, 9, 2, None, FAKE, FAKE, None, FAKE, sneed, None, 0) == 1
+    assert serve(slots=0) == 2 and serve(slots=257) == 2 and serve(steps=0) == 2 and serve(n_wait=-1) == 2
+    assert serve(ring_cap=0) == 2 and serve(wsb=sneed - 1) == 4 and serve(ws=FAKE + 8) == 4
     other = sun.make_cfg(wl.TINY_Q, "f32")
     rc, pool2 = _pool(lib, other)
     assert rc == 0 and step(pool=pool2) == 2           # pool and weights of different shapes
-    assert prefill(pool=pool2) == 2
+    assert prefill(pool=pool2) == 2 and serve(pool=pool2) == 2
     lib.sun_kv_pool_destroy(pool2)
     lib.sun_weights_destroy(w)
     lib.sun_kv_pool_destroy(pool)
