@@ -253,6 +253,10 @@ def main():
                          "allocation on the device (TPOT over an output length of K). "
                          "serve: one sun_decode_serve call of K iterations: rows retire at their output budget and "
                          "take waiting requests, on the device (continuous batching)")
+    ap.add_argument("--sweep-step-times", action="store_true",
+                    help="instead of one workload: time the decode step of the --workload shape over a grid of batch "
+                         "sizes and cache lengths (all requests of a point equally long) and print one JSON table; "
+                         "this is the input of paper_2603_02599_amd/placement.py")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (known size) to calibrate FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -337,6 +341,36 @@ def main():
                           "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": f"one prompt of {n} tokens, {shape.name} shape, shuffled pages, "
                                                  "through the decode step's kernels in blocks of 256 rows"}}))
+        return
+    if args.sweep_step_times:
+        from paper_2603_02599_amd import workloads as wl
+        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
+        shared = H.SharedWeights(shape, "bf16", 11, quant_mode=args.quant)
+        fn = sun.sun_qdecode_step if args.quant else sun.sun_decode_step
+        points = []
+        for B in (1, 4, 16, 32, 64, 128, 256):
+            for L in (256, 1024, 2048, 4096, 8192):
+                if B * L > (1 << 20):
+                    continue
+                work = wl.make_workload("cfg2", shape=shape, batch=B, lo=L, hi=L, seed=100 + B)
+                case = H.GpuCase(work, shared=shared)
+                host_lens = work.seq_lens.copy()
+                for _ in range(3):
+                    fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, None, case.next, case.ws,
+                       seq_lens_host=host_lens)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, None, case.next, case.ws,
+                       seq_lens_host=host_lens)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) * 1e3 / args.steps
+                points.append({"batch": B, "len": L, "kv_tokens": int(work.kv_tokens_read), "ms_per_step": ms})
+                print(f"[sweep] batch {B} len {L}: {ms:.3f} ms", file=sys.stderr, flush=True)
+                del case
+                torch.cuda.empty_cache()
+        print(json.dumps({"what": "decode step time", "shape": shape.name, "quant": args.quant, "device": "MI355X",
+                          "steps_per_point": args.steps, "points": points}))
         return
     if args.mode == "serve":
         return bench_serve(args, sun, H)

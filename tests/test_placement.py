@@ -1,0 +1,94 @@
+"""Host-side placement simulator (CPU only): closed forms, a schedule worked out by hand, and the
+qualitative behaviour the paper reports for pooled, model-agnostic decode workers (Figures 3 and 4)."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2603_02599_amd import placement as pl
+
+
+def _synthetic_model(a0=5.0, a_b=0.02, b=2e-5):
+    pts = [{"batch": B, "len": L, "kv_tokens": B * (L + 1), "ms_per_step": a0 + a_b * B + b * B * (L + 1)}
+           for B in (1, 16, 64, 256) for L in (256, 1024, 4096)]
+    return pl.StepTimeModel(pts)
+
+
+def test_zipf_split_closed_forms():
+    assert np.allclose(pl.zipf_split(4, 0.0), [0.25] * 4)
+    assert np.allclose(pl.zipf_split(4, 1.0), np.array([12, 6, 4, 3]) / 25.0)
+    s = pl.zipf_split(4, 1.5)
+    assert abs(s.sum() - 1) < 1e-12 and np.allclose(s[0] / s[1], 2 ** 1.5) and np.allclose(s[0] / s[3], 8.0)
+
+
+def test_step_time_model_recovers_a_linear_law_and_interpolates_in_batch():
+    m = _synthetic_model()
+    assert abs(m.ms_per_kv_token - 2e-5) < 1e-12 and m.max_rel_err < 1e-9
+    assert abs(m.ms(64, 100000) - (5.0 + 1.28 + 2.0)) < 1e-9
+    assert abs(m.ms(40, 0) - (5.0 + 0.02 * 40)) < 1e-9            # between measured batch sizes 16 and 64
+    assert abs(m.ms(1000, 0) - (5.0 + 0.02 * 256)) < 1e-9         # held constant outside the table
+
+
+def test_one_worker_schedule_by_hand():
+    """Two rows, constant 10 ms steps, three requests of two tokens present at t = 0: the first two finish at
+    20 ms, the third enters then and finishes at 40 ms; every request sees one 10 ms gap between its tokens."""
+    m = pl.StepTimeModel([{"batch": b, "len": 1, "kv_tokens": t, "ms_per_step": 10.0} for b in (1, 2) for t in (2, 50)])
+    w = pl.Worker(2, m)
+    reqs = [pl.Request(0, 0.0, 8, 2) for _ in range(3)]
+    w.queue += reqs
+    done, counters, now, ends = [], {"tokens": 0}, 0.0, []
+    end = w.start_step(now)
+    while end is not None:
+        now = end
+        ends.append(round(now, 6))
+        w.finish_step(now, done, (0.0, 1.0), counters)
+        end = w.start_step(now)
+    assert ends == [0.01, 0.02, 0.03, 0.04] and counters["tokens"] == 6
+    assert [round(r.last_token, 6) for r in reqs] == [0.02, 0.02, 0.04]
+    assert all(abs((r.last_token - r.first_token) - 0.01) < 1e-12 for r in reqs)
+
+
+def test_light_load_is_served_in_full_at_the_small_batch_step_time():
+    m = _synthetic_model()
+    r = pl.simulate(m, "shared", 4, 4, rps_total=2.0, alpha=0.0, isl=1024, osl=64, grace_s=10, window_s=60, seed=3)
+    assert 0.85 < r["achieved_over_offered"] < 1.15 and r["backlog_at_end"] <= 4
+    assert 5.0 < r["tpot_ms"] < 5.5
+    assert abs(r["throughput_tok_s"] - 2.0 * 64) < 0.15 * 2.0 * 64
+    with pytest.raises(ValueError):
+        pl.simulate(m, "isolated", 4, 3)
+
+
+def test_pooling_keeps_up_under_skew_where_isolated_workers_do_not():
+    """The shape of Figure 4: at a load the isolated baseline sustains when traffic is uniform, a Zipf skew of
+    1.5 sends 58 % of it to one decode worker, which saturates (achieved / offered falls, its requests queue),
+    while the pooled workers see the same total and are unaffected."""
+    m = _synthetic_model()
+    cap = pl.saturation_rps(m, 1024, 256, 16)
+    kw = dict(n_models=4, n_workers=4, rps_total=0.6 * 4 * cap, isl=1024, osl=256, rows=16, grace_s=20, window_s=60, seed=5)
+    iso0, sh0 = pl.simulate(m, "isolated", alpha=0.0, **kw), pl.simulate(m, "shared", alpha=0.0, **kw)
+    iso, sh = pl.simulate(m, "isolated", alpha=1.5, **kw), pl.simulate(m, "shared", alpha=1.5, **kw)
+    assert iso0["achieved_over_offered"] > 0.9 and sh0["achieved_over_offered"] > 0.9
+    assert sh["achieved_over_offered"] > 0.9 and iso["achieved_over_offered"] < 0.88   # 0.42 + 0.58 / 1.39 = 0.84 expected
+    assert sh["throughput_tok_s"] > 1.15 * iso["throughput_tok_s"]
+    assert iso["backlog_at_end"] > 5 * max(1, sh["backlog_at_end"])
+    assert abs(sh["tpot_ms"] - sh0["tpot_ms"]) < 0.1 * sh0["tpot_ms"]          # pooled: skew changes nothing
+
+
+def test_consolidating_decode_workers_raises_throughput_per_gpu():
+    """The shape of Figure 3: at moderate load the pooled configuration keeps the total throughput with fewer
+    decode workers (fuller batches cost little extra time per step), so throughput per GPU rises and
+    interactivity falls as K goes from 4 to 2."""
+    m = _synthetic_model()
+    cap = pl.saturation_rps(m, 1024, 256, 64)
+    kw = dict(n_models=4, rps_total=0.4 * 4 * cap, alpha=1.5, isl=1024, osl=256, rows=64, grace_s=20, window_s=60, seed=7)
+    k4, k2 = pl.simulate(m, "shared", n_workers=4, **kw), pl.simulate(m, "shared", n_workers=2, **kw)
+    assert abs(k2["throughput_tok_s"] - k4["throughput_tok_s"]) < 0.05 * k4["throughput_tok_s"]
+    assert k2["throughput_tok_s"] / 6 > 1.25 * k4["throughput_tok_s"] / 8
+    assert k2["tpot_ms"] > k4["tpot_ms"]
+
+
+def test_shipped_step_times_load_and_fit():
+    path = os.path.join(pl.DATA_DIR, "step_times_llama8b_bf16_mi355x.json")
+    m = pl.StepTimeModel.from_file(path)
+    assert m.max_rel_err < 0.15 and m.ms_per_kv_token > 0
+    assert 2.0 < m.ms(1, 1025) < m.ms(64, 64 * 2305) < m.ms(256, 256 * 2305) < 60.0
