@@ -7,7 +7,7 @@ Prints ONE JSON line: tokens/s (= batch / step time), TPOT (= step time), the ro
 dominant kernel (paged attention, HBM bound) measured with HIP events inside this run, and the
 CPU oracle timed on a bounded sample of the same workload on this machine's host cores.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5b] [--quant asym|sym]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5b] [--quant asym|sym|sym_noz]
 """
 from __future__ import annotations
 
@@ -34,10 +34,15 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def algorithmic_bytes(shape, work, quant: bool, logits_out: bool = True):
+def w4_bytes_per_weight(quant) -> float:
+    """4-bit codes + an fp16 scale per 128 weights, + an fp16 zero point unless the layout stores none."""
+    return 0.515625 if quant == "sym_noz" else 0.53125
+
+
+def algorithmic_bytes(shape, work, quant, logits_out: bool = True):
     """Bytes the method must move per step: weights once, lm_head (bf16), embedding rows,
     KV read for every cached position incl. the new one, KV write, fp32 logits."""
-    b_w = 0.53125 if quant else 2.0
+    b_w = w4_bytes_per_weight(quant) if quant else 2.0
     weights = shape.body_params * b_w + shape.vocab * shape.hidden * 2
     kv_tok = shape.kv_bytes_per_token()
     kv_read = float(work.kv_tokens_read) * kv_tok
@@ -143,7 +148,7 @@ def bench_run(args, sun, case, work, shape, desc, free_list):
     class _W:  # the average step of the run, for the byte count
         batch = work.batch
         kv_tokens_read = kv_tokens
-    alg = algorithmic_bytes(shape, _W, bool(args.quant), logits_out=False)
+    alg = algorithmic_bytes(shape, _W, args.quant, logits_out=False)
     alg["total"] += work.batch * shape.vocab * 4 / args.steps  # logits are written by the last step only
     out = {
         "metric": "shared-decode tokens/sec", "value": work.batch / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -237,7 +242,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--quant", default=None, choices=[None, "asym", "sym"])
+    ap.add_argument("--quant", default=None, choices=[None, "asym", "sym", "sym_noz"],
+                    help="4-bit group-128 decode weights: affine, symmetric, or symmetric without stored zero points")
     ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
@@ -431,7 +437,7 @@ def main():
     per_step = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)])
     ms_per_step = wall * 1e3 / args.steps
 
-    alg = algorithmic_bytes(shape, work, bool(args.quant))
+    alg = algorithmic_bytes(shape, work, args.quant)
     roof = None
     kernels = {}
     if not args.no_profile:
@@ -453,7 +459,7 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
                 "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
         w_bytes = {"qkv_proj": 0, "o_proj": 1, "gate_up_proj": 2, "down_proj": 3}
-        b_w = 0.53125 if args.quant else 2.0
+        b_w = w4_bytes_per_weight(args.quant) if args.quant else 2.0
         H_, QD, KD, F = shape.hidden, shape.q_dim, shape.kv_dim, shape.ffn
         sizes = {"qkv_proj": (QD + 2 * KD) * H_ * b_w, "o_proj": H_ * QD * b_w, "gate_up_proj": 2 * F * H_ * b_w,
                  "down_proj": H_ * F * b_w, "lm_head": shape.vocab * H_ * 2.0}

@@ -192,6 +192,9 @@ void sun_weights_destroy(sun_weights* w);
  * byte along k (low nibble = even k) [out, in/2], S and Z fp16 [out, in/128], Z
  * holding an integer in [0,15].  embed, gains and wlm are dense as in
  * sun_weight_ptrs (lm_head is not quantised).
+ * Symmetric layout (the quantisation Appendix A.1 names): z = NULL in every sun_qmat means
+ * Z = 8 everywhere, W_hat = (Q - 8) * S; no zero points are stored or read, which leaves
+ * 0.5 + 2/128 = 0.516 bytes per weight.  z must be given for every matrix or for none.
  */
 typedef struct sun_qmat {
     const void* q;
@@ -229,7 +232,8 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* dev, i
  * Z = clamp(rne(-min/S),0,15), Q = clamp(rne(w/S)+Z,0,15).  mode 1 (symmetric,
  * the wording of Appendix A.1): S = fp16(max|w|/7) (1 if 0), Z = 8,
  * Q = clamp(rne(w/S)+8,0,15).  Divisions use the stored fp16 S, in fp32.
- * Outputs (device): q [rows, cols/2] bytes, s and z fp16 [rows, cols/group].
+ * Outputs (device): q [rows, cols/2] bytes, s and z fp16 [rows, cols/group]; z may be NULL in
+ * mode 1 (it would hold 8 everywhere).
  */
 int sun_quantize_w4(const void* w, int dtype, int rows, int cols, int group, int mode, void* q,
                     void* s, void* z, void* stream);

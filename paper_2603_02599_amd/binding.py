@@ -275,7 +275,8 @@ def sun_qweights_create(cfg: ModelCfg, w: Dict[str, object], quant: Dict[str, li
         keep.append(arr)
         setattr(ptrs, k, C.cast(arr, C.POINTER(C.c_void_p)))
     for k in QUANT_KEYS:
-        arr = (QMat * len(quant[k]))(*[QMat(q.data_ptr(), s.data_ptr(), z.data_ptr()) for (q, s, z) in quant[k]])
+        arr = (QMat * len(quant[k]))(*[QMat(q.data_ptr(), s.data_ptr(), z.data_ptr() if z is not None else None)
+                                       for (q, s, z) in quant[k]])
         keep.append(arr)
         setattr(ptrs, k, C.cast(arr, C.POINTER(QMat)))
     ptrs.gf, ptrs.wlm = w["gf"].data_ptr(), w["wlm"].data_ptr()
@@ -289,14 +290,15 @@ def sun_qweights_create(cfg: ModelCfg, w: Dict[str, object], quant: Dict[str, li
 
 
 def sun_quantize_w4(w: torch.Tensor, group: int = 128, mode: str = "asym", stream=None):
-    """Returns (q uint8 [rows, cols/2], s fp16 [rows, cols/group], z fp16 [rows, cols/group])."""
+    """Returns (q uint8 [rows, cols/2], s fp16 [rows, cols/group], z fp16 [rows, cols/group]); mode "sym_noz" is
+    the symmetric grid without stored zero points (z is None: 8 everywhere)."""
     rows, cols = w.shape
     dt = {torch.float32: SUN_F32, torch.bfloat16: SUN_BF16}[w.dtype]
     q = torch.empty((rows, cols // 2), dtype=torch.uint8, device=w.device)
     s = torch.empty((rows, cols // group), dtype=torch.float16, device=w.device)
-    z = torch.empty_like(s)
-    _check(lib().sun_quantize_w4(_p(w), dt, rows, cols, group, {"asym": 0, "sym": 1}[mode], _p(q), _p(s), _p(z),
-                                 _stream(stream)))
+    z = torch.empty_like(s) if mode != "sym_noz" else None
+    _check(lib().sun_quantize_w4(_p(w), dt, rows, cols, group, {"asym": 0, "sym": 1, "sym_noz": 1}[mode], _p(q), _p(s),
+                                 _p(z), _stream(stream)))
     return q, s, z
 
 

@@ -431,11 +431,17 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
         if (int rc = check_ptr_arrays(narrs, 2, cfg->n_layers)) return rc;
     }
     const sun_qmat* const qarrs[] = {d->wq, d->wk, d->wv, d->wo, d->wg, d->wu, d->wd};
+    int with_z = 0, without_z = 0;
     for (auto qa : qarrs) {
         if (!qa) return fail(SUN_ERR_NULL, "a per-layer quantised matrix array is NULL");
-        for (int l = 0; l < cfg->n_layers; ++l)
-            if (!qa[l].q || !qa[l].s || !qa[l].z) return fail(SUN_ERR_NULL, "quantised matrix of layer %d has a NULL part", l);
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            if (!qa[l].q || !qa[l].s) return fail(SUN_ERR_NULL, "quantised matrix of layer %d has a NULL part", l);
+            ++(qa[l].z ? with_z : without_z);
+        }
     }
+    if (with_z && without_z)
+        return fail(SUN_ERR_NULL, "zero points must be given for every quantised matrix or for none (symmetric layout)");
+    const bool s_only = without_z > 0;
     const sun_model_cfg& c = *cfg;
     const int QD = c.n_q_heads * c.head_dim;
     if (c.hidden % kGroup || c.ffn % kGroup || QD % kGroup)
@@ -463,6 +469,7 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
         const int rows[3] = {r0, r1, r2};
         if (bf) {
             m.kind = MAT_W4_PACKED;
+            m.s_only = s_only;
             m.w = pm + off;
             m.sz = pm + off + align_up(packed_w4_bytes(m.N, m.K));
             if (e == hipSuccess) e = launch_pack_w4(src, rows, nsrc, mode, m.K, (void*)m.w, (void*)m.sz, st);
@@ -519,7 +526,7 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
 
 int sun_quantize_w4(const void* w, int dtype, int rows, int cols, int group, int mode, void* q, void* s, void* z,
                     void* stream) {
-    if (!w || !q || !s || !z) return fail(SUN_ERR_NULL, "NULL argument");
+    if (!w || !q || !s || (!z && mode != 1)) return fail(SUN_ERR_NULL, "NULL argument");
     if (dtype != SUN_F32 && dtype != SUN_BF16) return fail(SUN_ERR_SHAPE, "dtype must be SUN_F32 or SUN_BF16");
     if (group != kGroup || rows < 1 || cols < kGroup || cols % kGroup) return fail(SUN_ERR_SHAPE, "group must be 128 and divide cols");
     if (mode != 0 && mode != 1) return fail(SUN_ERR_SHAPE, "mode must be 0 (affine) or 1 (symmetric)");

@@ -111,7 +111,9 @@ struct Mat {
     int kind = MAT_NONE;
     int N = 0, K = 0;          // logical out/in features (N counts gate+up rows for the fused pair)
     const void* w = nullptr;   // F32: row-major fp32; BF16_PACKED / W4_PACKED: packed codes
-    const void* sz = nullptr;  // W4_PACKED: half2 (scale, zero) per (32-row block, group, row)
+    const void* sz = nullptr;  // W4_PACKED: half2 (scale, zero) per (32-row block, group, row); or, with
+                               // s_only, the fp16 scales alone, two groups per dword (zero point 8 everywhere)
+    bool s_only = false;
     // W4_LOGICAL (fp32 activations): logical arrays, up to two stacked sources (gate, up)
     const uint8_t* q[3] = {nullptr, nullptr, nullptr};
     const uint16_t* s[3] = {nullptr, nullptr, nullptr};

@@ -25,6 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct ProjArgs {
     const u32x4* W;
     const uint32_t* SZ;
+    int s_only;    // W4: SZ holds fp16 scales only, two 128-wide groups per dword; the zero point is 8 everywhere
     const u32x4* A;
     const float* hsum;
     float* out;
@@ -66,7 +67,8 @@ void proj_kernel(ProjArgs a) {
 
     // waves past the last column block work on block 0 and drop their result (keeps the loop branch-free)
     const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * (W4 ? 2 : 8) * 64 + lane;
-    const uint32_t* SZl = W4 ? a.SZ + ((size_t)(active ? nb : 0) * kch) * 32 + (lane & 31) : nullptr;
+    const uint32_t* SZl =
+        W4 ? a.SZ + ((size_t)(active ? nb : 0) * (a.s_only ? (kch + 1) >> 1 : kch)) * 32 + (lane & 31) : nullptr;
 
     f32x16 acc[MR];
     f32x16 accg[W4 ? MR : 1];
@@ -82,7 +84,10 @@ void proj_kernel(ProjArgs a) {
     auto load_w = [&](u32x4(&w)[WREGS], uint32_t& sz, int st) {
 #pragma unroll
         for (int j = 0; j < WREGS; ++j) w[j] = Wl[((size_t)st * WREGS + j) * 64];
-        if (W4) sz = SZl[(size_t)((st * KK) >> 3) * 32];
+        if (W4) {
+            const int g = (st * KK) >> 3;
+            sz = SZl[(size_t)(a.s_only ? g >> 1 : g) * 32];
+        }
     };
     auto load_a = [&](int st) {
 #pragma unroll
@@ -156,7 +161,9 @@ void proj_kernel(ProjArgs a) {
                 }
         }
         if (W4 && last) {
-            const __half2 h2 = __builtin_bit_cast(__half2, sz);
+            // scale-only layout: pick this group's half of the dword and put the constant zero point 8.0 beside it
+            const uint32_t szg = a.s_only ? (((sz >> (16 * (((st * KK) >> 3) & 1))) & 0xffffu) | 0x48000000u) : sz;
+            const __half2 h2 = __builtin_bit_cast(__half2, szg);
             const float s = __low2float(h2), nzz = -(128.f + __high2float(h2));
             const float* hs = hs_lds + (((st * KK) >> 3) & 3) * MR * 32;
 #pragma unroll
@@ -335,6 +342,7 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     ProjArgs a{};
     a.W = (const u32x4*)W.w;
     a.SZ = (const uint32_t*)W.sz;
+    a.s_only = W.s_only ? 1 : 0;
     a.A = (const u32x4*)p.A;
     a.hsum = p.hsum;
     a.out = p.out;
@@ -402,7 +410,7 @@ __global__ __launch_bounds__(256) void proj_f32_kernel(F32Mat m, const float* __
             const uint8_t byte = m.q[src][(size_t)r * (m.K / 2) + (k >> 1)];
             const float code = (float)((k & 1) ? (byte >> 4) : (byte & 15));
             const size_t g = (size_t)r * ng + k / kGroup;
-            const float zf = __half2float(__ushort_as_half(m.z[src][g]));
+            const float zf = m.z[src] ? __half2float(__ushort_as_half(m.z[src][g])) : 8.f;
             const float sf = __half2float(__ushort_as_half(m.s[src][g]));
             wv = (code - zf) * sf;  // exact: 5-bit integer times an 11-bit significand
         } else {
@@ -515,8 +523,13 @@ __global__ __launch_bounds__(256) void pack_w4_kernel(PackSrc s, uint32_t* __res
     dst[u] = o;
     if (kk == 0 && half == 0) {
         const size_t g = (size_t)row * kch + c;
-        const uint32_t sv = ((const uint16_t*)s.s[src])[g], zv = ((const uint16_t*)s.z[src])[g];
-        dst_sz[((size_t)nb * kch + c) * 32 + (lane & 31)] = sv | (zv << 16);
+        const uint32_t sv = ((const uint16_t*)s.s[src])[g];
+        if (s.z[src]) {
+            const uint32_t zv = ((const uint16_t*)s.z[src])[g];
+            dst_sz[((size_t)nb * kch + c) * 32 + (lane & 31)] = sv | (zv << 16);
+        } else {  // scales only: groups 2i and 2i+1 share a dword
+            ((uint16_t*)dst_sz)[(((size_t)nb * ((kch + 1) >> 1) + (c >> 1)) * 32 + (lane & 31)) * 2 + (c & 1)] = (uint16_t)sv;
+        }
     }
 }
 
@@ -598,7 +611,7 @@ __global__ __launch_bounds__(256) void quantize_w4_kernel(const void* __restrict
     q[(row * cols + (size_t)g * kGroup) / 2 + lane] = (uint8_t)(qa | (qb << 4));
     if (lane == 0) {
         s[grp] = __half_as_ushort(sh);
-        z[grp] = __half_as_ushort(__float2half_rn(Z));
+        if (z) z[grp] = __half_as_ushort(__float2half_rn(Z));
     }
 }
 

@@ -52,6 +52,14 @@ def weights_to_np(w: Dict[str, object]) -> Dict[str, object]:
     return out
 
 
+def oracle_triple(trip):
+    """(codes, scales, zero points) as the oracle takes them; where the GPU side stores no zero points (the
+    symmetric layout) the oracle gets the definition written out: 8.0 for every group."""
+    q, s, z = trip
+    sn = to_np(s)
+    return to_np(q), sn, (to_np(z) if z is not None else np.full(sn.shape, 0x4800, np.uint16))
+
+
 def layout_strides(lay) -> Dict[str, int]:
     keys = ["k_off", "k_layer", "k_page", "k_head", "k_token", "k_dim",
             "v_off", "v_layer", "v_page", "v_head", "v_token", "v_dim"]
@@ -80,7 +88,7 @@ class SharedWeights:
             wnp = weights_to_np(self.w)
             qnp = None
             if self.quant is not None:
-                qnp = {k: [tuple(to_np(t) for t in trip) for trip in v] for k, v in self.quant.items()}
+                qnp = {k: [oracle_triple(trip) for trip in v] for k, v in self.quant.items()}
                 for k, v in qnp.items():   # dense sources may have been released: only their width is needed
                     if k not in wnp:
                         wnp[k] = [np.empty((0, 2 * trip[0].shape[1]), np.float32) for trip in v]
@@ -143,7 +151,7 @@ class GpuCase:
         wnp = weights_to_np(self.w)
         qnp = None
         if self.quant is not None:
-            qnp = {k: [tuple(to_np(t) for t in trip) for trip in v] for k, v in self.quant.items()}
+            qnp = {k: [oracle_triple(trip) for trip in v] for k, v in self.quant.items()}
         self._keep = (wnp, qnp)
         return _orc().params_from_arrays(wnp, qnp)
 

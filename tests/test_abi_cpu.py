@@ -118,6 +118,31 @@ def test_weights_create_errors_and_sizes(lib):
     qb = lib.sun_qweights_pack_bytes(C.byref(cfg8), 128)
     assert qb == int(wl.LLAMA_8B.body_params * 0.53125) + 2 * 128256 * 4096      # 4 bits + fp16 scale and zero per 128
     assert lib.sun_qweights_pack_bytes(C.byref(cfg8), 64) == 0
+    # quantised tables (fp32 activations: nothing is packed, so fake device pointers are only stored): zero points
+    # for every matrix or for none
+    cfg_q = sun.make_cfg(wl.TINY_Q, "f32")
+    nl = wl.TINY_Q.n_layers
+
+    def qcreate(z_of):
+        qp = sun.QWeightPtrs()
+        arrs = []
+        qp.embed, qp.gf, qp.wlm = FAKE, FAKE, FAKE
+        for k in ("g1", "g2"):
+            a = (C.c_void_p * nl)(*[FAKE] * nl)
+            arrs.append(a)
+            setattr(qp, k, C.cast(a, C.POINTER(C.c_void_p)))
+        for k in sun.QUANT_KEYS:
+            a = (sun.QMat * nl)(*[sun.QMat(FAKE, FAKE, z_of(k, l)) for l in range(nl)])
+            arrs.append(a)
+            setattr(qp, k, C.cast(a, C.POINTER(sun.QMat)))
+        out = C.c_void_p()
+        rc = lib.sun_qweights_create(C.byref(cfg_q), C.byref(qp), 128, None, 0, None, C.byref(out))
+        if rc == 0:
+            lib.sun_weights_destroy(out)
+        return rc
+
+    assert qcreate(lambda k, l: FAKE) == 0 and qcreate(lambda k, l: None) == 0
+    assert qcreate(lambda k, l: None if (k, l) == ("wo", 1) else FAKE) == 1 and b"zero points" in lib.sun_last_error()
 
 
 def test_step_rejects_bad_arguments_before_enqueueing(lib):

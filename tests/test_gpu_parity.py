@@ -97,7 +97,7 @@ def test_argmax_ties_take_the_lowest_index(H, dtype):
 
 def test_fp32_qsun_tiny(H):
     """QSUN with fp32 activations: tight check of the dequantised projections (1e-4)."""
-    for mode in ("asym", "sym"):
+    for mode in ("asym", "sym", "sym_noz"):
         H.say(f"fp32 QSUN tiny_q {mode}")
         work = wl.make_workload("cfg1", shape=wl.TINY_Q, seed=79)
         case = H.GpuCase(work, quant_mode=mode)
@@ -120,6 +120,10 @@ def test_quantiser_matches_oracle_bit_for_bit(H):
             assert int((H.to_np(q) != qo).sum()) == 0
             assert int((H.to_np(s) != so).sum()) == 0
             assert int((H.to_np(z) != zo).sum()) == 0
+            if mode == "sym":       # without stored zero points: same codes and scales, and the grid's zero is 8
+                q2, s2, z2 = sun.sun_quantize_w4(w, 128, "sym_noz")
+                torch.cuda.synchronize()
+                assert z2 is None and torch.equal(q2, q) and torch.equal(s2, s) and (zo == 0x4800).all()
 
 
 @pytest.mark.parametrize("shape,dtype", [(wl.TINY, "f32"), (wl.SMALL128, "bf16"), (wl.TINY_Q, "bf16")])
@@ -227,7 +231,7 @@ def test_bf16_small_full_step(H, batch):
     _full_step_parity(H, case)
 
 
-@pytest.mark.parametrize("mode", ["asym", "sym"])
+@pytest.mark.parametrize("mode", ["asym", "sym", "sym_noz"])
 def test_qsun_small_full_step(H, mode):
     H.say(f"QSUN small128 {mode}")
     work = wl.make_workload("cfg2", shape=wl.SMALL128, batch=40, lo=1, hi=700, seed=91)
@@ -242,6 +246,21 @@ def test_bf16_and_qsun_gqa_ratio_5(H):
         work = wl.make_workload("cfg2", shape=wl.SMALL_G5, batch=20, n_models=4, lo=1, hi=900, seed=95)
         case = H.GpuCase(work, quant_mode=quant)
         _full_step_parity(H, case)
+
+
+def test_symmetric_layout_without_zero_points_equals_the_one_with(H):
+    """Scales only (two groups per dword, zero point 8 implied) against the same grid with stored zero points:
+    the same arithmetic on the same values, so the logits are bit-identical; odd and even group counts, and the
+    14B width whose 80 groups per row split unevenly over the K splits."""
+    for shape, batch in ((wl.SMALL128, 40), (wl.TINY_Q, 9), (wl.SMALL_G5, 70)):
+        H.say(f"QSUN {shape.name}: sym with and without stored zero points")
+        work = wl.make_workload("cfg2", shape=shape, batch=batch, lo=1, hi=500, seed=96)
+        a, b = H.GpuCase(work, quant_mode="sym"), H.GpuCase(work, quant_mode="sym_noz")
+        assert all(trip[2] is None for v in b.quant.values() for trip in v)
+        a.step()
+        b.step()
+        assert torch.equal(a.logits, b.logits) and torch.equal(a.next, b.next)
+        assert torch.equal(a.pool_mem, b.pool_mem)
 
 
 def test_bf16_head_dim_64(H):
