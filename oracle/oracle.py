@@ -275,7 +275,7 @@ def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_le
 
 def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, n_steps: int, waiting, ring_pages,
               idle_page: int, eos_id: int = -1, page_tokens: int = 16, mode: int = 0, forced_tokens=None,
-              state=None, keep_logits: bool = False):
+              state=None, keep_logits: bool = False, bookkeeping_only: bool = False):
     """A decode worker that admits and retires requests between steps (the continuous batching of
     Section 2.1.1): `slots` batch rows, each idle or occupied by one request, the decode step of Eq. 3
     over the occupied rows every iteration, and between iterations, in this order and in row order
@@ -297,8 +297,10 @@ def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, 
     row's own argmax (recorded, tested against eos_id and fed back), so that a replay follows another
     implementation through a near-tie; the row's own logits are kept for the comparison.  state: the dict a
     previous call returned (continues it) or None (all rows idle, then admission, before the first step).
+    bookkeeping_only (needs forced_tokens): the decode step is not run at all; what remains is the schedule
+    and the page accounting, which depend on the tokens through eos_id only.
     Returns the state dict: rows, ring (list, head first), counters, plus tokens/reqs [n_steps, slots]
-    (-1 for idle rows), writes (the (page, slot) every decoded row appended to, Eq. 4) and the logits of every step under keep_logits (rows of idle slots are NaN)."""
+    (-1 for idle rows), writes (step, row, request, page, slot of every position appended, Eq. 4) and the logits of every step under keep_logits (rows of idle slots are NaN)."""
     if state is None:
         st = {"req": [-1] * slots, "left": [0] * slots, "token": [0] * slots, "len": [0] * slots,
               "model": [0] * slots, "tables": np.full((slots, max_pages), -1, np.int32),
@@ -345,10 +347,11 @@ def serve_run(cfg: Cfg, params: Params, pool: Pool, slots: int, max_pages: int, 
     every, writes = [], []
     for s in range(n_steps):
         rows = [i for i in range(slots) if st["req"][i] >= 0]
-        writes += [(int(st["tables"][i, st["len"][i] // page_tokens]), st["len"][i] % page_tokens) for i in rows]
-        lg_all = np.full((slots, cfg.vocab), np.nan)
+        writes += [(s, i, st["req"][i], int(st["tables"][i, st["len"][i] // page_tokens]), st["len"][i] % page_tokens)
+                   for i in rows]
+        lg_all = np.full((slots, cfg.vocab), np.nan) if not bookkeeping_only else None
         nxt = {}
-        if rows:
+        if rows and not bookkeeping_only:
             res = decode_step(cfg, params, pool, np.array([st["token"][i] for i in rows], np.int32),
                               st["tables"][rows], np.array([st["len"][i] for i in rows], np.int32),
                               np.array([st["model"][i] for i in rows], np.int32), mode=mode)

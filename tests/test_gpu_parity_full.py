@@ -171,3 +171,96 @@ def test_cfg2_batch64_run_of_three_steps_sampled(H, dense8b):
         mask |= H.appended_mask(work.shape, st, before.size, tabs, work.seq_lens[rows] + s)
     off, total = H.check_appended_kv(case.pool_pages_now(used), host, before, mask, "bf16")
     H.say(f"   near-ties {near}; pages taken {head}; appended K/V off by >=1 bf16 ulp: {off} of {total}")
+
+
+def test_cfg2_batch64_continuous_batching_sampled(H, dense8b):
+    """sun_decode_serve at the benchmark size: 64 rows of the 8B shape fed from 160 waiting requests with
+    cfg2's lengths and short output budgets, 8 iterations, so that rows retire and are refilled inside the call.
+    The schedule, tables, ring and counters of all rows are compared exactly with the oracle's bookkeeping (its
+    loop without the model: with no end token the schedule does not depend on the tokens); the oracle's model
+    then replays four requests (one that retires early, one admitted in mid-call, the shortest and the longest
+    still running at the end), fed with the GPU's tokens."""
+    slots, n_wait, n_steps = 64, 160, 8
+    base = wl.make_workload("cfg2")
+    rng = np.random.default_rng(base.seed + 21)
+    lens = rng.integers(512, 4097, size=n_wait).astype(np.int32)
+    lens[:8] = lens[:8] - lens[:8] % 16 + 12 + np.arange(8) % 4          # some cross a page boundary during the call
+    budgets = rng.integers(2, 7, size=n_wait).astype(np.int32)
+    budgets[3] = 40                                                        # one request runs through the whole call
+    cols = (int(lens.max()) + 41) // 16 + 1
+    have = lens // 16 + 1
+    ring_n = 96
+    n_pages = 1 + int(have.sum()) + ring_n
+    perm = rng.permutation(n_pages).astype(np.int32)
+    idle, o = int(perm[0]), 1
+    tables = np.full((n_wait, cols), -1, np.int32)
+    for r in range(n_wait):
+        tables[r, :have[r]] = perm[o:o + have[r]]
+        o += int(have[r])
+    ring = [int(p) for p in perm[o:]]
+    waiting = {"req": np.arange(n_wait, dtype=np.int32), "token": rng.integers(0, base.shape.vocab, size=n_wait).astype(np.int32),
+               "tables": tables, "lens": lens, "model": rng.integers(0, 4, size=n_wait).astype(np.int32), "budget": budgets}
+    owait = [{"req": r, "token": int(waiting["token"][r]), "table": tables[r], "len": int(lens[r]),
+              "model": int(waiting["model"][r]), "budget": int(budgets[r])} for r in range(n_wait)]
+    # the schedule, from the oracle's bookkeeping alone (any tokens: there is no end token)
+    fake = np.zeros((n_steps, slots), np.int32)
+    book = H.orc.serve_run(None, None, None, slots, cols, n_steps, owait, ring, idle, forced_tokens=fake, bookkeeping_only=True)
+    assert book["retired"] > 60 and book["admitted"] > 120 and book["status"] == 0
+    last = book["reqs"][-1]
+    running = [int(q) for q in last if q >= 0]
+    first_step = {q: min(w[0] for w in book["writes"] if w[2] == q) for q in set(w[2] for w in book["writes"])}
+    early = next(q for q in range(slots) if budgets[q] <= 3)
+    mid = next(q for q in running if first_step[q] >= 2)
+    picks = sorted({early, mid, min(running, key=lambda q: lens[q]), max(running, key=lambda q: lens[q]), 3})
+    # tables of the picked requests as they stand after the call (pages taken during it included)
+    ptab = tables[picks].copy()
+    for (s, row, q, page, slot) in book["writes"]:
+        if q in picks:
+            ptab[picks.index(q), (int(lens[q]) + (s - first_step[q])) // 16] = page
+    work = base
+    work.page_tables, work.n_pages = np.full((slots, cols), -1, np.int32), n_pages
+    case = H.GpuCase(work, shared=dense8b)
+    case.work.page_tables = ptab                      # for the pool extraction below only
+    before_host, opool, tabs, used = case.extract_pool(list(range(len(picks))))
+    before = before_host.copy()
+    H.say(f"cfg2 serve: {book['admitted']} admitted, {book['retired']} retired in {n_steps} steps; oracle model on requests "
+          f"{picks} (lengths {[int(lens[q]) for q in picks]}, budgets {[int(budgets[q]) for q in picks]})")
+    state = sun.ServeTensors(slots, cols, waiting, ring, n_pages, idle)
+    ws = torch.empty(sun.sun_serve_workspace_bytes(case.cfg, slots, cols), dtype=torch.uint8, device="cuda")
+    toks = torch.empty((n_steps, slots), dtype=torch.int32, device="cuda")
+    reqs = torch.empty((n_steps, slots), dtype=torch.int32, device="cuda")
+    sun.sun_decode_serve(case.pool, case.weights, n_steps, state, toks, reqs, case.logits, ws,
+                         flags=sun.SUN_VALIDATE | sun.SUN_SERVE_RESET)
+    torch.cuda.synchronize()
+    got_t, got_r = toks.cpu().numpy(), reqs.cpu().numpy()
+    # bookkeeping of all rows: exact (the replay is fed the GPU's tokens, which it records and feeds back)
+    book = H.orc.serve_run(None, None, None, slots, cols, n_steps, owait, ring, idle, forced_tokens=got_t, bookkeeping_only=True)
+    assert np.array_equal(got_r, book["reqs"]) and (got_t[got_r < 0] == -1).all()
+    assert np.array_equal(state.page_tables.cpu().numpy(), book["tables"])
+    assert state.seq_lens.cpu().tolist() == book["len"] and state.slot_left.cpu().tolist() == book["left"]
+    assert state.slot_req.cpu().tolist() == book["req"] and state.token_ids.cpu().tolist() == book["token"]
+    cnt = state.counters.cpu().tolist()
+    rg = state.ring.cpu().numpy()
+    assert [int(rg[i % n_pages]) for i in range(cnt[1], cnt[2])] == book["ring"]
+    assert [cnt[0], cnt[3], cnt[4], cnt[5], cnt[6], cnt[7]] == [book["whead"], 0, book["retired"], book["admitted"],
+                                                                book["generated"], n_steps]
+    # the model, for the picked requests: each one's own steps, fed with the GPU's tokens
+    ocfg, params = H.orc.make_cfg(work.shape), case.oracle_params()
+    glogits = case.logits.cpu().numpy()
+    st = H.layout_strides(case.lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
+    mask = np.zeros(before.size, dtype=bool)
+    near = []
+    for j, q in enumerate(picks):
+        where = [(s, int(np.flatnonzero(got_r[s] == q)[0])) for s in range(n_steps) if (got_r[s] == q).any()]
+        forced = np.array([[got_t[s, row]] for s, row in where], np.int32)
+        ref = H.orc.decode_run(ocfg, params, opool, waiting["token"][q:q + 1], tabs[j:j + 1], lens[q:q + 1],
+                               waiting["model"][q:q + 1], np.zeros(0, np.int32), 0, len(where), forced_tokens=forced,
+                               keep_logits=True)
+        for n, (s, row) in enumerate(where):
+            near += [(s, q) for _ in H.check_next_tokens(got_t[s, row:row + 1], ref["logits"][n], 2e-2)]
+            mask |= H.appended_mask(work.shape, st, before.size, tabs[j:j + 1], lens[q:q + 1] + n)
+        if where[-1][0] == n_steps - 1:
+            H.check_logits(glogits[where[-1][1]][None], ref["logits"][-1], "bf16")
+    off, total = H.check_appended_kv(case.pool_pages_now(used), before_host, before, mask, "bf16")
+    H.say(f"   near-ties {near}; K/V of the picked requests off by >=1 bf16 ulp: {off} of {total}")

@@ -101,7 +101,7 @@ def _serve_and_compare(H, S, steps_per_call, eos=-1):
     after[idle_elems] = S.before[idle_elems]
     mask = np.zeros(after.size, bool)             # the slots Eq. 4 says were appended to, over all steps
     one = np.ones((S.shape.n_layers, 1, S.shape.n_kv_heads, S.shape.head_dim), np.uint16)
-    for page, slot in set(ref["writes"]):
+    for page, slot in {(w[3], w[4]) for w in ref["writes"]}:
         probe[:] = 0
         H.orc.kv_ingest(probe, st, one, one, slot, np.array([page], np.int32))
         mask |= probe != 0

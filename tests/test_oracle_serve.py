@@ -151,3 +151,16 @@ def test_budget_is_cut_to_the_table(orc):
     got = _per_request(res)
     assert len(got[100]) == 12 and got[100] == _greedy(orc, cfg, params, prompts[0], 12)   # positions 20..31
     assert res["status"] == 2 and res["retired"] == 1
+
+
+def test_bookkeeping_alone_gives_the_same_schedule(orc):
+    """Without an end token the schedule and the page accounting do not depend on the tokens: the loop with the
+    model switched off (fed any tokens) must reproduce who sat where, the tables, the ring and every write."""
+    lens, budgets = [3, 14, 30, 0, 17, 15], [6, 3, 20, 5, 1, 9]
+    shape, cfg, params, base, pool, waiting, prompts, ring, idle = _setup(orc, lens, budgets, 14, 760, 4)
+    full = orc.serve_run(cfg, params, pool, 2, 4, 30, waiting, ring, idle)
+    fake = np.full((30, 2), 5, np.int32)
+    book = orc.serve_run(None, None, None, 2, 4, 30, waiting, ring, idle, forced_tokens=fake, bookkeeping_only=True)
+    assert np.array_equal(book["reqs"], full["reqs"]) and book["ring"] == full["ring"] and book["writes"] == full["writes"]
+    assert np.array_equal(book["tables"], full["tables"]) and book["retired"] == full["retired"] == 6
+    assert (book["tokens"][book["reqs"] >= 0] == 5).all()
