@@ -54,6 +54,10 @@ def algorithmic_bytes(shape, work, quant, logits_out: bool = True):
 
 def build_workload(name: str):
     from paper_2603_02599_amd import workloads as wl
+    if name.startswith("b") and "x" in name:      # "b<batch>x<len>": 8B shape, that many requests, all that long
+        batch, length = (int(v) for v in name[1:].split("x"))
+        return (wl.make_workload("cfg2", batch=batch, lo=length, hi=length, n_models=min(4, batch), seed=100 + batch),
+                f"8B-shaped shared decode, batch {batch}, every cache {length} long (the grid of --sweep-step-times)")
     if name == "cfg2":
         return wl.make_workload("cfg2"), "8B-shaped shared decode, batch 64 over 4 source models, L~U[512,4096]"
     if name == "cfg3":
@@ -241,7 +245,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg2 (default, the headline configuration), cfg3, cfg5b, small, or b<batch>x<len>")
     ap.add_argument("--quant", default=None, choices=[None, "asym", "sym", "sym_noz"],
                     help="4-bit group-128 decode weights: affine, symmetric, or symmetric without stored zero points")
     ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")

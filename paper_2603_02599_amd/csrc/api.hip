@@ -131,7 +131,7 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
         w.qkv32 = (float*)take((size_t)batch * Nqkv * 4);
         w.o32 = (float*)take((size_t)batch * H * 4);
     }
-    const size_t mc = attn_max_chunks(batch, max_pages);
+    const size_t mc = attn_max_chunks(batch, max_pages, c.n_kv_heads);
     w.plan.max_chunks = (int)std::min<size_t>(mc, 0x7fffffff);
     w.plan.chunk_off = (int32_t*)take((size_t)(batch + 1) * 4);
     w.plan.full_off = (int32_t*)take((size_t)(batch + 1) * 4);
@@ -579,13 +579,13 @@ static int validate_device_arrays(const KvPool& pool, int batch, const int32_t* 
     return SUN_OK;
 }
 
-static int total_chunks_from_host(const int32_t* host, int len_plus, int batch) {
+static int total_chunks_from_host(const int32_t* host, int len_plus, int batch, int Hkv) {
     if (!host) return -1;
     long long tot = 0;
     for (int b = 0; b < batch; ++b) {
         const long long n = std::max<long long>((long long)host[b] + len_plus, 1);
-        int nf, ns;
-        attn_chunking((int)std::min<long long>(n, 0x7fffffff), nf, ns);
+        int nf, ns, ch;
+        attn_chunking((int)std::min<long long>(n, 0x7fffffff), batch, Hkv, nf, ns, ch);
         tot += nf + ns;
     }
     return (int)std::min<long long>(tot, 0x7fffffff);
@@ -619,7 +619,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
     const bool prof = flags & SUN_PROFILE;
     const bool bf = c.act_dtype == SUN_BF16;
     const int H = c.hidden;
-    const int hint = total_chunks_from_host(seq_lens_host, 1, batch);
+    const int hint = total_chunks_from_host(seq_lens_host, 1, batch, c.n_kv_heads);
     float* logits = logits_out ? logits_out : ws.logits;
 
     {
@@ -1003,7 +1003,7 @@ int sun_paged_attention(sun_kv_pool* pool_, int layer, int batch, const float* q
     const Workspace ws = carve(c, batch, max_pages, (char*)workspace);
     if (ws.bytes > workspace_bytes) return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, ws.bytes);
     hipStream_t st = (hipStream_t)stream;
-    const int hint = total_chunks_from_host(n_tokens_host, 0, batch);
+    const int hint = total_chunks_from_host(n_tokens_host, 0, batch, c.n_kv_heads);
     SUN_HIP_CHECK(launch_attn_plan(ws.plan, n_tokens, 0, batch, page_tables, max_pages, (int)pool.lay.n_pages, c.n_kv_heads, st));
     SUN_HIP_CHECK(launch_attn_split(pool, layer, ws.plan, q, page_tables, max_pages, n_tokens, 0, batch, hint,
                                     c.act_dtype == SUN_F32, st));

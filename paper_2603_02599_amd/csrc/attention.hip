@@ -5,9 +5,9 @@
 // handled identically, the pool is addressed through the page table only.
 //
 // Work decomposition: a work item is (request, kv head, chunk of positions).  All but the last
-// 256..511 positions of a request form full chunks of 256, the rest small chunks of 64; the
-// chunk grid of a request depends on its own length only, so a request's result does not depend
-// on its batch-mates.  One persistent workgroup of 8 waves per compute unit works through a
+// 256..511 positions of a request form full chunks of 256, the rest small chunks of 64 (below 64
+// requests the full chunks are shorter, see attn_full_chunk); the chunk grid of a request depends on
+// its own length and the batch size only, so a request's result does not depend on its batch-mates.  One persistent workgroup of 8 waves per compute unit works through a
 // statically dealt item list, full chunks first; a wave streams an item's K and V^T pages with
 // 16-byte loads straight into matrix-core operand registers:
 //   S^T[token, head] = K[token, :] . q[head, :]      (16x16x32 MFMA, q split hi+lo bf16)
@@ -32,9 +32,13 @@ constexpr int kRecInts = 24;  // ints per item record
 #endif
 constexpr int kTopUp = SUN_ATTN_TOPUP;  // small chunks that stand for one full chunk in a wave's item list
 
-size_t attn_max_chunks(int batch, int max_pages) {
-    const size_t per_req = ((size_t)max_pages * kPageTokens) / CH + CH / kAttnSmall + CH / kAttnSmall;
-    return (size_t)batch * per_req;
+size_t attn_max_chunks(int batch, int max_pages, int Hkv) {
+    // An upper bound for every batch size up to `batch` (a workspace sized for a larger batch serves a smaller
+    // one).  Full chunks of a request: n / ch with ch = 256, or a shorter ch only while n * Hkv * b / 2048 < 256,
+    // which bounds b * n / ch by 4096 / Hkv over the b < 64 requests; small chunks: at most
+    // (2 * 256 - 1) / 64 + 1 = 8 per request.
+    const size_t max_tokens = (size_t)max_pages * kPageTokens;
+    return (size_t)batch * (max_tokens / CH + 2 * CH / kAttnSmall + 1) + 4096 / (size_t)Hkv + 64;
 }
 
 // ---------------------------------------------------------------------------------
@@ -42,11 +46,11 @@ size_t attn_max_chunks(int batch, int max_pages) {
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t* __restrict__ n_or_len, int len_plus, int batch,
                                                          int32_t* __restrict__ chunk_off, int32_t* __restrict__ full_off,
-                                                         int32_t* __restrict__ small_off, int max_tokens) {
+                                                         int32_t* __restrict__ small_off, int max_tokens, int Hkv) {
     __shared__ int scan_f[1024], scan_s[1024];
     const int t = threadIdx.x;
-    int nf = 0, ns = 0;
-    if (t < batch) attn_chunking(min(max(n_or_len[t] + len_plus, 1), max_tokens), nf, ns);
+    int nf = 0, ns = 0, ch = 0;
+    if (t < batch) attn_chunking(min(max(n_or_len[t] + len_plus, 1), max_tokens), batch, Hkv, nf, ns, ch);
     scan_f[t] = nf;
     scan_s[t] = ns;
     __syncthreads();
@@ -91,8 +95,9 @@ __global__ __launch_bounds__(256) void attn_records_kernel(const int32_t* __rest
         const int local = idx - off[req] * Hkv, head = local / nc, cj = local % nc;
         const int n = min(max(n_or_len[req] + len_plus, 1), max_pages * kPageTokens);
         const int nfull = full_off[req + 1] - full_off[req];
-        const int t0 = is_full ? cj * CH : nfull * CH + cj * kAttnSmall;
-        const int t1 = is_full ? t0 + CH : min(n, t0 + kAttnSmall);
+        const int ch = attn_full_chunk(n, batch, Hkv);
+        const int t0 = is_full ? cj * ch : nfull * ch + cj * kAttnSmall;
+        const int t1 = is_full ? t0 + ch : min(n, t0 + kAttnSmall);
         const int npages = (t1 - t0 + kPageTokens - 1) / kPageTokens;
         int32_t* rec = records + (size_t)item * kRecInts;
         rec[slot] = slot < npages ? min(max(page_tables[(size_t)req * max_pages + t0 / kPageTokens + slot], 0), n_pages - 1) : -1;
@@ -107,7 +112,7 @@ hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int l
                             const int32_t* page_tables, int max_pages, int n_pages, int Hkv, hipStream_t st) {
     if (batch > 1024) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, st, n_or_len, len_plus, batch, plan.chunk_off,
-                       plan.full_off, plan.small_off, max_pages * kPageTokens);
+                       plan.full_off, plan.small_off, max_pages * kPageTokens, Hkv);
     const long long items = (long long)plan.max_chunks * Hkv;
     const int grid = (int)max(1LL, min((items + 15) / 16, 1024LL));
     hipLaunchKernelGGL(attn_records_kernel, dim3(grid), dim3(256), 0, st, n_or_len, len_plus, batch, plan.chunk_off,

@@ -23,12 +23,26 @@ constexpr int kPageTokens = 16;     // tokens per KV page
 #endif
 constexpr int kAttnChunk = SUN_ATTN_CHUNK;  // tokens per full split-K work item
 constexpr int kAttnSmall = SUN_ATTN_SMALL;  // tokens per small work item at the end of a request
-// A request's chunking depends on its own length only: all but the last full chunk's worth of
-// tokens go into full chunks, the remaining 1 .. 2*kAttnChunk-1 tokens into small chunks.
-__host__ __device__ inline void attn_chunking(int n, int& n_full, int& n_small) {
-    const int f = n / kAttnChunk;
+// Length of a request's full chunks.  From 64 requests up it is kAttnChunk.  A smaller batch has too few
+// chunks of that length to occupy the chip (and one wave walks a chunk step by step, a memory latency per
+// step), so there the length is the power of two in [kAttnSmall, kAttnChunk] that gives about 2048 items over
+// the whole batch if every request were like this one.  It depends on the request's own length, the batch
+// size and the number of KV heads, never on the other requests, so a request's result does not depend on its
+// batch-mates.
+__host__ __device__ inline int attn_full_chunk(int n, int batch, int Hkv) {
+    if (batch >= 64) return kAttnChunk;
+    const long long target = (long long)n * Hkv * batch / 2048;
+    int ch = kAttnSmall;
+    while (2 * ch <= target && 2 * ch <= kAttnChunk) ch *= 2;
+    return ch;
+}
+// All but the last full chunk's worth of tokens go into full chunks of length ch, the remaining
+// 1 .. 2*ch-1 tokens into small chunks.
+__host__ __device__ inline void attn_chunking(int n, int batch, int Hkv, int& n_full, int& n_small, int& ch) {
+    ch = attn_full_chunk(n, batch, Hkv);
+    const int f = n / ch;
     n_full = f > 1 ? f - 1 : 0;
-    n_small = (n - n_full * kAttnChunk + kAttnSmall - 1) / kAttnSmall;
+    n_small = (n - n_full * ch + kAttnSmall - 1) / kAttnSmall;
 }
 constexpr int kGroup = 128;         // quantisation group along K (Appendix A.1)
 constexpr int kMaxBatchTile = 256;  // rows one projection launch covers

@@ -50,7 +50,7 @@ struct AttnPlan {           // device arrays inside the workspace
     float* partial;         // [max_chunks][Hq][d+2]  (o[d], m, l)
     int max_chunks;
 };
-size_t attn_max_chunks(int batch, int max_pages);
+size_t attn_max_chunks(int batch, int max_pages, int Hkv);
 hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch,
                             const int32_t* page_tables, int max_pages, int n_pages, int Hkv, hipStream_t st);
 // n_tokens(i) = n_or_len[i] + len_plus.  q fp32 [batch, Hq*d].  total_chunks_hint < 0 if unknown.
