@@ -168,3 +168,16 @@ def test_serve_validation(H):
         assert e.value.status == status, (kw, e.value.status)
     call()
     torch.cuda.synchronize()
+
+
+def test_serve_many_rows(H):
+    """More rows than one 64-row projection tile and more waiting requests than rows: 130 rows, 300 short
+    requests, so that dozens of rows retire and refill in every iteration."""
+    H.say("serve: fp32 tiny, 130 rows, 300 requests")
+    rng = np.random.default_rng(540)
+    lens = rng.integers(0, 90, size=300)
+    budgets = rng.integers(1, 7, size=300)
+    S = _Setup(H, wl.TINY, "f32", 130, lens, budgets, 40, 8, 541)
+    _, r, ref = _serve_and_compare(H, S, [7, 6])
+    assert ref["admitted"] == 300 and ref["retired"] > 250 and ref["status"] == 0
+    assert (r[0] >= 0).all() and (r[-1] < 0).any()
