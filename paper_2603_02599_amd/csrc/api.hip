@@ -679,15 +679,24 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
                 SUN_HIP_CHECK(launch_residual_norm(c, ws.x, ws.part, so, batch, L.g2, batch, nullptr, ws.hA,
                                                    W.quant ? ws.hs : nullptr, st));
             }
-            const int sg = proj_pick_splits(L.gu, batch, kMaxSplitsWide);
-            {
+            if (!W.quant && batch > 64) {
+                // bf16 above 64 rows (no split-K there): SwiGLU in the epilogue, the down projection's tile as
+                // output.  Up to 64 rows the two-way split over 256 workgroups plus a separate SwiGLU kernel is
+                // faster: unsplit, the 28672 columns make 224 workgroups and leave 32 compute units idle.
                 ProfScope p(prof, 4, st);
-                ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch};
+                ProjLaunch pl{&L.gu, ws.hA, nullptr, batch, EPI_SWIGLU, 1, (float*)ws.uA, L.gu.N, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
-            }
-            {
-                ProfScope p(prof, 7, st);
-                SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, W.quant ? ws.hs : nullptr, st));
+            } else {
+                const int sg = proj_pick_splits(L.gu, batch, kMaxSplitsWide);
+                {
+                    ProfScope p(prof, 4, st);
+                    ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch};
+                    SUN_HIP_CHECK(launch_proj(pl, st));
+                }
+                {
+                    ProfScope p(prof, 7, st);
+                    SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, ws.hs, st));
+                }
             }
             const int sd = proj_pick_splits(L.down, batch, kMaxSplits);
             {
@@ -1038,10 +1047,15 @@ int sun_linear(const sun_weights* weights_, int layer, int mat, int batch, const
     const bool w4 = M.kind == MAT_W4_PACKED;
     SUN_HIP_CHECK(launch_tile_rows(x, batch, M.K, in, w4 ? ws.hs : nullptr, st));
     if (mat == 2) {
-        const int s = proj_pick_splits(M, batch, kMaxSplitsWide);
-        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch};
-        SUN_HIP_CHECK(launch_proj(pl, st));
-        SUN_HIP_CHECK(launch_swiglu_tile(ws.part, s, batch, batch, c.ffn, ws.uA, nullptr, st));
+        if (!w4) {
+            ProjLaunch pl{&M, in, nullptr, batch, EPI_SWIGLU, 1, (float*)ws.uA, M.N, batch};
+            SUN_HIP_CHECK(launch_proj(pl, st));
+        } else {
+            const int s = proj_pick_splits(M, batch, kMaxSplitsWide);
+            ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch};
+            SUN_HIP_CHECK(launch_proj(pl, st));
+            SUN_HIP_CHECK(launch_swiglu_tile(ws.part, s, batch, batch, c.ffn, ws.uA, nullptr, st));
+        }
         SUN_HIP_CHECK(launch_untile_rows(ws.uA, batch, c.ffn, out, st));
     } else if (mat == 4) {
         ProjLaunch pl{&M, in, nullptr, batch, EPI_STORE, 1, out, M.N, batch};

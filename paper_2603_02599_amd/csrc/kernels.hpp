@@ -7,7 +7,8 @@ namespace sun {
 // ---------------- projections (proj.hip) ----------------
 
 enum ProjEpilogue {
-    EPI_STORE = 0    // fp32 partial sums: out[(split * ld_rows + b) * ldo + n]
+    EPI_STORE = 0,   // fp32 partial sums: out[(split * ld_rows + b) * ldo + n]
+    EPI_SWIGLU = 1   // gate/up pair, bf16 weights, no split: out is the two-plane tile of silu(gate) * up [rows, N/2]
 };
 
 struct ProjLaunch {

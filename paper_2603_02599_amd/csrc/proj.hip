@@ -232,7 +232,40 @@ void proj_kernel(ProjArgs a) {
     if (!active) return;
 
     const int col = lane & 31;
-    {
+    if constexpr (EPI == EPI_SWIGLU) {
+        // The wave's 32 columns are 16 gate columns followed by the 16 up columns of the same u columns (the
+        // packing order of the pair): lane c < 16 fetches its up value from lane c + 16 and owns u column
+        // nb*16 + c.  The results leave as the tile the down projection reads: hi and lo plane, 16-byte units
+        // of 8 consecutive u columns of one row, gathered through the wave's own piece of the (now idle)
+        // activation ring.  Every wave has passed the barrier that follows the last stage.
+        uint16_t* sw = reinterpret_cast<uint16_t*>(&lds[0][0]) + (size_t)wave * (MR * 32 * 16 * 2);
+#pragma unroll
+        for (int m = 0; m < MR; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float g = acc[m][r];
+                const float up = __shfl_xor(g, 16);
+                const float y = g / (1.f + __expf(-g)) * up;
+                const uint16_t hi = f32_to_bf16_bits(y);
+                const uint16_t lo = f32_to_bf16_bits(y - bf16_bits_to_f32(hi));
+                const int rl = m * 32 + 8 * (r >> 2) + 4 * half + (r & 3);  // row inside the workgroup's tile
+                if (col < 16) {
+                    sw[(0 * MR * 32 + rl) * 16 + col] = hi;
+                    sw[(1 * MR * 32 + rl) * 16 + col] = lo;
+                }
+            }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's LDS writes have landed (no other wave reads them)
+        __builtin_amdgcn_wave_barrier();
+        u32x4* tile = reinterpret_cast<u32x4*>(a.out);
+#pragma unroll
+        for (int i = 0; i < MR * 2; ++i) {       // MR*32 rows x 2 units x 2 planes = MR*128 units, 64 lanes
+            const int idx = i * 64 + lane;
+            const int plane = idx / (MR * 64), rem = idx % (MR * 64), rl = rem >> 1, un = rem & 1;
+            const int b = mb_off * 32 + rl;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(sw + ((size_t)plane * MR * 32 + rl) * 16 + un * 8);
+            if (b < a.rows) tile[atile_unit(ATile{a.mb_rows}, plane, b, nb * 2 + un)] = v;
+        }
+    } else {
         float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
 #pragma unroll
         for (int m = 0; m < MR; ++m)
@@ -248,6 +281,14 @@ template <int MB, int KS, bool W4, int NW = 4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
     constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
+    if (epilogue == EPI_SWIGLU) {
+        if constexpr (!W4) {
+            if (splits != 1) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, false, NBUF>), grid, block, 0, st, a);
+            return hipGetLastError();
+        }
+        return hipErrorInvalidValue;
+    }
     if (epilogue != EPI_STORE) return hipErrorInvalidValue;
     hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4, NBUF>), grid, block, 0, st, a);
     return hipGetLastError();
