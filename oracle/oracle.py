@@ -34,7 +34,7 @@ class Cfg(C.Structure):
                 ("vocab", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double),
                 ("act_bf16", C.c_int32), ("qk_norm", C.c_int32), ("rope_scaling", C.c_int32),
                 ("rope_orig_max", C.c_int32), ("rope_factor", C.c_double), ("rope_low_freq", C.c_double),
-                ("rope_high_freq", C.c_double)]
+                ("rope_high_freq", C.c_double), ("qkv_bias", C.c_int32), ("pad_", C.c_int32)]
 
 
 class Mat(C.Structure):
@@ -86,7 +86,8 @@ def make_cfg(shape, act_bf16: bool = False) -> Cfg:
     return Cfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                shape.ffn, shape.vocab, float(shape.rms_eps), float(shape.rope_base), int(act_bf16),
                int(bool(getattr(shape, "qk_norm", False))), 1 if rs else 0, int(rs[3]) if rs else 0,
-               float(rs[0]) if rs else 1.0, float(rs[1]) if rs else 1.0, float(rs[2]) if rs else 1.0)
+               float(rs[0]) if rs else 1.0, float(rs[1]) if rs else 1.0, float(rs[2]) if rs else 1.0,
+               int(bool(getattr(shape, "qkv_bias", False))), 0)
 
 
 _KIND = {np.dtype(np.float32): F32, np.dtype(np.uint16): BF16, np.dtype(np.float64): F64}
@@ -124,7 +125,8 @@ class Params:
 
 LAYER_KEYS = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
 HEAD_NORM_KEYS = ("qn", "kn")   # gains of the optional q/k head norm, length head_dim; absent -> ones (unused)
-PER_LAYER = len(LAYER_KEYS) + len(HEAD_NORM_KEYS)
+BIAS_KEYS = ("bq", "bk", "bv")  # biases of the optional q/k/v projection bias; absent -> a dummy (unused)
+PER_LAYER = len(LAYER_KEYS) + len(HEAD_NORM_KEYS) + len(BIAS_KEYS)
 QUANT_KEYS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd")
 
 
@@ -144,7 +146,7 @@ def params_from_arrays(w: Dict[str, object], quant: Optional[Dict[str, list]] = 
                 p.set(1 + PER_LAYER * l + j, w4_mat(q, s, z, cols, group), q, s, z)
             else:
                 p.set(1 + PER_LAYER * l + j, dense_mat(w[k][l]), w[k][l])
-        for j, k in enumerate(HEAD_NORM_KEYS):
+        for j, k in enumerate(HEAD_NORM_KEYS + BIAS_KEYS):
             g = w[k][l] if k in w else np.ones(1, dtype=np.float64)
             p.set(1 + PER_LAYER * l + len(LAYER_KEYS) + j, dense_mat(g), g)
     p.set(1 + PER_LAYER * nl, dense_mat(w["gf"]), w["gf"])

@@ -62,6 +62,8 @@ typedef struct {
     int32_t rope_scaling;  /* backbone option (LLaMA-3.1 class): 0 = none, 1 = frequency-dependent scaling */
     int32_t rope_orig_max; /* original context length of the scaling rule */
     double rope_factor, rope_low_freq, rope_high_freq;
+    int32_t qkv_bias;      /* backbone option (Qwen2 class): q, k and v projections add a bias vector */
+    int32_t pad_;
 } orc_cfg;
 
 /* One parameter tensor, row-major [rows, cols]; y = M x contracts over cols. */
@@ -75,9 +77,10 @@ typedef struct {
     const uint16_t *z;   /* ORC_W4: fp16 zero points, same shape */
 } orc_mat;
 
-/* Parameter table: mats[0]=E, then 11 per layer (g1,Wq,Wk,Wv,Wo,g2,Wg,Wu,Wd and the
- * head-norm gains qn, kn of length head_dim, read only under qk_norm), then g_f, W_lm. */
-enum { M_G1 = 0, M_WQ, M_WK, M_WV, M_WO, M_G2, M_WG, M_WU, M_WD, M_QN, M_KN, M_PER_LAYER };
+/* Parameter table: mats[0]=E, then 14 per layer (g1,Wq,Wk,Wv,Wo,g2,Wg,Wu,Wd, the
+ * head-norm gains qn, kn of length head_dim, read only under qk_norm, and the projection
+ * biases bq, bk, bv, read only under qkv_bias), then g_f, W_lm. */
+enum { M_G1 = 0, M_WQ, M_WK, M_WV, M_WO, M_G2, M_WG, M_WU, M_WD, M_QN, M_KN, M_BQ, M_BK, M_BV, M_PER_LAYER };
 #define MAT_E(m) (&(m)[0])
 #define MAT_L(m, l, w) (&(m)[1 + (l) * M_PER_LAYER + (w)])
 #define MAT_GF(m, nl) (&(m)[1 + (nl) * M_PER_LAYER])
@@ -257,6 +260,19 @@ static void norm_and_rotate(const orc_cfg *c, const orc_mat *mats, int l, double
 
 static double silu(double z) { return z / (1.0 + exp(-z)); }
 
+/* q, k, v of B rows: the three projections of the normed input, plus their bias vectors if the block has them */
+static void qkv_project(const orc_cfg *c, const orc_mat *mats, int l, const double *Hn, int B, double *Q, double *K,
+                        double *V) {
+    double *out[3] = {Q, K, V};
+    const int width[3] = {c->n_q_heads * c->head_dim, c->n_kv_heads * c->head_dim, c->n_kv_heads * c->head_dim};
+    for (int w = 0; w < 3; ++w) {
+        linear(MAT_L(mats, l, M_WQ + w), Hn, B, out[w]);
+        if (c->qkv_bias)
+            for (int b = 0; b < B; ++b)
+                for (int j = 0; j < width[w]; ++j) out[w][(size_t)b * width[w] + j] += mat_get(MAT_L(mats, l, M_BQ + w), 0, j);
+    }
+}
+
 /* 16-bit configuration: a projection consumes bf16 activations. */
 static void act_round(const orc_cfg *c, double *x, size_t n) {
     if (!c->act_bf16) return;
@@ -414,9 +430,7 @@ int orc_decode_step(const orc_cfg *c, const orc_mat *mats, const orc_pool *pool,
     for (int l = 0; l < NL && rc == ORC_OK; ++l) {
         for (int b = 0; b < B; ++b) rmsnorm(MAT_L(mats, l, M_G1), X + (size_t)b * H, H, c->rms_eps, Hn + (size_t)b * H);
         act_round(c, Hn, nx);
-        linear(MAT_L(mats, l, M_WQ), Hn, B, Q);
-        linear(MAT_L(mats, l, M_WK), Hn, B, K);
-        linear(MAT_L(mats, l, M_WV), Hn, B, Vv);
+        qkv_project(c, mats, l, Hn, B, Q, K, Vv);
 #pragma omp parallel for schedule(dynamic, 1)
         for (int b = 0; b < B; ++b) {
             const int64_t L = seq_lens[b], n = L + 1;
@@ -500,9 +514,7 @@ int orc_decode_contig_f64(const orc_cfg *c, const orc_mat *mats, int32_t token, 
     for (int l = 0; l < NL && rc == ORC_OK; ++l) {
         rmsnorm(MAT_L(mats, l, M_G1), X, H, c->rms_eps, Hn);
         act_round(c, Hn, H);
-        linear(MAT_L(mats, l, M_WQ), Hn, 1, q);
-        linear(MAT_L(mats, l, M_WK), Hn, 1, k);
-        linear(MAT_L(mats, l, M_WV), Hn, 1, v);
+        qkv_project(c, mats, l, Hn, 1, q, k, v);
         norm_and_rotate(c, mats, l, q, k, L);
         double *Kl = Kc + (size_t)l * cap * KD, *Vl = Vc + (size_t)l * cap * KD;
         for (int j = 0; j < KD; ++j) {
@@ -541,9 +553,7 @@ int orc_full_forward(const orc_cfg *c, const orc_mat *mats, int T, const int32_t
     for (int l = 0; l < NL && rc == ORC_OK; ++l) {
         for (int t = 0; t < T; ++t) rmsnorm(MAT_L(mats, l, M_G1), X + (size_t)t * H, H, c->rms_eps, Hn + (size_t)t * H);
         act_round(c, Hn, nx);
-        linear(MAT_L(mats, l, M_WQ), Hn, T, Q);
-        linear(MAT_L(mats, l, M_WK), Hn, T, K);
-        linear(MAT_L(mats, l, M_WV), Hn, T, V);
+        qkv_project(c, mats, l, Hn, T, Q, K, V);
         for (int t = 0; t < T; ++t) {
             norm_and_rotate(c, mats, l, Q + (size_t)t * QD, K + (size_t)t * KD, t);
         }

@@ -19,6 +19,7 @@ class MiniShape:
     rope_base: float = 10000.0
     qk_norm: bool = False                 # RMSNorm over head_dim on q and k heads before the rotation
     rope_scaling: tuple = None            # (factor, low_freq_factor, high_freq_factor, original_max_position)
+    qkv_bias: bool = False                # bias vectors on the q, k and v projections
 
 
 def random_weights(shape, rng, dtype=np.float64, std=0.3, gains_random=True):
@@ -49,6 +50,9 @@ def random_weights(shape, rng, dtype=np.float64, std=0.3, gains_random=True):
     if getattr(shape, "qk_norm", False):
         w["qn"] = [np.ascontiguousarray((1.0 + 0.2 * rng.normal(size=shape.head_dim)).astype(dtype)) for _ in range(shape.n_layers)]
         w["kn"] = [np.ascontiguousarray((1.0 + 0.2 * rng.normal(size=shape.head_dim)).astype(dtype)) for _ in range(shape.n_layers)]
+    if getattr(shape, "qkv_bias", False):
+        for k, n in (("bq", qd), ("bk", kd), ("bv", kd)):
+            w[k] = [np.ascontiguousarray(rng.normal(0.0, 0.5, size=n).astype(dtype)) for _ in range(shape.n_layers)]
     return w
 
 

@@ -23,6 +23,9 @@ def _load(model, shape, w):
     for l in range(shape.n_layers):
         for k, n in names.items():
             sd[f"model.layers.{l}.{n}.weight"] = w[k][l]
+        if "bq" in w:
+            for k, n in (("bq", "q_proj"), ("bk", "k_proj"), ("bv", "v_proj")):
+                sd[f"model.layers.{l}.self_attn.{n}.bias"] = w[k][l]
     missing, unexpected = model.load_state_dict({k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in sd.items()},
                                                 strict=False)
     assert not unexpected and all("rotary" in m or "inv_freq" in m for m in missing), (missing, unexpected)
@@ -122,3 +125,40 @@ def test_scaled_rotary_variant_equals_transformers_llama(orc):
     assert np.abs(got - want).max() < 3e-4 * max(1.0, want.std()), np.abs(got - want).max()
     plain = orc.full_forward(orc.make_cfg(MiniShape(**{**shape.__dict__, "rope_scaling": None})), orc.params_from_arrays(w), toks)
     assert np.abs(plain - want).max() > 1e-3
+
+
+def test_qkv_bias_variant_equals_transformers_qwen2(orc):
+    """Backbone option of the Qwen2 class: bias vectors on the q, k and v projections (added before the rotation;
+    the output projection has none)."""
+    shape = MiniShape(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=16, hidden=64, ffn=48, qkv_bias=True)
+    rng = np.random.default_rng(35)
+    w = random_weights(shape, rng)
+    cfg = transformers.Qwen2Config(
+        vocab_size=shape.vocab, hidden_size=shape.hidden, intermediate_size=shape.ffn, num_hidden_layers=shape.n_layers,
+        num_attention_heads=shape.n_q_heads, num_key_value_heads=shape.n_kv_heads, rms_norm_eps=shape.rms_eps,
+        rope_theta=shape.rope_base, max_position_embeddings=512, tie_word_embeddings=False, use_sliding_window=False,
+        attn_implementation="eager")
+    model = transformers.Qwen2ForCausalLM(cfg).double().eval()
+    assert model.model.layers[0].self_attn.q_proj.bias is not None and model.model.layers[0].self_attn.o_proj.bias is None
+    _load(model, shape, w)
+    toks = rng.integers(0, shape.vocab, size=31)
+    with torch.no_grad():
+        want = model(torch.from_numpy(toks)[None]).logits[0].numpy()
+    ocfg, params = orc.make_cfg(shape), orc.params_from_arrays(w)
+    got = orc.full_forward(ocfg, params, toks)
+    assert np.abs(got - want).max() < 3e-4 * max(1.0, want.std()), np.abs(got - want).max()
+    # the option matters, and each of the three vectors does
+    off = orc.full_forward(orc.make_cfg(MiniShape(**{**shape.__dict__, "qkv_bias": False})), params, toks)
+    assert np.abs(off - want).max() > 1e-2
+    for k in ("bq", "bk", "bv"):
+        w2 = dict(w)
+        w2[k] = [np.zeros_like(b) for b in w[k]]
+        assert np.abs(orc.full_forward(ocfg, orc.params_from_arrays(w2), toks) - want).max() > 1e-3, k
+    # and the paged decode step agrees with the forward under the option (the Eq. 1 = Eq. 2 + Eq. 3 identity)
+    from test_oracle_pins import _prefill_into_pool
+    L = 20
+    table = rng.permutation(6)[:3].astype(np.int32)
+    base, pool = _prefill_into_pool(orc, shape, ocfg, params, toks[:L], 6, table, rng)
+    ref = orc.full_forward(ocfg, params, toks[:L + 1], round_kv=True)
+    r = orc.decode_step(ocfg, params, pool, toks[L:L + 1], table[None], [L], [0])
+    assert np.abs(r["logits"][0] - ref[L]).max() < 1e-10
