@@ -83,6 +83,9 @@ typedef struct sun_model_cfg {
                               rope_original_max_position / wavelength */
     int32_t rope_original_max_position;
     float rope_factor, rope_low_freq_factor, rope_high_freq_factor;
+    int32_t qkv_bias;      /* Qwen2 class: 1 = the q, k and v projections add a bias vector (before the head norm
+                              and the rotation); needs bq / bk / bv in the weight table.  Neither family of
+                              Section 4.1 uses it; it is here for the same backbone interface. */
 } sun_model_cfg;
 
 /* ------------------------------------------------------------------ KV pool */
@@ -169,6 +172,9 @@ typedef struct sun_weight_ptrs {
     const void* wlm;
     const void* const* q_norm; /* per layer [head_dim]; read only if cfg.qk_norm, else may be NULL */
     const void* const* k_norm;
+    const void* const* bq;     /* per layer [Hq*d], [Hkv*d], [Hkv*d], element type as the weights; read only if */
+    const void* const* bk;     /* cfg.qkv_bias, else may be NULL */
+    const void* const* bv;
 } sun_weight_ptrs;
 
 typedef struct sun_weights sun_weights;
@@ -217,6 +223,9 @@ typedef struct sun_qweight_ptrs {
     const void* wlm;
     const void* const* q_norm; /* as in sun_weight_ptrs */
     const void* const* k_norm;
+    const void* const* bq;     /* as in sun_weight_ptrs (biases are not quantised) */
+    const void* const* bk;
+    const void* const* bv;
 } sun_qweight_ptrs;
 
 size_t sun_qweights_pack_bytes(const sun_model_cfg* cfg, int group);

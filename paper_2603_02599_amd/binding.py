@@ -50,7 +50,7 @@ class ModelCfg(C.Structure):
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
                 ("rope_base", C.c_float), ("act_dtype", C.c_int32), ("qk_norm", C.c_int32), ("rope_scaling", C.c_int32),
                 ("rope_original_max_position", C.c_int32), ("rope_factor", C.c_float),
-                ("rope_low_freq_factor", C.c_float), ("rope_high_freq_factor", C.c_float)]
+                ("rope_low_freq_factor", C.c_float), ("rope_high_freq_factor", C.c_float), ("qkv_bias", C.c_int32)]
 
 
 class KvLayout(C.Structure):
@@ -64,7 +64,8 @@ class KvLayout(C.Structure):
 class WeightPtrs(C.Structure):
     _fields_ = [("embed", C.c_void_p)] + [(k, C.POINTER(C.c_void_p)) for k in
                                           ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")] + \
-               [("gf", C.c_void_p), ("wlm", C.c_void_p), ("q_norm", C.POINTER(C.c_void_p)), ("k_norm", C.POINTER(C.c_void_p))]
+               [("gf", C.c_void_p), ("wlm", C.c_void_p), ("q_norm", C.POINTER(C.c_void_p)), ("k_norm", C.POINTER(C.c_void_p)),
+                ("bq", C.POINTER(C.c_void_p)), ("bk", C.POINTER(C.c_void_p)), ("bv", C.POINTER(C.c_void_p))]
 
 
 class QMat(C.Structure):
@@ -77,7 +78,8 @@ class QWeightPtrs(C.Structure):
                 ("g2", C.POINTER(C.c_void_p)),
                 ("wg", C.POINTER(QMat)), ("wu", C.POINTER(QMat)), ("wd", C.POINTER(QMat)),
                 ("gf", C.c_void_p), ("wlm", C.c_void_p),
-                ("q_norm", C.POINTER(C.c_void_p)), ("k_norm", C.POINTER(C.c_void_p))]
+                ("q_norm", C.POINTER(C.c_void_p)), ("k_norm", C.POINTER(C.c_void_p)),
+                ("bq", C.POINTER(C.c_void_p)), ("bk", C.POINTER(C.c_void_p)), ("bv", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -160,13 +162,13 @@ def _stream(stream) -> Optional[int]:
 
 def make_cfg(shape, act_dtype: str) -> ModelCfg:
     """shape: object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, rms_eps, rope_base and
-    optionally qk_norm (bool) and rope_scaling = (factor, low_freq_factor, high_freq_factor, original_max_position)."""
+    optionally qk_norm (bool), qkv_bias (bool) and rope_scaling = (factor, low_freq_factor, high_freq_factor, original_max_position)."""
     rs = getattr(shape, "rope_scaling", None)
     return ModelCfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                     shape.vocab, float(shape.rms_eps), float(shape.rope_base),
                     {"f32": SUN_F32, "bf16": SUN_BF16}[act_dtype], int(bool(getattr(shape, "qk_norm", False))),
                     1 if rs else 0, int(rs[3]) if rs else 0, float(rs[0]) if rs else 0.0, float(rs[1]) if rs else 0.0,
-                    float(rs[2]) if rs else 0.0)
+                    float(rs[2]) if rs else 0.0, int(bool(getattr(shape, "qkv_bias", False))))
 
 
 # ------------------------------------------------------------------ pool
@@ -224,9 +226,11 @@ def _ptr_array(tensors: Sequence[torch.Tensor]):
 
 
 def _set_head_norms(ptrs, w, cfg: ModelCfg, keep: List[object]):
-    if not cfg.qk_norm:
-        return
-    for field, key in (("q_norm", "qn"), ("k_norm", "kn")):
+    """Per-layer vectors of the backbone options: head-norm gains (w["qn"], w["kn"]) and projection biases
+    (w["bq"], w["bk"], w["bv"])."""
+    fields = ((("q_norm", "qn"), ("k_norm", "kn")) if cfg.qk_norm else ()) + \
+             ((("bq", "bq"), ("bk", "bk"), ("bv", "bv")) if cfg.qkv_bias else ())
+    for field, key in fields:
         arr = _ptr_array(w[key])
         keep.extend([arr, w[key]])
         setattr(ptrs, field, C.cast(arr, C.POINTER(C.c_void_p)))

@@ -47,6 +47,7 @@ static int check_cfg(const sun_model_cfg* c) {
         return fail(SUN_ERR_SHAPE, "act_dtype must be SUN_F32 or SUN_BF16");
     }
     if (c->qk_norm != 0 && c->qk_norm != 1) return fail(SUN_ERR_SHAPE, "qk_norm must be 0 or 1");
+    if (c->qkv_bias != 0 && c->qkv_bias != 1) return fail(SUN_ERR_SHAPE, "qkv_bias must be 0 or 1");
     if (c->rope_scaling != 0 && c->rope_scaling != 1) return fail(SUN_ERR_SHAPE, "rope_scaling must be 0 or 1");
     if (c->rope_scaling == 1 && (!(c->rope_factor > 0.f) || !(c->rope_low_freq_factor > 0.f) ||
                                  !(c->rope_high_freq_factor > c->rope_low_freq_factor) || c->rope_original_max_position < 1))
@@ -57,7 +58,7 @@ static int check_cfg(const sun_model_cfg* c) {
 static bool same_shape(const sun_model_cfg& a, const sun_model_cfg& b) {
     return a.n_layers == b.n_layers && a.hidden == b.hidden && a.n_q_heads == b.n_q_heads &&
            a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.ffn == b.ffn && a.vocab == b.vocab &&
-           a.qk_norm == b.qk_norm && a.rope_scaling == b.rope_scaling &&
+           a.qk_norm == b.qk_norm && a.qkv_bias == b.qkv_bias && a.rope_scaling == b.rope_scaling &&
            (a.rope_scaling == 0 || (a.rope_original_max_position == b.rope_original_max_position &&
                                     a.rope_factor == b.rope_factor && a.rope_low_freq_factor == b.rope_low_freq_factor &&
                                     a.rope_high_freq_factor == b.rope_high_freq_factor));
@@ -359,6 +360,10 @@ int sun_weights_create(const sun_model_cfg* cfg, const sun_weight_ptrs* d, void*
         const void* const* const narrs[] = {d->q_norm, d->k_norm};
         if (int rc = check_ptr_arrays(narrs, 2, cfg->n_layers)) return rc;
     }
+    if (cfg->qkv_bias) {
+        const void* const* const barrs[] = {d->bq, d->bk, d->bv};
+        if (int rc = check_ptr_arrays(barrs, 3, cfg->n_layers)) return rc;
+    }
     const sun_model_cfg& c = *cfg;
     const bool bf = c.act_dtype == SUN_BF16;
     if (bf) {
@@ -402,6 +407,11 @@ int sun_weights_create(const sun_model_cfg* cfg, const sun_weight_ptrs* d, void*
             L.qn = d->q_norm[l];
             L.kn = d->k_norm[l];
         }
+        if (c.qkv_bias) {
+            L.bq = d->bq[l];
+            L.bk = d->bk[l];
+            L.bv = d->bv[l];
+        }
         pack(L.qkv, 0, d->wq[l], d->wk[l], d->wv[l], QD, KD, KD, 3, 0);
         pack(L.o, 1, d->wo[l], nullptr, nullptr, c.hidden, 0, 0, 1, 0);
         pack(L.gu, 2, d->wg[l], d->wu[l], nullptr, c.ffn, c.ffn, 0, 2, bf ? 1 : 0);
@@ -429,6 +439,10 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
     if (cfg->qk_norm) {
         const void* const* const narrs[] = {d->q_norm, d->k_norm};
         if (int rc = check_ptr_arrays(narrs, 2, cfg->n_layers)) return rc;
+    }
+    if (cfg->qkv_bias) {
+        const void* const* const barrs[] = {d->bq, d->bk, d->bv};
+        if (int rc = check_ptr_arrays(barrs, 3, cfg->n_layers)) return rc;
     }
     const sun_qmat* const qarrs[] = {d->wq, d->wk, d->wv, d->wo, d->wg, d->wu, d->wd};
     int with_z = 0, without_z = 0;
@@ -492,6 +506,11 @@ int sun_qweights_create(const sun_model_cfg* cfg, const sun_qweight_ptrs* d, int
         if (c.qk_norm) {
             L.qn = d->q_norm[l];
             L.kn = d->k_norm[l];
+        }
+        if (c.qkv_bias) {
+            L.bq = d->bq[l];
+            L.bk = d->bk[l];
+            L.bv = d->bv[l];
         }
         pack(L.qkv, 0, &d->wq[l], &d->wk[l], &d->wv[l], QD, KD, KD, 3, 0);
         pack(L.o, 1, &d->wo[l], nullptr, nullptr, c.hidden, 0, 0, 1, 0);
@@ -647,7 +666,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             {
                 ProfScope p(prof, 7, st);
                 SUN_HIP_CHECK(launch_rope_append(pool, l, ws.part, sq, batch, ws.table, seq_lens, page_tables, max_pages,
-                                                 batch, ws.q, L.qn, L.kn, st));
+                                                 batch, ws.q, L.qn, L.kn, L.bq, L.bk, L.bv, st));
             }
         } else {
             ProfScope p(prof, 7, st);
@@ -655,7 +674,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             else SUN_HIP_CHECK(launch_residual_norm(c, ws.x, nullptr, 0, batch, L.g1, batch, ws.h32, nullptr, nullptr, st));
             SUN_HIP_CHECK(launch_proj_f32(L.qkv, ws.h32, batch, ws.qkv32, st));
             SUN_HIP_CHECK(launch_rope_append(pool, l, ws.qkv32, 1, batch, ws.table, seq_lens, page_tables, max_pages,
-                                             batch, ws.q, L.qn, L.kn, st));
+                                             batch, ws.q, L.qn, L.kn, L.bq, L.bk, L.bv, st));
         }
         {
             ProfScope p(prof, 0, st);

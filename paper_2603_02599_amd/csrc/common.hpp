@@ -142,6 +142,7 @@ struct LayerW {
     const void* g2;
     const void* qn = nullptr;  // head-norm gains [head_dim], only with cfg.qk_norm
     const void* kn = nullptr;
+    const void *bq = nullptr, *bk = nullptr, *bv = nullptr;  // projection biases, only with cfg.qkv_bias
     Mat qkv, o, gu, down;
 };
 

@@ -97,7 +97,8 @@ hipError_t launch_rope_table(const sun_model_cfg& cfg, const int32_t* seq_lens, 
 // qkv partial sums [nparts][ld_rows][Nqkv] -> rotated q fp32 [batch, Hq*d]; K,V (bf16) appended to the pool.
 hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, int nparts, int ld_rows,
                               const float* table, const int32_t* seq_lens, const int32_t* page_tables, int max_pages,
-                              int batch, float* q_out, const void* q_norm, const void* k_norm, hipStream_t st);
+                              int batch, float* q_out, const void* q_norm, const void* k_norm, const void* bq, const void* bk,
+                              const void* bv, hipStream_t st);
 hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipStream_t st);
 // gate/up partial sums (projection column order) -> silu(g)*u as two-plane tiled bf16 (+ group sums)
 hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,

@@ -206,6 +206,7 @@ struct RopeArgs {
     int nparts, ld_rows, Hq, Hkv, D, max_pages, n_pages;
     const void* qn;  // head-norm gains [D] for q and k heads, or NULL (no head norm)
     const void* kn;
+    const void *bq, *bk, *bv;  // projection biases [Hq*D], [Hkv*D], [Hkv*D] (element type as the gains), or NULL
     int gain_bf16;
     float eps;
 };
@@ -228,6 +229,12 @@ __global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
             lo += src[s * pstride + j];
             hi += src[s * pstride + j + half];
         }
+    }
+    if (a.bq && act) {  // bias of this head's slice of the q, k or v projection
+        const void* bias = hh < a.Hq ? a.bq : hh < a.Hq + a.Hkv ? a.bk : a.bv;
+        const int h0 = (hh < a.Hq ? hh : hh < a.Hq + a.Hkv ? hh - a.Hq : hh - a.Hq - a.Hkv) * D;
+        lo += a.gain_bf16 ? bf16_bits_to_f32(((const uint16_t*)bias)[h0 + j]) : ((const float*)bias)[h0 + j];
+        hi += a.gain_bf16 ? bf16_bits_to_f32(((const uint16_t*)bias)[h0 + j + half]) : ((const float*)bias)[h0 + j + half];
     }
     if (a.qn && hh < a.Hq + a.Hkv) {  // RMSNorm over the head's D elements (uniform branch: all lanes take part)
         const float ss = wave_sum(lo * lo + hi * hi);
@@ -263,7 +270,8 @@ __global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
 
 hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, int nparts, int ld_rows,
                               const float* table, const int32_t* seq_lens, const int32_t* page_tables, int max_pages,
-                              int batch, float* q_out, const void* q_norm, const void* k_norm, hipStream_t st) {
+                              int batch, float* q_out, const void* q_norm, const void* k_norm, const void* bq, const void* bk,
+                              const void* bv, hipStream_t st) {
     const sun_model_cfg& c = pool.cfg;
     if (c.head_dim > 128) return hipErrorInvalidValue;
     const sun_kv_layout& L = pool.lay;
@@ -295,7 +303,11 @@ hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, i
     a.kn = c.qk_norm ? k_norm : nullptr;
     a.gain_bf16 = c.act_dtype == SUN_BF16;
     a.eps = c.rms_eps;
+    a.bq = c.qkv_bias ? bq : nullptr;
+    a.bk = c.qkv_bias ? bk : nullptr;
+    a.bv = c.qkv_bias ? bv : nullptr;
     if (c.qk_norm && (!q_norm || !k_norm)) return hipErrorInvalidValue;
+    if (c.qkv_bias && (!bq || !bk || !bv)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(rope_append_kernel, dim3(c.n_q_heads + 2 * c.n_kv_heads, batch), dim3(64), 0, st, a);
     return hipGetLastError();
 }

@@ -37,6 +37,7 @@ class Shape:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     qk_norm: bool = False              # Qwen3-class option: RMSNorm over head_dim on q and k heads
+    qkv_bias: bool = False             # Qwen2-class option: bias vectors on the q, k and v projections
     rope_scaling: Optional[tuple] = None  # LLaMA-3.1-class option: (factor, low_freq, high_freq, original_max_position)
 
     @property
@@ -61,6 +62,8 @@ TINY = Shape("tiny", 2, 256, 4, 2, 64, 688, 1024)
 # Tiny shape whose FFN width is a multiple of the 128-wide quantisation group.
 TINY_Q = Shape("tiny_q", 2, 256, 4, 2, 64, 768, 1024)
 # The tiny and small shapes with the backbone options of the paper's model families switched on.
+TINY_BIAS = Shape("tiny_bias", 2, 256, 4, 2, 64, 768, 1024, qkv_bias=True)
+SMALL_BIAS = Shape("small_bias", 2, 512, 8, 2, 128, 1024, 2048, qkv_bias=True)
 TINY_QWEN = Shape("tiny_qwen", 2, 256, 4, 2, 64, 768, 1024, rms_eps=1e-6, rope_base=1000000.0, qk_norm=True)
 SMALL_LLAMA31 = Shape("small_llama31", 2, 512, 8, 2, 128, 1024, 2048, rope_base=500000.0,
                       rope_scaling=(8.0, 1.0, 4.0, 256))
@@ -214,6 +217,12 @@ def make_weights(shape: Shape, dtype: str, device: str, seed: int,
         g_ = g
         w["qn"] = [head_gain() for _ in range(nl)]
         w["kn"] = [head_gain() for _ in range(nl)]
+    if shape.qkv_bias:  # N(0, 0.5^2): large enough that a dropped or misplaced bias shows in the logits
+        def bias(n):
+            return torch.empty(n, dtype=torch.float32, device=device).normal_(0.0, 0.5, generator=g).to(dt)
+        w["bq"] = [bias(shape.q_dim) for _ in range(nl)]
+        w["bk"] = [bias(shape.kv_dim) for _ in range(nl)]
+        w["bv"] = [bias(shape.kv_dim) for _ in range(nl)]
     return w
 
 

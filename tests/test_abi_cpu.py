@@ -42,7 +42,7 @@ def test_struct_sizes_match_the_header(tmp_path):
     sizes = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert sizes == [C.sizeof(sun.ModelCfg), C.sizeof(sun.KvLayout), C.sizeof(sun.QMat), C.sizeof(sun.WeightPtrs),
                      C.sizeof(sun.QWeightPtrs), C.sizeof(sun.ServeState)]
-    assert C.sizeof(sun.ModelCfg) == 64 and C.sizeof(sun.KvLayout) == 8 + 8 + 12 * 8 + 8 and C.sizeof(sun.QMat) == 24
+    assert C.sizeof(sun.ModelCfg) == 68 and C.sizeof(sun.KvLayout) == 8 + 8 + 12 * 8 + 8 and C.sizeof(sun.QMat) == 24
 
 
 FAKE = 0x7F0000000000  # aligned, never dereferenced: these calls fail (or only store it) before any GPU work

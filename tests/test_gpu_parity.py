@@ -248,6 +248,23 @@ def test_bf16_and_qsun_gqa_ratio_5(H):
         _full_step_parity(H, case)
 
 
+@pytest.mark.parametrize("dtype,quant", [("f32", None), ("bf16", None), ("bf16", "asym")])
+def test_qkv_bias_option(H, dtype, quant):
+    """Qwen2-class block: bias vectors on the q, k and v projections, added before the rotation."""
+    H.say(f"q/k/v bias {dtype} quant={quant}")
+    shape = wl.TINY_BIAS if dtype == "f32" else wl.SMALL_BIAS
+    work = wl.make_workload("cfg2", shape=shape, dtype=dtype, batch=14, lo=1, hi=700, seed=98)
+    _full_step_parity(H, H.GpuCase(work, quant_mode=quant))
+    if quant is None:       # the option is live: the same weights without the biases give different logits
+        import dataclasses
+        plain = dataclasses.replace(shape, qkv_bias=False)
+        work2 = wl.make_workload("cfg2", shape=plain, dtype=dtype, batch=14, lo=1, hi=700, seed=98)
+        c1, c2 = H.GpuCase(work), H.GpuCase(work2)
+        c1.step()
+        c2.step()
+        assert (c1.logits - c2.logits).abs().max() > 1e-2
+
+
 def test_symmetric_layout_without_zero_points_equals_the_one_with(H):
     """Scales only (two groups per dword, zero point 8 implied) against the same grid with stored zero points:
     the same arithmetic on the same values, so the logits are bit-identical; odd and even group counts, and the
