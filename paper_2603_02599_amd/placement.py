@@ -177,6 +177,23 @@ def simulate(step_model: StepTimeModel, policy: str, n_models: int = 4, n_worker
             "backlog_at_end": sum(w.load() for w in workers)}
 
 
+def closed_loop(step_model: StepTimeModel, concurrency: int, isl: int, osl: int, ttft_ms: float = 0.0) -> Dict[str, float]:
+    """One decode worker kept at `concurrency` requests in lockstep (the closed-loop client of the paper's
+    concurrency table): TPOT is the mean step time over the osl - 1 steps after the first token, with every
+    row at length isl + t; a request takes ttft + (osl - 1) * TPOT, so the worker delivers
+    TPUT = concurrency * osl / (ttft + (osl - 1) * TPOT) output tokens per second."""
+    steps = [step_model.ms(concurrency, concurrency * (isl + t + 1)) for t in range(1, osl)]
+    tpot = float(np.mean(steps)) if steps else step_model.ms(concurrency, concurrency * (isl + 1))
+    total_ms = ttft_ms + (osl - 1) * tpot
+    return {"concurrency": concurrency, "isl": isl, "osl": osl, "tpot_ms": tpot, "interactivity_tok_s": 1000.0 / tpot,
+            "throughput_tok_s": throughput_from_latencies(concurrency, osl, ttft_ms, tpot) if total_ms > 0 else float("nan")}
+
+
+def throughput_from_latencies(concurrency: int, osl: int, ttft_ms: float, tpot_ms: float) -> float:
+    """Output tokens per second of `concurrency` requests in flight, each taking ttft + (osl - 1) * TPOT."""
+    return concurrency * osl / ((ttft_ms + (osl - 1) * tpot_ms) * 1e-3)
+
+
 def saturation_rps(step_model: StepTimeModel, isl: int, osl: int, rows: int) -> float:
     """Requests/s one worker sustains with every row busy: rows / (osl * step time at the mean cache length)."""
     t = 1e-3 * step_model.ms(rows, rows * (isl + osl / 2.0))
@@ -226,6 +243,9 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--step-times", default=os.path.join(DATA_DIR, "step_times_llama8b_bf16_mi355x.json"))
     ap.add_argument("--figure", type=int, choices=[3, 4], default=3)
+    ap.add_argument("--concurrency-table", action="store_true",
+                    help="instead of a figure: TPOT and throughput at concurrency 1/4/16 and input 1024/2048/4096, output "
+                         "1024 (the grid of the paper's concurrency table), from the measured step times alone (TTFT 0)")
     ap.add_argument("--load", type=float, default=None,
                     help="offered rate as a fraction of what four isolated decode workers sustain (default 0.45 for "
                          "figure 3, 0.6 for figure 4)")
@@ -234,6 +254,13 @@ def main():
     args = ap.parse_args()
     model = StepTimeModel.from_file(args.step_times)
     print(f"step-time model: {model.ms_per_kv_token * 1e3:.4f} us per cached token + a(B); worst fit error {model.max_rel_err:.1%}")
+    if args.concurrency_table:
+        print(f"{'isl':>5} {'conc':>5} {'TPOT ms':>8} {'TPUT tok/s':>11}")
+        for isl in (1024, 2048, 4096):
+            for c in (1, 4, 16):
+                r = closed_loop(model, c, isl, 1024)
+                print(f"{isl:>5d} {c:>5d} {r['tpot_ms']:>8.2f} {r['throughput_tok_s']:>11.1f}")
+        return
     load = args.load if args.load is not None else (0.45 if args.figure == 3 else 0.6)
     rows = (figure3 if args.figure == 3 else figure4)(model, load, args.rows, args.seed)
     print(_table(rows))

@@ -92,3 +92,48 @@ def test_shipped_step_times_load_and_fit():
     m = pl.StepTimeModel.from_file(path)
     assert m.max_rel_err < 0.15 and m.ms_per_kv_token > 0
     assert 2.0 < m.ms(1, 1025) < m.ms(64, 64 * 2305) < m.ms(256, 256 * 2305) < 60.0
+
+
+def _paper_rows():
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_concurrency_table.txt")
+    rows = []
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        model, method, isl, osl, c, ttft, tpot, tput = line.split()
+        rows.append((model, method, int(isl), int(osl), int(c), float(ttft), float(tpot), float(tput)))
+    return rows
+
+
+def test_throughput_identity_holds_on_the_numbers_the_paper_prints():
+    """Appendix "Performance of QSUN in Higher Concurrency and ISL": 54 printed (TTFT, TPOT, TPUT) triples at
+    concurrency 1, 4 and 16.  With c requests in flight, each taking TTFT + (OSL - 1) TPOT, the throughput is
+    c * OSL / (TTFT + (OSL - 1) TPOT); the printed values satisfy that to within 4 % (TPOT is printed to 0.1 ms),
+    which pins the way the simulator turns step times into TPOT, interactivity and throughput."""
+    rows = _paper_rows()
+    assert len(rows) == 54
+    worst = 0.0
+    for model, method, isl, osl, c, ttft, tpot, tput in rows:
+        got = pl.throughput_from_latencies(c, osl, ttft, tpot)
+        worst = max(worst, abs(got - tput) / tput)
+    assert worst < 0.04, worst
+    # a dropped TTFT, OSL instead of OSL - 1 with TTFT counted twice, or a missing concurrency factor all miss it
+    m, me, isl, osl, c, ttft, tpot, tput = [r for r in rows if r[4] == 4 and r[2] == 4096 and r[1] == "AWQ"][0]
+    assert abs(pl.throughput_from_latencies(c, osl, 0.0, tpot) - tput) / tput > 0.05       # TTFT is 8 % of that request
+    assert abs(pl.throughput_from_latencies(1, osl, ttft, tpot) - tput) / tput > 0.5
+    # the paper's headline for QSUN (Section 4.3): TPOT down by up to 45 % against the 16-bit baseline
+    base = {(r[0], r[2], r[4]): r[6] for r in rows if r[1] == "Full-FT"}
+    cut = max(1 - r[6] / base[(r[0], r[2], r[4])] for r in rows if r[1] == "QSUN")
+    assert 0.44 < cut < 0.49
+
+
+def test_closed_loop_metrics_from_a_step_law():
+    m = _synthetic_model()
+    r = pl.closed_loop(m, 4, 1024, 256, ttft_ms=50.0)
+    mean_len = 1024 + 1 + (1 + 255) / 2.0                      # rows at length isl + t + 1, t = 1..255
+    want_tpot = 5.0 + 0.02 * 4 + 2e-5 * 4 * mean_len           # a(B) interpolated between batch 1 and 16
+    assert abs(r["tpot_ms"] - want_tpot) < 1e-9
+    assert abs(r["throughput_tok_s"] - 4 * 256 / ((50.0 + 255 * want_tpot) * 1e-3)) < 1e-6
+    # as in the paper's table: TPOT grows with concurrency and with the input length, throughput with concurrency
+    a, b, c = pl.closed_loop(m, 1, 1024, 64), pl.closed_loop(m, 16, 1024, 64), pl.closed_loop(m, 16, 4096, 64)
+    assert a["tpot_ms"] < b["tpot_ms"] < c["tpot_ms"] and b["throughput_tok_s"] > 10 * a["throughput_tok_s"]
