@@ -181,3 +181,39 @@ def test_serve_many_rows(H):
     _, r, ref = _serve_and_compare(H, S, [7, 6])
     assert ref["admitted"] == 300 and ref["retired"] > 250 and ref["status"] == 0
     assert (r[0] >= 0).all() and (r[-1] < 0).any()
+
+
+def test_serve_without_retirement_equals_the_run(H):
+    """With as many rows as requests and budgets longer than the call, continuous batching has nothing to retire
+    or admit after the start, and must do exactly what sun_decode_run does for the same requests: same tokens,
+    same pages taken in the same order, same cache bits."""
+    H.say("serve == run when nobody retires")
+    lens = [3, 15, 16, 31, 62, 250, 5, 40]
+    S = _Setup(H, wl.SMALL128, "bf16", len(lens), lens, [20] * len(lens), 24, 18, 550)
+    case, n_steps, B = S.case, 14, len(lens)
+    state = sun.ServeTensors(B, S.cols, S.waiting, S.ring, S.n_pages, S.idle)
+    ws = torch.empty(sun.sun_serve_workspace_bytes(case.cfg, B, S.cols), dtype=torch.uint8, device="cuda")
+    toks = torch.empty((n_steps, B), dtype=torch.int32, device="cuda")
+    reqs = torch.empty((n_steps, B), dtype=torch.int32, device="cuda")
+    sun.sun_decode_serve(case.pool, case.weights, n_steps, state, toks, reqs, case.logits, ws,
+                         flags=sun.SUN_VALIDATE | sun.SUN_SERVE_RESET)
+    torch.cuda.synchronize()
+    pool_serve, logits_serve = case.pool_mem.clone(), case.logits.clone()
+    assert (reqs.cpu().numpy() == S.waiting["req"][None, :]).all()
+    # the same requests through sun_decode_run on a fresh copy of the pool
+    case.pool_mem.copy_(torch.from_numpy(S.before.view(np.int16)).cuda().view(torch.bfloat16))
+    d_tok = torch.from_numpy(S.waiting["token"]).cuda()
+    d_tab = torch.from_numpy(S.waiting["tables"]).cuda()
+    d_len = torch.from_numpy(S.waiting["lens"]).cuda()
+    d_ids = torch.from_numpy(S.waiting["model"]).cuda()
+    d_free = torch.tensor(S.ring, dtype=torch.int32, device="cuda")
+    d_head = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = torch.empty((n_steps, B), dtype=torch.int32, device="cuda")
+    sun.sun_decode_run(case.pool, case.weights, n_steps, d_tok, d_tab, d_len, d_ids, d_free, d_head, d_status, out,
+                       case.logits, ws, flags=sun.SUN_VALIDATE)
+    torch.cuda.synchronize()
+    assert torch.equal(out, toks) and torch.equal(case.logits, logits_serve)
+    assert torch.equal(d_tab, state.page_tables) and torch.equal(d_len, state.seq_lens)
+    assert int(d_head.cpu()[0]) == int(state.counters.cpu()[1]) and int(d_status.cpu()[0]) == 0
+    assert torch.equal(case.pool_mem, pool_serve)
