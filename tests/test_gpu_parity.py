@@ -126,7 +126,12 @@ def test_quantiser_matches_oracle_bit_for_bit(H):
                 assert z2 is None and torch.equal(q2, q) and torch.equal(s2, s) and (zo == 0x4800).all()
 
 
-@pytest.mark.parametrize("shape,dtype", [(wl.TINY, "f32"), (wl.SMALL128, "bf16"), (wl.TINY_Q, "bf16")])
+_GQA_SHAPES = [wl.Shape(f"gqa{g}_d128", 1, 256, g, 1, 128, 256, 256) for g in (1, 3, 6, 7, 8)] + \
+              [wl.Shape(f"gqa{g}_d64", 1, 256, 2 * g, 2, 64, 256, 256) for g in (1, 3, 8)]
+
+
+@pytest.mark.parametrize("shape,dtype", [(wl.TINY, "f32"), (wl.SMALL128, "bf16"), (wl.TINY_Q, "bf16")] +
+                         [(s, "bf16") for s in _GQA_SHAPES], ids=lambda v: v.name if hasattr(v, "name") else v)
 def test_paged_attention_op(H, shape, dtype):
     """Attention sub-step alone against the oracle's paged attention (ragged lengths, shuffled tables)."""
     from oracle import oracle as orc
