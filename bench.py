@@ -86,12 +86,12 @@ def cpu_baseline(case, work, n_sample: int):
     tests = os.path.join(ROOT, "tests")
     if tests not in sys.path:
         sys.path.insert(0, tests)
-    import gpu_harness as H
+    import gpu_harness as H   # the tests' oracle mirrors: the only leg of bench.py that touches the oracle
     from oracle import oracle as orc
     order = np.argsort(work.seq_lens)
     rows = sorted({int(order[int(round(q * (work.batch - 1)))]) for q in np.linspace(0, 1, n_sample)})
-    params = case.oracle_params()
-    host, pool, tabs, used = case.extract_pool(rows)
+    params = H.case_oracle_params(case)
+    host, pool, tabs, used = H.case_extract_pool(case, rows)
     ocfg = orc.make_cfg(work.shape)
     t0 = time.perf_counter()
     orc.decode_step(ocfg, params, pool, work.tokens[rows], tabs, work.seq_lens[rows], work.model_ids[rows])
@@ -198,7 +198,7 @@ def bench_serve(args, sun, H):
     work = base
     work.page_tables, work.n_pages = np.full((slots, cols), -1, np.int32), n_pages
     t_setup = time.perf_counter()
-    case = H.GpuCase(work, quant_mode=args.quant)
+    case = H.DeviceCase(work, quant_mode=args.quant)
     if args.quant:
         for k in sun.QUANT_KEYS:
             case.w[k] = None
@@ -284,13 +284,10 @@ def main():
         raise SystemExit("bench.py: this build measures one GPU only (one decode worker holds a full copy of the "
                          "shared decode weights; more GPUs are more independent workers). Run with --gpus 1.")
     import torch
-    tests = os.path.join(ROOT, "tests")
-    if tests not in sys.path:
-        sys.path.insert(0, tests)
     from paper_2603_02599_amd import binding as sun
     sun.lib()  # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    import gpu_harness as H   # plumbing only (device buffers, handles); the oracle is used in cpu_baseline alone
+    from paper_2603_02599_amd import device_case as H   # device buffers and handles; nothing of the oracle
 
     if args.ingest_tokens > 0:
         from paper_2603_02599_amd import workloads as wl
@@ -356,7 +353,7 @@ def main():
     if args.sweep_step_times:
         from paper_2603_02599_amd import workloads as wl
         shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
-        shared = H.SharedWeights(shape, "bf16", 11, quant_mode=args.quant)
+        shared = H.DeviceWeights(shape, "bf16", 11, quant_mode=args.quant)
         fn = sun.sun_qdecode_step if args.quant else sun.sun_decode_step
         points = []
         for B in (1, 4, 16, 32, 64, 128, 256):
@@ -364,7 +361,7 @@ def main():
                 if B * L > (1 << 20):
                     continue
                 work = wl.make_workload("cfg2", shape=shape, batch=B, lo=L, hi=L, seed=100 + B)
-                case = H.GpuCase(work, shared=shared)
+                case = H.DeviceCase(work, shared=shared)
                 host_lens = work.seq_lens.copy()
                 for _ in range(3):
                     fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, None, case.next, case.ws,
@@ -399,7 +396,7 @@ def main():
         assert len(free_list) >= work.batch * (grow // 16 + 1), "pool has too few spare pages for this output length"
         work.page_tables = wide
     t_setup = time.perf_counter()
-    case = H.GpuCase(work, quant_mode=args.quant)
+    case = H.DeviceCase(work, quant_mode=args.quant)
     if args.quant:  # the dense projection sources are no longer needed on the device
         for k in sun.QUANT_KEYS:
             case.w[k] = None

@@ -1,6 +1,6 @@
-"""Test-side plumbing for GPU parity: builds one workload on the GPU, mirrors exactly the
-bytes the GPU consumes into the CPU oracle, and compares.  The oracle is imported on first use only, so that
-bench.py can share the case-building code without touching it outside its cpu_baseline leg."""
+"""Test-side plumbing for GPU parity: on top of the package's device-side case (pool, weights, inputs on the
+GPU) it mirrors exactly the bytes the GPU consumes into the CPU oracle, and compares.  The oracle is imported on
+first use only."""
 from __future__ import annotations
 
 import sys
@@ -11,6 +11,7 @@ import torch
 
 from paper_2603_02599_amd import binding as sun
 from paper_2603_02599_amd import workloads as wl
+from paper_2603_02599_amd.device_case import DEV, DeviceCase, DeviceWeights, layout_strides, say, to_np, weights_to_np  # noqa: F401
 
 
 def _orc():
@@ -25,33 +26,6 @@ def __getattr__(name):  # H.orc for the tests
     raise AttributeError(name)
 
 
-DEV = "cuda:0"
-
-
-def say(msg: str):
-    print(f"[gpu-case] {msg}", flush=True)
-    sys.stdout.flush()
-
-
-def to_np(t: torch.Tensor) -> np.ndarray:
-    t = t.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).numpy().view(np.uint16)
-    if t.dtype == torch.float16:
-        return t.view(torch.int16).numpy().view(np.uint16)
-    return t.numpy()
-
-
-def weights_to_np(w: Dict[str, object]) -> Dict[str, object]:
-    out = {}
-    for k, v in w.items():
-        if isinstance(v, list):
-            out[k] = [to_np(t) for t in v]
-        elif isinstance(v, torch.Tensor):
-            out[k] = to_np(v)
-    return out
-
-
 def oracle_triple(trip):
     """(codes, scales, zero points) as the oracle takes them; where the GPU side stores no zero points (the
     symmetric layout) the oracle gets the definition written out: 8.0 for every group."""
@@ -60,134 +34,76 @@ def oracle_triple(trip):
     return to_np(q), sn, (to_np(z) if z is not None else np.full(sn.shape, 0x4800, np.uint16))
 
 
-def layout_strides(lay) -> Dict[str, int]:
-    keys = ["k_off", "k_layer", "k_page", "k_head", "k_token", "k_dim",
-            "v_off", "v_layer", "v_page", "v_head", "v_token", "v_dim"]
-    return {k: int(getattr(lay, k)) for k in keys}
-
-
-class SharedWeights:
-    """Decode weights on the GPU (dense, and optionally their 4-bit quantisation) with the library
-    handle and a lazily built oracle mirror; shared by several workloads of the same shape."""
-
-    def __init__(self, shape, dtype: str, seed: int, quant_mode: Optional[str] = None):
-        self.shape, self.dtype = shape, dtype
-        self.cfg = sun.make_cfg(shape, dtype)
-        self.w = wl.make_weights(shape, dtype, DEV, seed)
-        self.quant = None
-        if quant_mode is None:
-            self.handle = sun.sun_weights_create(self.cfg, self.w)
-        else:
-            self.quant = {k: [sun.sun_quantize_w4(m, 128, quant_mode) for m in self.w[k]] for k in sun.QUANT_KEYS}
-            self.handle = sun.sun_qweights_create(self.cfg, self.w, self.quant)
-        torch.cuda.synchronize()
-        self._params = None
-
-    def oracle_params(self):
-        if self._params is None:
-            wnp = weights_to_np(self.w)
-            qnp = None
-            if self.quant is not None:
-                qnp = {k: [oracle_triple(trip) for trip in v] for k, v in self.quant.items()}
-                for k, v in qnp.items():   # dense sources may have been released: only their width is needed
-                    if k not in wnp:
-                        wnp[k] = [np.empty((0, 2 * trip[0].shape[1]), np.float32) for trip in v]
-            self._keep = (wnp, qnp)
-            self._params = _orc().params_from_arrays(wnp, qnp)
-        return self._params
-
-
-class GpuCase:
-    """One workload resident on the GPU with handles created through the C ABI."""
-
-    def __init__(self, work: wl.Workload, weights: Optional[Dict[str, object]] = None, quant_mode: Optional[str] = None,
-                 pool_seed: Optional[int] = None, weights_seed: Optional[int] = None,
-                 shared: Optional[SharedWeights] = None):
-        self.work = work
-        shape = work.shape
-        self.cfg = sun.make_cfg(shape, work.dtype)
-        self.shared = shared
-        if shared is not None:
-            self.w = shared.w
-        else:
-            self.w = weights if weights is not None else wl.make_weights(shape, work.dtype, DEV, weights_seed or work.seed + 1)
-        nbytes = sun.sun_kv_pool_bytes(self.cfg, work.n_pages)
-        self.pool_mem = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=DEV)
-        wl.fill_kv_pool(self.pool_mem, pool_seed or work.seed + 2)
-        self.pool = sun.sun_kv_pool_create(self.cfg, self.pool_mem, 16, work.n_models)
-        self.lay = self.pool.layout()
-        assert self.lay.n_pages == work.n_pages
-        self.quant = None
-        if shared is not None:
-            self.quant, self.weights = shared.quant, shared.handle
-        elif quant_mode is None:
-            self.weights = sun.sun_weights_create(self.cfg, self.w)
-        else:
-            self.quant = {k: [sun.sun_quantize_w4(m, 128, quant_mode) for m in self.w[k]] for k in sun.QUANT_KEYS}
-            self.weights = sun.sun_qweights_create(self.cfg, self.w, self.quant)
-        self.tokens = torch.from_numpy(work.tokens).to(DEV)
-        self.tables = torch.from_numpy(work.page_tables).to(DEV)
-        self.lens = torch.from_numpy(work.seq_lens).to(DEV)
-        self.ids = torch.from_numpy(work.model_ids).to(DEV)
-        self.ws = torch.empty(sun.sun_workspace_bytes(self.cfg, work.batch, work.max_pages), dtype=torch.uint8, device=DEV)
-        self.logits = torch.empty((work.batch, shape.vocab), dtype=torch.float32, device=DEV)
-        self.next = torch.empty(work.batch, dtype=torch.int32, device=DEV)
-        torch.cuda.synchronize()
-
-    def step(self, flags: int = 0, host_lens: bool = True, tokens=None, tables=None, lens=None, ids=None,
-             logits=None, nxt=None):
-        fn = sun.sun_qdecode_step if self.quant is not None else sun.sun_decode_step
-        lens_t = self.lens if lens is None else lens
-        fn(self.pool, self.weights, self.tokens if tokens is None else tokens,
-           self.tables if tables is None else tables, lens_t, self.ids if ids is None else ids,
-           self.logits if logits is None else logits, self.next if nxt is None else nxt, self.ws,
-           seq_lens_host=(lens_t.cpu().numpy() if host_lens else None), flags=flags)
-        torch.cuda.synchronize()
-
-    # ---- oracle mirror ----
-    def oracle_params(self):
-        if self.shared is not None:
-            return self.shared.oracle_params()
-        wnp = weights_to_np(self.w)
+def weights_oracle_params(sw: DeviceWeights):
+    """Oracle mirror of shared device weights, built once per object."""
+    if getattr(sw, "_params", None) is None:
+        wnp = weights_to_np(sw.w)
         qnp = None
-        if self.quant is not None:
-            qnp = {k: [oracle_triple(trip) for trip in v] for k, v in self.quant.items()}
-        self._keep = (wnp, qnp)
-        return _orc().params_from_arrays(wnp, qnp)
+        if sw.quant is not None:
+            qnp = {k: [oracle_triple(trip) for trip in v] for k, v in sw.quant.items()}
+            for k, v in qnp.items():   # dense sources may have been released: only their width is needed
+                if k not in wnp:
+                    wnp[k] = [np.empty((0, 2 * trip[0].shape[1]), np.float32) for trip in v]
+        sw._keep = (wnp, qnp)
+        sw._params = _orc().params_from_arrays(wnp, qnp)
+    return sw._params
+
+
+def case_oracle_params(case: DeviceCase):
+    if case.shared is not None:
+        return weights_oracle_params(case.shared)
+    wnp = weights_to_np(case.w)
+    qnp = None
+    if case.quant is not None:
+        qnp = {k: [oracle_triple(trip) for trip in v] for k, v in case.quant.items()}
+    case._keep = (wnp, qnp)
+    return _orc().params_from_arrays(wnp, qnp)
+
+
+def case_extract_pool(case: DeviceCase, rows: Sequence[int]):
+    """Copies only the pages the given requests reference into a compact host pool with
+    the same in-page layout; returns (host uint16 array, oracle pool, remapped tables, page ids)."""
+    work, lay = case.work, case.lay
+    tabs = work.page_tables[list(rows)]
+    used = np.unique(tabs[tabs >= 0])
+    remap = {int(p): i for i, p in enumerate(used)}
+    new_tabs = np.vectorize(lambda p: remap.get(int(p), -1))(tabs).astype(np.int32)
+    page_elems = int(lay.k_page)
+    nl = work.shape.n_layers
+    view = case.pool_mem.view(nl, int(lay.n_pages), page_elems)
+    idx = torch.from_numpy(used.astype(np.int64)).to(DEV)
+    small = view.index_select(1, idx).contiguous()
+    host = to_np(small).reshape(-1).copy()
+    st = layout_strides(lay)
+    st["k_layer"] = st["v_layer"] = len(used) * page_elems
+    pool = _orc().make_pool(host, len(used), 16, st)
+    return host, pool, new_tabs, used
+
+
+class SharedWeights(DeviceWeights):
+    """Decode weights on the GPU with a lazily built oracle mirror."""
+
+    def oracle_params(self):
+        return weights_oracle_params(self)
+
+
+class GpuCase(DeviceCase):
+    """One workload resident on the GPU, with the oracle mirrors the parity tests need."""
+
+    def oracle_params(self):
+        return case_oracle_params(self)
 
     def extract_pool(self, rows: Sequence[int]):
-        """Copies only the pages the given requests reference into a compact host pool with
-        the same in-page layout; returns (host uint16 array, oracle pool, remapped tables)."""
-        work, lay = self.work, self.lay
-        tabs = work.page_tables[list(rows)]
-        used = np.unique(tabs[tabs >= 0])
-        remap = {int(p): i for i, p in enumerate(used)}
-        new_tabs = np.vectorize(lambda p: remap.get(int(p), -1))(tabs).astype(np.int32)
-        page_elems = int(lay.k_page)
-        nl = work.shape.n_layers
-        view = self.pool_mem.view(nl, int(lay.n_pages), page_elems)
-        idx = torch.from_numpy(used.astype(np.int64)).to(DEV)
-        small = view.index_select(1, idx).contiguous()
-        host = to_np(small).reshape(-1).copy()
-        st = layout_strides(lay)
-        st["k_layer"] = st["v_layer"] = len(used) * page_elems
-        pool = _orc().make_pool(host, len(used), 16, st)
-        return host, pool, new_tabs, used
-
-    def pool_pages_now(self, used: np.ndarray) -> np.ndarray:
-        lay = self.lay
-        view = self.pool_mem.view(self.work.shape.n_layers, int(lay.n_pages), int(lay.k_page))
-        idx = torch.from_numpy(used.astype(np.int64)).to(DEV)
-        return to_np(view.index_select(1, idx).contiguous()).reshape(-1)
+        return case_extract_pool(self, rows)
 
 
-def run_oracle(case: GpuCase, rows: Sequence[int], params=None, tokens=None, lens=None, ids=None, **kw):
+def run_oracle(case: DeviceCase, rows: Sequence[int], params=None, tokens=None, lens=None, ids=None, **kw):
     """Oracle step on the sampled requests, from the pool state *before* the GPU step
     (call this before case.step())."""
     work = case.work
     rows = list(rows)
-    host, pool, tabs, used = case.extract_pool(rows)
-    params = params if params is not None else case.oracle_params()
+    host, pool, tabs, used = case_extract_pool(case, rows)
+    params = params if params is not None else case_oracle_params(case)
     ocfg = _orc().make_cfg(work.shape)
     toks = (work.tokens if tokens is None else tokens)[rows]
     ln = (work.seq_lens if lens is None else lens)[rows]
