@@ -249,7 +249,7 @@ def main():
                     help="cfg2 (default, the headline configuration), cfg3, cfg5b, small, or b<batch>x<len>")
     ap.add_argument("--quant", default=None, choices=[None, "asym", "sym", "sym_noz"],
                     help="4-bit group-128 decode weights: affine, symmetric, or symmetric without stored zero points")
-    ap.add_argument("--cpu-sample", type=int, default=4, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=24, help="requests the oracle is timed on (0 = skip); 24 are about 10 s of CPU work")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
     ap.add_argument("--ingest-tokens", type=int, default=0,
