@@ -63,7 +63,7 @@ enum {
  * Decoder shape (pre-norm Llama-style block: RMSNorm, GQA attention with rotary
  * embedding in half-split pairing, SwiGLU, untied lm_head).  act_dtype selects the
  * arithmetic: SUN_F32 = fp32 weights and activations on the vector ALUs (parity
- * configuration), SUN_BF16 = bf16 weights, bf16 matrix-core inputs, fp32
+ * configuration), SUN_BF16 = bf16 weights, activations as two bf16 planes (value + remainder) into the matrix cores, fp32
  * accumulators / residual stream / softmax.  The KV pool is bf16 in both.
  * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with ratio
  * <= 8; SUN_BF16 additionally needs hidden, ffn and n_q_heads*head_dim multiples
@@ -465,7 +465,8 @@ int sun_paged_attention(sun_kv_pool* pool, int layer, int batch, const float* q,
  *   mat: index into the projection list of layer `layer`: 0 = [Wq;Wk;Wv] stacked,
  *        1 = Wo, 2 = fused silu(Wg x) * (Wu x) (out has ffn columns), 3 = Wd, 4 = lm_head
  *        (layer ignored).  x dev fp32 [batch, in]; out dev fp32 [batch, out].
- * Under SUN_BF16 x is rounded to bf16 first, as in the step.
+ * Under SUN_BF16 x enters the matrix cores as in the step: two bf16 values per element (the rounded value and
+ * the rounded remainder, 16 significant bits together); the output of mat 2 passes through the same split.
  */
 int sun_linear(const sun_weights* weights, int layer, int mat, int batch, const float* x, float* out,
                void* workspace, size_t workspace_bytes, void* stream);
