@@ -5,6 +5,8 @@
 #include <string.h>
 
 #include <algorithm>
+#include <exception>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -30,6 +32,18 @@ static int fail(int code, const char* fmt, ...) {
 }
 
 static size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Host-side checks allocate with std::vector; no C++ exception may leave through the C ABI.
+template <class F>
+static int guarded(F&& f) {
+    try {
+        return f();
+    } catch (const std::bad_alloc&) {
+        return fail(SUN_ERR_NULL, "out of host memory");
+    } catch (const std::exception& e) {
+        return fail(SUN_ERR_NULL, "host error: %s", e.what());
+    }
+}
 
 static int check_cfg(const sun_model_cfg* c) {
     if (!c) return fail(SUN_ERR_NULL, "cfg is NULL");
@@ -151,7 +165,8 @@ struct ProfRec {
     int kind;
     hipEvent_t a, b;
 };
-static std::vector<ProfRec> g_prof;
+static std::vector<ProfRec> g_prof;   // shared by all threads of the process
+static std::mutex g_prof_mu;
 
 struct ProfScope {
     bool on;
@@ -169,7 +184,13 @@ struct ProfScope {
     ~ProfScope() {
         if (!on) return;
         (void)hipEventRecord(rec.b, st);
-        g_prof.push_back(rec);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        try {
+            g_prof.push_back(rec);
+        } catch (const std::exception&) {   // this launch goes untimed
+            (void)hipEventDestroy(rec.a);
+            (void)hipEventDestroy(rec.b);
+        }
     }
 };
 
@@ -183,6 +204,7 @@ const char* sun_last_error(void) { return g_err; }
 const char* sun_version(void) { return "libsun 0.1 (gfx950)"; }
 
 void sun_profile_reset(void) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
     for (auto& r : g_prof) {
         (void)hipEventDestroy(r.a);
         (void)hipEventDestroy(r.b);
@@ -194,6 +216,7 @@ int sun_profile_read(int kind, double* ms, int64_t* launches) {
     if (!ms || !launches) return fail(SUN_ERR_NULL, "NULL output");
     double tot = 0;
     int64_t n = 0;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
     for (auto& r : g_prof)
         if (r.kind == kind) {
             float t = 0;
@@ -232,7 +255,10 @@ int sun_kv_pool_create(const sun_model_cfg* cfg, void* dev_mem, size_t bytes, in
     p->base = (uint16_t*)dev_mem;
     p->lay = make_layout(*cfg, n_pages);
     p->n_source_models = n_source_models;
-    p->ingested.assign((size_t)n_source_models, 0);
+    if (int rc = guarded([&] { p->ingested.assign((size_t)n_source_models, 0); return (int)SUN_OK; })) {
+        delete p;
+        return rc;
+    }
     *out = (sun_kv_pool*)p;
     return SUN_OK;
 }
@@ -259,13 +285,17 @@ int sun_kv_pool_ingest(sun_kv_pool* pool_, int model_id, const void* k_src, cons
     if (((uintptr_t)k_src | (uintptr_t)v_src) % 16) return fail(SUN_ERR_SHAPE, "k_src and v_src must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     if (flags & SUN_VALIDATE) {
-        std::vector<int32_t> row((size_t)max_pages);
-        SUN_HIP_CHECK(hipMemcpyAsync(row.data(), page_table, row.size() * 4, hipMemcpyDeviceToHost, st));
-        SUN_HIP_CHECK(hipStreamSynchronize(st));
-        for (long long lp = first_pos / kPageTokens; lp <= last / kPageTokens; ++lp)
-            if (row[lp] < 0 || row[lp] >= pool.lay.n_pages)
-                return fail(SUN_ERR_PAGE_RANGE, "page-table entry %lld = %d outside [0, %lld)", lp, row[lp],
-                            (long long)pool.lay.n_pages);
+        const int rc = guarded([&]() -> int {
+            std::vector<int32_t> row((size_t)max_pages);
+            SUN_HIP_CHECK(hipMemcpyAsync(row.data(), page_table, row.size() * 4, hipMemcpyDeviceToHost, st));
+            SUN_HIP_CHECK(hipStreamSynchronize(st));
+            for (long long lp = first_pos / kPageTokens; lp <= last / kPageTokens; ++lp)
+                if (row[lp] < 0 || row[lp] >= pool.lay.n_pages)
+                    return fail(SUN_ERR_PAGE_RANGE, "page-table entry %lld = %d outside [0, %lld)", lp, row[lp],
+                                (long long)pool.lay.n_pages);
+            return SUN_OK;
+        });
+        if (rc != SUN_OK) return rc;
     }
     SUN_HIP_CHECK(launch_kv_ingest(pool, k_src, v_src, n_tokens, first_pos, page_table, st));
     pool.ingested[model_id] += n_tokens;
@@ -633,7 +663,9 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
         return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, step needs %zu", workspace_bytes, ws.bytes);
     hipStream_t st = (hipStream_t)stream;
     if (flags & SUN_VALIDATE)
-        if (int rc = validate_device_arrays(pool, batch, token_ids, page_tables, max_pages, seq_lens, model_ids, 1, st))
+        if (int rc = guarded([&] {
+                return validate_device_arrays(pool, batch, token_ids, page_tables, max_pages, seq_lens, model_ids, 1, st);
+            }))
             return rc;
     const bool prof = flags & SUN_PROFILE;
     const bool bf = c.act_dtype == SUN_BF16;
@@ -782,26 +814,30 @@ int sun_decode_run(sun_kv_pool* pool_, const sun_weights* weights_, int batch, i
     if (n_steps < 1) return fail(SUN_ERR_SHAPE, "n_steps must be >= 1");
     const Weights& W = *(const Weights*)weights_;
     if (flags & SUN_VALIDATE) {
-        const KvPool& pool = *(const KvPool*)pool_;
-        if (!token_ids || !page_tables || !seq_lens || !model_ids) return fail(SUN_ERR_NULL, "a required device pointer is NULL");
-        if (batch < 1 || batch > kMaxBatchTile || max_pages < 1) return fail(SUN_ERR_SHAPE, "bad batch or max_pages");
-        hipStream_t st = (hipStream_t)stream;
-        std::vector<int32_t> fp((size_t)n_free), tabs((size_t)batch * max_pages);
-        int32_t head = 0;
-        if (n_free) SUN_HIP_CHECK(hipMemcpyAsync(fp.data(), free_pages, fp.size() * 4, hipMemcpyDeviceToHost, st));
-        SUN_HIP_CHECK(hipMemcpyAsync(tabs.data(), page_tables, tabs.size() * 4, hipMemcpyDeviceToHost, st));
-        SUN_HIP_CHECK(hipMemcpyAsync(&head, free_head, 4, hipMemcpyDeviceToHost, st));
-        SUN_HIP_CHECK(hipStreamSynchronize(st));
-        if (head < 0 || head > n_free) return fail(SUN_ERR_PAGE_RANGE, "free_head %d outside [0, %d]", head, n_free);
-        std::vector<char> used((size_t)pool.lay.n_pages, 0);
-        for (int32_t pg : tabs)
-            if (pg >= 0 && pg < pool.lay.n_pages) used[pg] = 1;
-        for (int i = head; i < n_free; ++i) {
-            const int32_t pg = fp[i];
-            if (pg < 0 || pg >= pool.lay.n_pages) return fail(SUN_ERR_PAGE_RANGE, "free_pages[%d] = %d outside the pool", i, pg);
-            if (used[pg]) return fail(SUN_ERR_PAGE_RANGE, "free_pages[%d] = %d is referenced by a page table or listed twice", i, pg);
-            used[pg] = 1;
-        }
+        const int vrc = guarded([&]() -> int {
+            const KvPool& pool = *(const KvPool*)pool_;
+            if (!token_ids || !page_tables || !seq_lens || !model_ids) return fail(SUN_ERR_NULL, "a required device pointer is NULL");
+            if (batch < 1 || batch > kMaxBatchTile || max_pages < 1) return fail(SUN_ERR_SHAPE, "bad batch or max_pages");
+            hipStream_t st = (hipStream_t)stream;
+            std::vector<int32_t> fp((size_t)n_free), tabs((size_t)batch * max_pages);
+            int32_t head = 0;
+            if (n_free) SUN_HIP_CHECK(hipMemcpyAsync(fp.data(), free_pages, fp.size() * 4, hipMemcpyDeviceToHost, st));
+            SUN_HIP_CHECK(hipMemcpyAsync(tabs.data(), page_tables, tabs.size() * 4, hipMemcpyDeviceToHost, st));
+            SUN_HIP_CHECK(hipMemcpyAsync(&head, free_head, 4, hipMemcpyDeviceToHost, st));
+            SUN_HIP_CHECK(hipStreamSynchronize(st));
+            if (head < 0 || head > n_free) return fail(SUN_ERR_PAGE_RANGE, "free_head %d outside [0, %d]", head, n_free);
+            std::vector<char> used((size_t)pool.lay.n_pages, 0);
+            for (int32_t pg : tabs)
+                if (pg >= 0 && pg < pool.lay.n_pages) used[pg] = 1;
+            for (int i = head; i < n_free; ++i) {
+                const int32_t pg = fp[i];
+                if (pg < 0 || pg >= pool.lay.n_pages) return fail(SUN_ERR_PAGE_RANGE, "free_pages[%d] = %d outside the pool", i, pg);
+                if (used[pg]) return fail(SUN_ERR_PAGE_RANGE, "free_pages[%d] = %d is referenced by a page table or listed twice", i, pg);
+                used[pg] = 1;
+            }
+            return SUN_OK;
+        });
+        if (vrc != SUN_OK) return vrc;
     }
     for (int s = 0; s < n_steps; ++s) {
         const bool last = s + 1 == n_steps;
@@ -909,7 +945,7 @@ int sun_decode_serve(sun_kv_pool* pool_, const sun_weights* weights_, int slots,
     hipStream_t st = (hipStream_t)stream;
     const bool reset = flags & SUN_SERVE_RESET;
     if (flags & SUN_VALIDATE)
-        if (int rc = validate_serve(pool, s, slots, max_pages, reset, st)) return rc;
+        if (int rc = guarded([&] { return validate_serve(pool, s, slots, max_pages, reset, st); })) return rc;
     int32_t* next = (int32_t*)((char*)workspace + step_bytes);
     ServeArgs a{s.token_ids, s.page_tables, s.seq_lens, s.model_ids, s.slot_req, s.slot_left, s.w_req, s.w_token,
                 s.w_tables, s.w_lens, s.w_model, s.w_budget, s.ring, s.counters, s.n_wait, s.ring_cap, s.idle_page,
@@ -981,17 +1017,21 @@ int sun_prefill(sun_kv_pool* pool_, const sun_weights* weights_, int n_tokens, c
         return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, prefill needs %zu", workspace_bytes, step_bytes + ex.bytes);
     hipStream_t st = (hipStream_t)stream;
     if (flags & SUN_VALIDATE) {
-        std::vector<int32_t> row((size_t)max_pages), tok((size_t)n_tokens);
-        SUN_HIP_CHECK(hipMemcpyAsync(row.data(), page_table, row.size() * 4, hipMemcpyDeviceToHost, st));
-        SUN_HIP_CHECK(hipMemcpyAsync(tok.data(), token_ids, tok.size() * 4, hipMemcpyDeviceToHost, st));
-        SUN_HIP_CHECK(hipStreamSynchronize(st));
-        for (long long lp = 0; lp <= last / kPageTokens; ++lp)
-            if (row[lp] < 0 || row[lp] >= pool.lay.n_pages)
-                return fail(SUN_ERR_PAGE_RANGE, "page-table entry %lld = %d outside [0, %lld)", lp, row[lp],
-                            (long long)pool.lay.n_pages);
-        for (int i = 0; i < n_tokens; ++i)
-            if (tok[i] < 0 || tok[i] >= c.vocab)
-                return fail(SUN_ERR_TOKEN, "prompt token %d: id %d outside [0, %d)", i, tok[i], c.vocab);
+        const int vrc = guarded([&]() -> int {
+            std::vector<int32_t> row((size_t)max_pages), tok((size_t)n_tokens);
+            SUN_HIP_CHECK(hipMemcpyAsync(row.data(), page_table, row.size() * 4, hipMemcpyDeviceToHost, st));
+            SUN_HIP_CHECK(hipMemcpyAsync(tok.data(), token_ids, tok.size() * 4, hipMemcpyDeviceToHost, st));
+            SUN_HIP_CHECK(hipStreamSynchronize(st));
+            for (long long lp = 0; lp <= last / kPageTokens; ++lp)
+                if (row[lp] < 0 || row[lp] >= pool.lay.n_pages)
+                    return fail(SUN_ERR_PAGE_RANGE, "page-table entry %lld = %d outside [0, %lld)", lp, row[lp],
+                                (long long)pool.lay.n_pages);
+            for (int i = 0; i < n_tokens; ++i)
+                if (tok[i] < 0 || tok[i] >= c.vocab)
+                    return fail(SUN_ERR_TOKEN, "prompt token %d: id %d outside [0, %d)", i, tok[i], c.vocab);
+            return SUN_OK;
+        });
+        if (vrc != SUN_OK) return vrc;
     }
     // Row r of a block is the decode step of position first + r over the one page table: its
     // attention spans positions 0..first + r, and the K/V of all rows of the block are in the
