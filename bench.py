@@ -31,6 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # summaries with the commands are under profiles/.  Workloads that were not counted report null.
 MEASURED_TRAFFIC_BYTES = {
     "cfg2": (298542.9 / 0.5 + 14060.5 / 1.0) * 1024.0,
+    "cfg3": (960163.0 / 0.5 + 49223.1 / 1.0) * 1024.0,
 }
 
 

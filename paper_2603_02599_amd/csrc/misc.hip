@@ -603,34 +603,56 @@ hipError_t launch_advance(const int32_t* next, int batch, int max_pages, const i
 }
 
 // ---------------- continuous batching: retire, advance, admit between two steps ----------------
-// One workgroup of 256 threads, thread t owns row t.  All orders are row order (exclusive scans), so the
-// result does not depend on scheduling.  The phases follow the declaration of sun_decode_serve.
+// One workgroup of 1024 threads; thread t < slots owns row t, and all 16 waves share the walks over page-table
+// rows (a wave per row, 64 columns per load), so that no thread walks a row alone.  All orders are row order
+// (exclusive scans) and column order (ballots), so the result does not depend on scheduling.  The phases
+// follow the declaration of sun_decode_serve.
+constexpr int kServeThreads = 1024;
+constexpr int kServeWaves = kServeThreads / 64;
+
+// exclusive prefix sum over the workgroup in thread order; total = the sum over all threads
 __device__ __forceinline__ int block_scan_excl(int v, int* sc, int& total) {
-    const int t = threadIdx.x;
-    __syncthreads();  // sc may still be read from the previous scan
-    sc[t] = v;
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
-        const int u = t >= o ? sc[t - o] : 0;
-        __syncthreads();
-        sc[t] += u;
-        __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int u = __shfl_up(inc, o);
+        if (lane >= o) inc += u;
     }
-    total = sc[255];
-    return sc[t] - v;
+    __syncthreads();  // sc may still be read from the previous scan
+    if (lane == 63) sc[w] = inc;
+    __syncthreads();
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kServeWaves; ++i) {
+        const int part = sc[i];
+        before += i < w ? part : 0;
+        tot += part;
+    }
+    total = tot;
+    return before + inc - v;
 }
 
-__device__ __forceinline__ int pages_held(const int32_t* row, int max_pages) {
+// pages (entries >= 0) in one table row, counted by a whole wave; the same value in every lane
+__device__ __forceinline__ int wave_count_row(const int32_t* row, int max_pages) {
+    const int lane = threadIdx.x & 63;
     int n = 0;
-    for (int c = 0; c < max_pages; ++c) n += row[c] >= 0;
+    for (int c0 = 0; c0 < max_pages; c0 += 64) {
+        const int c = c0 + lane;
+        const bool have = c < max_pages && row[c] >= 0;
+        n += __popcll(__ballot(have));
+    }
     return n;
 }
 
-__global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* __restrict__ next,
-                                                    int32_t* __restrict__ tokens_out, int32_t* __restrict__ req_out,
-                                                    int do_reset, int do_advance) {
-    __shared__ int sc[256];
-    const int t = threadIdx.x;
+__global__ __launch_bounds__(kServeThreads) void serve_kernel(ServeArgs a, const int32_t* __restrict__ next,
+                                                              int32_t* __restrict__ tokens_out,
+                                                              int32_t* __restrict__ req_out, int do_reset, int do_advance) {
+    __shared__ int sc[kServeWaves];
+    __shared__ int held[256];  // pages per row, later pages per admission candidate
+    __shared__ int roff[256];  // ring offset of a retiring row's first page, else -1
+    __shared__ int act[256];   // what happens to a row's table: -1 nothing, -2 written as idle, q >= 0 copied from waiting q
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const bool row = t < a.slots;
     int whead = a.counters[0], head = a.counters[1], tail = a.counters[2];
     int32_t* tab = a.page_tables + (size_t)(row ? t : 0) * a.max_pages;
@@ -640,6 +662,13 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
         left = a.slot_left[t];
         len = a.seq_lens[t];
     }
+    if (!do_reset)
+        for (int r = wave; r < a.slots; r += kServeWaves) {
+            const int n = wave_count_row(a.page_tables + (size_t)r * a.max_pages, a.max_pages);
+            if (lane == 0) held[r] = n;
+        }
+    __syncthreads();
+    int my_held = (row && !do_reset) ? held[t] : 0;
     bool occ = req >= 0;
     bool clear = row && do_reset;  // rows to be written as idle
     if (do_advance) {
@@ -656,12 +685,23 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
         }
         // retire: pages to the ring's tail, rows in order, columns in order
         int give_total;
-        const int give = (occ && fin) ? pages_held(tab, a.max_pages) : 0;
+        const int give = (occ && fin) ? my_held : 0;
         const int off = block_scan_excl(give, sc, give_total);
+        if (t < 256) roff[t] = (occ && fin) ? off : -1;
+        __syncthreads();
+        for (int r = wave; r < a.slots; r += kServeWaves) {
+            if (roff[r] < 0) continue;  // the same for the whole wave
+            const int32_t* src = a.page_tables + (size_t)r * a.max_pages;
+            int at = tail + roff[r];
+            for (int c0 = 0; c0 < a.max_pages; c0 += 64) {
+                const int c = c0 + lane;
+                const int pg = c < a.max_pages ? src[c] : -1;
+                const unsigned long long m = __ballot(pg >= 0);
+                if (pg >= 0) a.ring[(unsigned)(at + __popcll(m & ((1ull << lane) - 1ull))) % (unsigned)a.ring_cap] = pg;
+                at += __popcll(m);
+            }
+        }
         if (occ && fin) {
-            int j = 0;
-            for (int c = 0; c < a.max_pages; ++c)
-                if (tab[c] >= 0) a.ring[(unsigned)(tail + off + j++) % (unsigned)a.ring_cap] = tab[c];
             retired = 1;
             clear = true;
         }
@@ -679,7 +719,10 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
             } else if (wants && head + rank >= tail) {
                 status |= 1;
             } else {
-                if (wants) tab[col] = a.ring[(unsigned)(head + rank) % (unsigned)a.ring_cap];
+                if (wants) {
+                    tab[col] = a.ring[(unsigned)(head + rank) % (unsigned)a.ring_cap];
+                    my_held += 1;
+                }
                 len = new_len;
             }
             a.token_ids[t] = tok;
@@ -691,7 +734,6 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
     }
     if (do_reset) occ = false;
     if (clear) {
-        for (int c = 0; c < a.max_pages; ++c) tab[c] = c == 0 ? a.idle_page : -1;
         a.token_ids[t] = 0;
         a.seq_lens[t] = 0;
         a.model_ids[t] = 0;
@@ -700,12 +742,17 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
     }
     // admission
     int out_total, idle_total, need_total, ok_total;
-    const int outst = occ ? max(0, (len + left - 1) / kPageTokens + 1 - pages_held(tab, a.max_pages)) : 0;
+    const int outst = occ ? max(0, (len + left - 1) / kPageTokens + 1 - my_held) : 0;
     block_scan_excl(outst, sc, out_total);
     const int avail = (tail - head) - out_total;
     const bool idle = row && !occ;
     const int idle_rank = block_scan_excl(idle ? 1 : 0, sc, idle_total);
     const int ncand = max(0, min(idle_total, a.n_wait - whead));
+    for (int q = wave; q < ncand; q += kServeWaves) {  // the scans above separate this from the last use of held[]
+        const int n = wave_count_row(a.w_tables + (size_t)(whead + q) * a.max_pages, a.max_pages);
+        if (lane == 0) held[q] = n;
+    }
+    __syncthreads();
     auto cut_budget = [&](int q, bool& cut) {
         const int room = a.max_pages * kPageTokens - a.w_lens[q];
         const int b = a.w_budget[q];
@@ -717,23 +764,33 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
         const int q = whead + t;
         bool cut;
         const int b = cut_budget(q, cut);
-        need = max(0, (a.w_lens[q] + b - 1) / kPageTokens + 1 - pages_held(a.w_tables + (size_t)q * a.max_pages, a.max_pages));
+        need = max(0, (a.w_lens[q] + b - 1) / kPageTokens + 1 - held[t]);
     }
     const int before = block_scan_excl(need, sc, need_total);
     // candidate t is admitted if it and all before it fit (needs are >= 0, so the admitted ones are a prefix)
     const int ok = t < ncand && before + need <= avail;
     block_scan_excl(ok, sc, ok_total);
+    int what = clear ? -2 : -1;
     if (idle && idle_rank < ok_total) {
         const int q = whead + idle_rank;
         bool cut;
         const int b = cut_budget(q, cut);
         if (cut) status |= 2;
-        for (int c = 0; c < a.max_pages; ++c) tab[c] = a.w_tables[(size_t)q * a.max_pages + c];
+        what = q;
         a.token_ids[t] = a.w_token[q];
         a.seq_lens[t] = a.w_lens[q];
         a.model_ids[t] = a.w_model[q];
         a.slot_req[t] = a.w_req[q];
         a.slot_left[t] = b;
+    }
+    if (t < 256) act[t] = what;
+    __syncthreads();  // also: every read of the old tables (retirement, tab[col]) is behind us
+    for (int r = wave; r < a.slots; r += kServeWaves) {
+        const int w = act[r];
+        if (w == -1) continue;
+        int32_t* dst = a.page_tables + (size_t)r * a.max_pages;
+        const int32_t* src = w >= 0 ? a.w_tables + (size_t)w * a.max_pages : nullptr;
+        for (int c = lane; c < a.max_pages; c += 64) dst[c] = src ? src[c] : (c == 0 ? a.idle_page : -1);
     }
     int ret_total, gen_total;
     block_scan_excl(retired, sc, ret_total);
@@ -753,7 +810,8 @@ __global__ __launch_bounds__(256) void serve_kernel(ServeArgs a, const int32_t* 
 hipError_t launch_serve(const ServeArgs& a, const int32_t* next, int32_t* tokens_out, int32_t* req_out, bool reset,
                         bool advance, hipStream_t st) {
     if (a.slots < 1 || a.slots > 256) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(serve_kernel, dim3(1), dim3(256), 0, st, a, next, tokens_out, req_out, reset ? 1 : 0, advance ? 1 : 0);
+    hipLaunchKernelGGL(serve_kernel, dim3(1), dim3(kServeThreads), 0, st, a, next, tokens_out, req_out, reset ? 1 : 0,
+                       advance ? 1 : 0);
     return hipGetLastError();
 }
 

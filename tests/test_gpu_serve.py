@@ -21,17 +21,23 @@ def H():
 
 
 class _Setup:
-    def __init__(self, H, shape, dtype, slots, lens, budgets, ring_n, cols, seed, quant=None, n_models=3):
+    def __init__(self, H, shape, dtype, slots, lens, budgets, ring_n, cols, seed, quant=None, n_models=3, extra=None):
+        """extra: {request: column} gives that request one more page of its own at a column past its prompt's."""
         rng = np.random.default_rng(seed)
         lens, budgets = np.asarray(lens, np.int32), np.asarray(budgets, np.int32)
         have = lens // 16 + 1
-        n_pages = 1 + int(have.sum()) + ring_n
+        extra = extra or {}
+        n_pages = 1 + int(have.sum()) + len(extra) + ring_n
         perm = rng.permutation(n_pages).astype(np.int32)
         self.idle, o = int(perm[0]), 1
         tables = np.full((len(lens), cols), -1, np.int32)
         for r in range(len(lens)):
             tables[r, :have[r]] = perm[o:o + have[r]]
             o += int(have[r])
+            if r in extra:
+                assert extra[r] >= have[r]
+                tables[r, extra[r]] = perm[o]
+                o += 1
         self.ring = [int(p) for p in perm[o:]]
         work = wl.make_workload("cfg1", shape=shape, dtype=dtype, batch=slots, n_models=n_models, seed=seed)
         work.page_tables, work.n_pages = np.full((slots, cols), -1, np.int32), n_pages
@@ -181,6 +187,19 @@ def test_serve_many_rows(H):
     _, r, ref = _serve_and_compare(H, S, [7, 6])
     assert ref["admitted"] == 300 and ref["retired"] > 250 and ref["status"] == 0
     assert (r[0] >= 0).all() and (r[-1] < 0).any()
+
+
+def test_serve_wide_tables(H):
+    """Page tables of 140 columns (the bookkeeping walks a row 64 columns at a time): prompts that end in the
+    first, second and third stretch of 64 columns, and two requests that bring a page of their own far past
+    their prompt (columns 70 and 137), which counts as held and goes back to the ring in column order."""
+    H.say("serve: fp32 tiny, 3 rows, 8 requests, 140-column tables")
+    lens = [2100, 1023, 1024, 30, 1500, 2047, 700, 2200]
+    budgets = [10, 20, 5, 30, 17, 3, 12, 25]
+    S = _Setup(H, wl.TINY, "f32", 3, lens, budgets, 4, 140, 550, extra={3: 137, 6: 70})
+    _, _, ref = _serve_and_compare(H, S, [30, 40])
+    assert ref["retired"] == 8 and ref["status"] == 0
+    assert sorted(ref["ring"]) == sorted(set(range(S.n_pages)) - {S.idle})
 
 
 def test_serve_without_retirement_equals_the_run(H):
