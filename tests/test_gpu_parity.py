@@ -134,9 +134,19 @@ _GQA_SHAPES = [wl.Shape(f"gqa{g}_d128", 1, 256, g, 1, 128, 256, 256) for g in (1
                          [(s, "bf16") for s in _GQA_SHAPES], ids=lambda v: v.name if hasattr(v, "name") else v)
 def test_paged_attention_op(H, shape, dtype):
     """Attention sub-step alone against the oracle's paged attention (ragged lengths, shuffled tables)."""
+    _attention_op_case(H, shape, dtype, [1, 2, 16, 17, 33, 255, 256, 257, 511, 513, 1000, 31])
+
+
+@pytest.mark.parametrize("shape,dtype", [(wl.TINY, "f32"), (wl.SMALL128, "bf16")], ids=lambda v: v.name if hasattr(v, "name") else v)
+def test_paged_attention_op_more_requests_than_a_step_takes(H, shape, dtype):
+    """The attention operation alone takes up to 1024 requests (the step: 256): 700 short ragged ones."""
+    rng = np.random.default_rng(90)
+    _attention_op_case(H, shape, dtype, [int(v) for v in rng.integers(1, 120, size=700)])
+
+
+def _attention_op_case(H, shape, dtype, lens):
     from oracle import oracle as orc
-    lens = [1, 2, 16, 17, 33, 255, 256, 257, 511, 513, 1000, 31]
-    H.say(f"paged attention {shape.name} {dtype}")
+    H.say(f"paged attention {shape.name} {dtype}, {len(lens)} requests")
     work = wl.make_workload("cfg1", shape=shape, dtype=dtype, batch=len(lens), seed=80)
     rng = np.random.default_rng(6)
     work.seq_lens = np.array(lens, np.int32) - 1
