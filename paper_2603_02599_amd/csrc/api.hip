@@ -136,7 +136,7 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
         w.hA = take(atile_bytes(ATile{mb}, H));
         w.aA = take(atile_bytes(ATile{mb}, QD));
         w.uA = take(atile_bytes(ATile{mb}, F));
-        w.hs = (float*)take((size_t)(std::max(std::max(H, QD), F) / 128 + 1) * mb * 32 * 4);
+        w.hs = (float*)take((size_t)(std::max(std::max(H, QD), F) / 128 + 1) * mb * 32 * 8);  // scale and integer sum per row and group
         w.part = (float*)take(std::max((size_t)kMaxSplits * batch * std::max(Nqkv, H), (size_t)kMaxSplitsWide * batch * 2 * F) * 4);
     } else {
         w.h32 = (float*)take((size_t)batch * H * 4);
@@ -746,7 +746,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
                 }
                 {
                     ProfScope p(prof, 7, st);
-                    SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, ws.hs, st));
+                    SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, W.quant ? ws.hs : nullptr, st));
                 }
             }
             const int sd = proj_pick_splits(L.down, batch, kMaxSplits);

@@ -514,7 +514,6 @@ struct CombineArgs {
 };
 
 __global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
-    __shared__ float red[2];
     const int b = blockIdx.y, col = blockIdx.x * 128 + threadIdx.x;
     const int h = col / a.D, j = col % a.D;
     const int c0 = a.chunk_off[b], c1 = a.chunk_off[b + 1];
@@ -549,17 +548,33 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
     }
     const float v = num / den;
     if (a.out_f32) a.out_f32[(size_t)b * a.Hq * a.D + col] = v;
-    if (a.out_tiled) {
+    if (a.out_tiled && !a.hsum) {
         uint16_t lo;
         const uint16_t hi = split_bf16(v, lo);
         a.out_tiled[atile_elem(ATile{a.out_mb}, 0, b, col)] = hi;
         a.out_tiled[atile_elem(ATile{a.out_mb}, 1, b, col)] = lo;
-        if (a.hsum) {
-            const float s = wave_sum(bf16_bits_to_f32(hi) + bf16_bits_to_f32(lo));
-            if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-            __syncthreads();
-            if (threadIdx.x == 0) a.hsum[(size_t)blockIdx.x * (a.out_mb * 32) + b] = red[0] + red[1];
-        }
+    }
+    if (a.out_tiled && a.hsum) {
+        // fixed-point tile of the 4-bit O projection: the workgroup's 128 columns are one group
+        __shared__ float red_max[2];
+        __shared__ int red_sum[2];
+        const float wm = wave_max(fabsf(v));
+        if ((threadIdx.x & 63) == 0) red_max[threadIdx.x >> 6] = wm;
+        __syncthreads();
+        const float am = fmaxf(red_max[0], red_max[1]);
+        const int xi = (int)rintf(v * qtile_inv(am));
+        const int l = ((xi + 128) & 255) - 128, hq = (xi - l) >> 8;
+        uint8_t* tile = reinterpret_cast<uint8_t*>(a.out_tiled);
+        tile[qtile_unit(ATile{a.out_mb}, 0, b, col >> 4) * 16 + (col & 15)] = (uint8_t)(hq & 255);
+        tile[qtile_unit(ATile{a.out_mb}, 1, b, col >> 4) * 16 + (col & 15)] = (uint8_t)(l & 255);
+        int sum = xi;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if ((threadIdx.x & 63) == 0) red_sum[threadIdx.x >> 6] = sum;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            reinterpret_cast<float2*>(a.hsum)[(size_t)blockIdx.x * (a.out_mb * 32) + b] =
+                float2{am / kQMax, __int_as_float(red_sum[0] + red_sum[1])};
     }
 }
 

@@ -97,6 +97,39 @@ __device__ __forceinline__ uint16_t split_bf16(float x, uint16_t& lo) {
     return hi;
 }
 
+// ---- 4-bit projections: activations as 16-bit fixed point in two int8 planes ----
+// The 4-bit codes are integers, so the quantised projections run on the int8 matrix cores with exact
+// int32 sums (Eq. 8 evaluated on the integer grid; the scales are applied to the sums in fp32).  Per row
+// and 128-wide group (the weights' group) an activation is x ~ sx * xi with sx = max|x| / kQMax and the
+// integer xi = 256 * hi + lo, hi and lo in [-128, 127]: 16 bits below the group's largest value.  The
+// producer of the activations also stores sx and sum_k xi (for the zero point) per row and group.
+// Tile: 16-byte units of 16 consecutive k of one row and plane, ordered [group][k-step 0..3][plane]
+// [32-row block][lane = half * 32 + row % 32] with k = group * 128 + half * 64 + step * 16 + (0..15):
+// a unit is one lane's operand of a 32x32x32 int8 MFMA.
+constexpr float kQMax = 32639.f;  // 127 * 256 + 127
+__host__ __device__ __forceinline__ size_t qtile_unit(ATile t, int plane, int b, int k16) {
+    const int c = k16 >> 3, g = k16 & 7, half = g >> 2, s = g & 3;
+    return ((size_t)((c * 4 + s) * 2 + plane) * t.MB + (b >> 5)) * 64 + half * 32 + (b & 31);
+}
+// eight consecutive values of one row (k8 = index of the octet) -> their bytes in both planes; returns sum of xi
+__device__ __forceinline__ int qtile_store8(uint8_t* tile, ATile t, int b, int k8, const float (&x)[8], float inv) {
+    uint32_t hi[2] = {0u, 0u}, lo[2] = {0u, 0u};
+    int sum = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int xi = (int)rintf(x[e] * inv);
+        const int l = ((xi + 128) & 255) - 128, h = (xi - l) >> 8;
+        sum += xi;
+        hi[e >> 2] |= (uint32_t)(h & 255) << (8 * (e & 3));
+        lo[e >> 2] |= (uint32_t)(l & 255) << (8 * (e & 3));
+    }
+    *reinterpret_cast<uint2*>(tile + qtile_unit(t, 0, b, k8 >> 1) * 16 + (k8 & 1) * 8) = uint2{hi[0], hi[1]};
+    *reinterpret_cast<uint2*>(tile + qtile_unit(t, 1, b, k8 >> 1) * 16 + (k8 & 1) * 8) = uint2{lo[0], lo[1]};
+    return sum;
+}
+// 1 / sx for a group whose largest magnitude is amax (an all-zero group maps to zeros with sx = 0)
+__device__ __forceinline__ float qtile_inv(float amax) { return amax > 0.f ? kQMax / amax : 0.f; }
+
 // ---- wave reductions (all lanes receive the result; fixed order => deterministic) ----
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -25,6 +25,26 @@ hipError_t launch_embed(const sun_model_cfg& cfg, const void* embed, const int32
     return hipGetLastError();
 }
 
+// Writes eight consecutive values of row b (unit u = k / 8) into the fixed-point tile of a 4-bit projection.
+// The 16 lanes that hold one 128-wide group share its scale (largest magnitude over the group); the first of
+// them stores the scale and the sum of the group's integers.  Every lane of the wave must call it.
+__device__ __forceinline__ void qtile_group16(uint8_t* tile, float2* qscale, ATile t, int b, int u, bool live,
+                                              const float (&y)[8]) {
+    float am = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) am = fmaxf(am, fabsf(y[e]));
+    am = fmaxf(am, __shfl_xor(am, 1));
+    am = fmaxf(am, __shfl_xor(am, 2));
+    am = fmaxf(am, __shfl_xor(am, 4));
+    am = fmaxf(am, __shfl_xor(am, 8));
+    int sum = live ? qtile_store8(tile, t, b, u, y, qtile_inv(am)) : 0;
+    sum += __shfl_xor(sum, 1);
+    sum += __shfl_xor(sum, 2);
+    sum += __shfl_xor(sum, 4);
+    sum += __shfl_xor(sum, 8);
+    if (live && (threadIdx.x & 15) == 0) qscale[(size_t)(u >> 4) * (t.MB * 32) + b] = float2{am / kQMax, __int_as_float(sum)};
+}
+
 // ---------------- residual add + RMSNorm ----------------
 // One block per row.  x += sum_s partial[s] (s ascending), h = x * rsqrt(mean(x^2) + eps) * g.
 struct NormArgs {
@@ -33,7 +53,7 @@ struct NormArgs {
     const void* gain;
     float* h_f32;
     uint16_t* h_tiled;
-    float* hsum;
+    float2* qscale;  // not NULL: h_tiled is the fixed-point tile of a 4-bit projection, and this its scales and sums
     int nparts, ld_rows, H, gain_bf16, mb;
     float eps;
 };
@@ -90,9 +110,9 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(NormArgs a) {
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int u = tid + it * nthreads;
-        float gsum = 0.f;
+        float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (u < nunits) {
-            float g[8], y[8];
+            float g[8];
             if (a.gain_bf16) {
                 const u32x4 gw = *reinterpret_cast<const u32x4*>((const uint16_t*)a.gain + u * 8);
 #pragma unroll
@@ -110,25 +130,19 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(NormArgs a) {
                 *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8) = f32x4{y[0], y[1], y[2], y[3]};
                 *reinterpret_cast<f32x4*>(a.h_f32 + (size_t)b * H + u * 8 + 4) = f32x4{y[4], y[5], y[6], y[7]};
             }
-            if (a.h_tiled) {
+            if (a.h_tiled && !a.qscale) {
                 u32x4 o, ol;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
                     ol[e] = pack_bf16(y[2 * e] - bf16_lo(o[e]), y[2 * e + 1] - bf16_hi(o[e]));
-                    gsum += (bf16_lo(o[e]) + bf16_lo(ol[e])) + (bf16_hi(o[e]) + bf16_hi(ol[e]));
                 }
                 reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, 0, b, u)] = o;
                 reinterpret_cast<u32x4*>(a.h_tiled)[atile_unit(ATile{a.mb}, 1, b, u)] = ol;
             }
         }
-        if (a.hsum) {  // 16 consecutive units (lanes) form one 128-wide group
-            gsum += __shfl_xor(gsum, 1);
-            gsum += __shfl_xor(gsum, 2);
-            gsum += __shfl_xor(gsum, 4);
-            gsum += __shfl_xor(gsum, 8);
-            if (u < nunits && (tid & 15) == 0) a.hsum[(size_t)(u >> 4) * (a.mb * 32) + b] = gsum;
-        }
+        if (a.qscale)  // fixed-point tile of a 4-bit projection: 16 consecutive units (lanes) form one 128-wide group
+            qtile_group16((uint8_t*)a.h_tiled, a.qscale, ATile{a.mb}, b, u, u < nunits, y);
     }
 }
 
@@ -140,7 +154,7 @@ hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float*
     a.gain = gain;
     a.h_f32 = h_f32;
     a.h_tiled = (uint16_t*)h_tiled;
-    a.hsum = hsum;
+    a.qscale = (float2*)hsum;
     a.nparts = nparts;
     a.ld_rows = ld_rows;
     a.H = cfg.hidden;
@@ -327,13 +341,13 @@ hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipS
 
 // ---------------- SwiGLU over the gate/up projection's partial sums ----------------
 // part: [nparts][ld_rows][2*ffn] fp32 with the projection's column order (blocks of 16 gate
-// columns followed by their 16 up columns).  Writes u = silu(sum g) * (sum u) as two-plane tiled
-// bf16 [rows, ffn] and, if asked, the per-128 group sums the 4-bit projection needs.
+// columns followed by their 16 up columns).  Writes u = silu(sum g) * (sum u) [rows, ffn] as the down
+// projection's input: two-plane tiled bf16, or (hsum given) the fixed-point tile of a 4-bit projection.
 __global__ __launch_bounds__(256) void swiglu_tile_kernel(const float* __restrict__ part, int nparts, int ld_rows,
                                                           int ffn, int mb, u32x4* __restrict__ tiled,
                                                           float* __restrict__ hsum) {
     const int b = blockIdx.y, u = blockIdx.x * 256 + threadIdx.x;  // unit = 8 consecutive u columns
-    float gsum = 0.f;
+    float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (u < ffn / 8) {
         const int j = u * 8;
         const float* p = part + (size_t)b * 2 * ffn + (j >> 4) * 32 + (j & 15);
@@ -345,29 +359,23 @@ __global__ __launch_bounds__(256) void swiglu_tile_kernel(const float* __restric
             u0 += *reinterpret_cast<const f32x4*>(p + s * slab + 16);
             u1 += *reinterpret_cast<const f32x4*>(p + s * slab + 20);
         }
-        float y[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             y[e] = g0[e] / (1.f + __expf(-g0[e])) * u0[e];
             y[4 + e] = g1[e] / (1.f + __expf(-g1[e])) * u1[e];
         }
-        u32x4 o, ol;
+        if (!hsum) {
+            u32x4 o, ol;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
-            ol[e] = pack_bf16(y[2 * e] - bf16_lo(o[e]), y[2 * e + 1] - bf16_hi(o[e]));
-            gsum += (bf16_lo(o[e]) + bf16_lo(ol[e])) + (bf16_hi(o[e]) + bf16_hi(ol[e]));
+            for (int e = 0; e < 4; ++e) {
+                o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
+                ol[e] = pack_bf16(y[2 * e] - bf16_lo(o[e]), y[2 * e + 1] - bf16_hi(o[e]));
+            }
+            tiled[atile_unit(ATile{mb}, 0, b, u)] = o;
+            tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
         }
-        tiled[atile_unit(ATile{mb}, 0, b, u)] = o;
-        tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
     }
-    if (hsum) {
-        gsum += __shfl_xor(gsum, 1);
-        gsum += __shfl_xor(gsum, 2);
-        gsum += __shfl_xor(gsum, 4);
-        gsum += __shfl_xor(gsum, 8);
-        if (u < ffn / 8 && (threadIdx.x & 15) == 0) hsum[(size_t)(u >> 4) * (mb * 32) + b] = gsum;
-    }
+    if (hsum) qtile_group16((uint8_t*)tiled, (float2*)hsum, ATile{mb}, b, u, u < ffn / 8, y);
 }
 
 hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,
@@ -820,26 +828,23 @@ __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict_
                                                         u32x4* __restrict__ tiled, float* __restrict__ hsum) {
     const int b = blockIdx.y;
     const int u = blockIdx.x * 256 + threadIdx.x;
-    float gsum = 0.f;
+    float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (u < K / 8) {
         const float* p = x + (size_t)b * K + u * 8;
-        u32x4 o, ol;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            o[e] = pack_bf16(p[2 * e], p[2 * e + 1]);
-            ol[e] = pack_bf16(p[2 * e] - bf16_lo(o[e]), p[2 * e + 1] - bf16_hi(o[e]));
-            gsum += (bf16_lo(o[e]) + bf16_lo(ol[e])) + (bf16_hi(o[e]) + bf16_hi(ol[e]));
+        for (int e = 0; e < 8; ++e) y[e] = p[e];
+        if (!hsum) {
+            u32x4 o, ol;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
+                ol[e] = pack_bf16(y[2 * e] - bf16_lo(o[e]), y[2 * e + 1] - bf16_hi(o[e]));
+            }
+            tiled[atile_unit(ATile{mb}, 0, b, u)] = o;
+            tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
         }
-        tiled[atile_unit(ATile{mb}, 0, b, u)] = o;
-        tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
     }
-    if (hsum) {
-        gsum += __shfl_xor(gsum, 1);
-        gsum += __shfl_xor(gsum, 2);
-        gsum += __shfl_xor(gsum, 4);
-        gsum += __shfl_xor(gsum, 8);
-        if (u < K / 8 && (threadIdx.x & 15) == 0) hsum[(size_t)(u >> 4) * (mb * 32) + b] = gsum;
-    }
+    if (hsum) qtile_group16((uint8_t*)tiled, (float2*)hsum, ATile{mb}, b, u, u < K / 8, y);
 }
 
 hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st) {

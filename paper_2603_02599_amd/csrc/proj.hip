@@ -9,12 +9,14 @@
 // pre-tiled by their producer, staged through LDS (double buffered) and shared by the
 // waves of a workgroup; wave w owns 32 output columns and all batch rows.
 //
-// W4 path: codes are widened in registers to the bf16 value 128+q (a shift and an
-// and-or per pair), fed to the MFMA per 128-wide group, and the group's partial sum is
-// corrected and scaled in fp32:  acc += S * (sum_k (128+q_k) x_k - (128+Z) * sum_k x_k),
-// which equals sum_k (q_k - Z) S x_k up to fp32 rounding; the integer grid is never
-// rounded.  sum_k x_k per group comes from the activation producer.
+// W4 path (proj_w4_kernel): the codes stay integers.  Activations arrive as 16-bit fixed point in two
+// int8 planes with one scale per row and group (see common.hpp), the 4-bit codes are widened to bytes
+// (an and, a shift-and per four codes) and both go through the 32x32x32 int8 MFMA, whose int32 sums
+// are exact.  Per 128-wide group:  acc += (S * sx) * (256 * sum_k q_k hi_k + sum_k q_k lo_k - Z * sum_k xi_k),
+// which is sum_k (q_k - Z) S (sx xi_k) up to the rounding of one int -> fp32 conversion and one fma.
 #include <hip/hip_fp16.h>
+
+#include <type_traits>
 
 #include "kernels.hpp"
 
@@ -277,6 +279,177 @@ void proj_kernel(ProjArgs a) {
     }
 }
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+// 4-bit weights: MR 32-row blocks per workgroup (all rows up to 64; 64-row tiles above), one stage =
+// one 128-wide group = four int8 MFMA k-steps, three stages of activations in the LDS ring.
+template <int MR, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void proj_w4_kernel(ProjArgs a) {
+    constexpr int STEPS = 4;
+    constexpr int STAGE_UNITS = STEPS * 2 * MR * 64;  // 16-byte units of activations per stage (two planes)
+    constexpr int NT = NW * 64;
+    constexpr int UPT = (STAGE_UNITS + NT - 1) / NT;
+    __shared__ u32x4 lds[3][STAGE_UNITS];
+    __shared__ __attribute__((aligned(16))) float sx_lds[4][MR * 32];  // ring over groups: scale of each row ...
+    __shared__ __attribute__((aligned(16))) int xs_lds[4][MR * 32];    // ... and its sum of integers
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5;
+    const int nb = blockIdx.x * NW + wave;
+    const bool active = nb < a.N / 32;
+    const int split = blockIdx.y;
+    const int mb_off = blockIdx.z * MR;
+    const int s0 = split * a.stages_per_split;
+    const int s1 = min(a.n_stages, s0 + a.stages_per_split);
+    const int kch = a.K / 128;
+
+    // waves past the last column block work on block 0 and drop their result (keeps the loop branch-free)
+    const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * 2 * 64 + lane;
+    const uint32_t* SZl = a.SZ + ((size_t)(active ? nb : 0) * (a.s_only ? (kch + 1) >> 1 : kch)) * 32 + (lane & 31);
+    const float2* QS = reinterpret_cast<const float2*>(a.hsum);
+
+    f32x16 acc[MR];
+    i32x16 ih[MR], il[MR];
+#pragma unroll
+    for (int m = 0; m < MR; ++m)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+
+    u32x4 w0[2], w1[2], w2[2], areg[UPT];
+    uint32_t sz0 = 0, sz1 = 0, sz2 = 0;
+    float2 qreg = float2{0.f, 0.f};
+
+    auto load_w = [&](u32x4(&w)[2], uint32_t& sz, int st) {
+        w[0] = Wl[((size_t)st * 2) * 64];
+        w[1] = Wl[((size_t)st * 2 + 1) * 64];
+        sz = SZl[(size_t)(a.s_only ? st >> 1 : st) * 32];
+    };
+    auto load_a = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            const int u = min(i * NT + tid, STAGE_UNITS - 1);  // past the stage: re-read its last unit, never stored
+            const int sp = u / (MR * 64), rem = u % (MR * 64);  // sp = step * 2 + plane
+            areg[i] = a.A[((size_t)(st * 8 + sp) * a.mb_rows + mb_off + (rem >> 6)) * 64 + (rem & 63)];
+        }
+        if (tid < MR * 32) qreg = QS[(size_t)st * (a.mb_rows * 32) + mb_off * 32 + tid];
+    };
+    auto store_a = [&](int buf, int st) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i)
+            if (STAGE_UNITS % NT == 0 || i * NT + tid < STAGE_UNITS) lds[buf][i * NT + tid] = areg[i];
+        if (tid < MR * 32) {
+            sx_lds[st & 3][tid] = qreg.x;
+            xs_lds[st & 3][tid] = __float_as_int(qreg.y);
+        }
+    };
+    auto compute = [&](int buf, const u32x4(&w)[2], uint32_t sz, int st) {
+        u32x4 afr[2][2 * MR];  // operands of one k-step (both planes), read one step ahead
+#pragma unroll
+        for (int i = 0; i < 2 * MR; ++i) afr[0][i] = lds[buf][i * 64 + lane];
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            if (s + 1 < STEPS) {
+#pragma unroll
+                for (int i = 0; i < 2 * MR; ++i) afr[(s + 1) & 1][i] = lds[buf][((s + 1) * 2 * MR + i) * 64 + lane];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const uint32_t wa = w[s >> 1][(s & 1) * 2], wb = w[s >> 1][(s & 1) * 2 + 1];
+            const i32x4 bfrag = {(int)(wa & 0x0F0F0F0Fu), (int)((wa >> 4) & 0x0F0F0F0Fu), (int)(wb & 0x0F0F0F0Fu),
+                                 (int)((wb >> 4) & 0x0F0F0F0Fu)};
+#pragma unroll
+            for (int m = 0; m < MR; ++m) {
+                const i32x4 ah = __builtin_bit_cast(i32x4, afr[s & 1][m]), al = __builtin_bit_cast(i32x4, afr[s & 1][MR + m]);
+                if (s == 0) {
+                    i32x16 zero;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) zero[r] = 0;
+                    ih[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bfrag, zero, 0, 0, 0);
+                    il[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bfrag, zero, 0, 0, 0);
+                } else {
+                    ih[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bfrag, ih[m], 0, 0, 0);
+                    il[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bfrag, il[m], 0, 0, 0);
+                }
+            }
+        }
+        // scale-only layout: pick this group's half of the dword; the zero point is 8 everywhere
+        const uint32_t szg = a.s_only ? (((sz >> (16 * (st & 1))) & 0xffffu) | 0x48000000u) : sz;
+        const __half2 h2 = __builtin_bit_cast(__half2, szg);
+        const float sc = __low2float(h2);
+        const int zi = (int)__high2float(h2);  // zero points are integer codes (Appendix A.1)
+        const float* sxp = sx_lds[st & 3];
+        const int* xsp = xs_lds[st & 3];
+#pragma unroll
+        for (int m = 0; m < MR; ++m)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const f32x4 sx4 = *reinterpret_cast<const f32x4*>(sxp + m * 32 + 8 * rr + 4 * half);
+                const i32x4 xs4 = *reinterpret_cast<const i32x4*>(xsp + m * 32 + 8 * rr + 4 * half);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int e = rr * 4 + q;
+                    const int tot = (ih[m][e] << 8) + il[m][e] - __mul24(zi, xs4[q]);
+                    acc[m][e] = fmaf((float)tot, sc * sx4[q], acc[m][e]);
+                }
+            }
+    };
+
+    // Steady state without branches around the loads, so that the requests of the following stages stay in
+    // flight while this stage is computed; past the end the last stage is re-read and never used.
+    if (s0 < s1) {
+        auto phase = [&](const u32x4(&wc)[2], uint32_t szc, u32x4(&wn)[2], uint32_t& szn, int bufc, int bufn, int st) {
+            const int nx = min(st + 2, s1 - 1);
+            load_a(nx);  // before the weights: the LDS store below then waits for these only
+            load_w(wn, szn, nx);
+            compute(bufc, wc, szc, st);
+            store_a(bufn, nx);
+            __syncthreads();
+        };
+        const int sA = min(s0 + 1, s1 - 1);
+        load_w(w0, sz0, s0);
+        load_a(s0);
+        store_a(0, s0);
+        load_w(w1, sz1, sA);
+        load_a(sA);
+        store_a(1, sA);
+        __syncthreads();
+        for (int st = s0; st < s1; st += 3) {
+            phase(w0, sz0, w2, sz2, 0, 2, st);
+            if (st + 1 >= s1) break;
+            phase(w1, sz1, w0, sz0, 1, 0, st + 1);
+            if (st + 2 >= s1) break;
+            phase(w2, sz2, w1, sz1, 2, 1, st + 2);
+        }
+    }
+    if (!active) return;
+    const int col = lane & 31;
+    float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
+#pragma unroll
+    for (int m = 0; m < MR; ++m)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int b = (mb_off + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (b < a.rows) o[(size_t)b * a.ldo] = acc[m][r];
+        }
+}
+
+template <int MR>
+static hipError_t launch_proj_w4(const ProjArgs& a, int nw, int splits, int mtiles, hipStream_t st) {
+    const auto go = [&](auto nwc) {
+        constexpr int NW = decltype(nwc)::value;
+        dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
+        hipLaunchKernelGGL((proj_w4_kernel<MR, NW>), grid, block, 0, st, a);
+        return hipGetLastError();
+    };
+    switch (nw) {
+    case 4: return go(std::integral_constant<int, 4>{});
+    case 5: return go(std::integral_constant<int, 5>{});
+    case 6: return go(std::integral_constant<int, 6>{});
+    case 7: return go(std::integral_constant<int, 7>{});
+    }
+    return hipErrorInvalidValue;
+}
+
 template <int MB, int KS, bool W4, int NW = 4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
     constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
@@ -406,10 +579,12 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
         a.n_stages = kch;
         a.stages_per_split = cps;
         const int nw = proj_pick_waves(W, p.rows, splits);
-        if (t.mb == 2) return w4 ? launch_proj_nw<2, 128, true>(a, nw, p.epilogue, splits, t.mtiles, st)
-                                 : launch_proj_nw<2, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
-        return w4 ? launch_proj_nw<4, 128, true>(a, nw, p.epilogue, splits, t.mtiles, st)
-                  : launch_proj_nw<4, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
+        if (w4) {
+            if (p.epilogue != EPI_STORE) return hipErrorInvalidValue;
+            return t.mb == 2 ? launch_proj_w4<1>(a, nw, splits, t.mtiles, st) : launch_proj_w4<2>(a, nw, splits, t.mtiles, st);
+        }
+        if (t.mb == 2) return launch_proj_nw<2, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
+        return launch_proj_nw<4, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
     }
     a.n_stages = kch * 2;
     a.stages_per_split = cps * 2;
@@ -554,13 +729,11 @@ __global__ __launch_bounds__(256) void pack_w4_kernel(PackSrc s, uint32_t* __res
     int src, row;
     pack_row(s, pn, src, row);
     const uint32_t word = *reinterpret_cast<const uint32_t*>((const uint8_t*)s.p[src] + ((size_t)row * s.K + k) / 2);
-    // logical: code e at bits [4e, 4e+4).  packed: e = 2p at bits [4p..], e = 2p+1 at bits [16+4p..]
+    // logical: code e at bits [4e, 4e+4).  packed: the low nibbles of the four bytes hold e = 0..3, the
+    // high nibbles e = 4..7, so that "and 0x0F0F0F0F" and "shift by 4, and" give the codes as bytes in order
     uint32_t o = 0;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        o |= ((word >> (8 * p)) & 15u) << (4 * p);
-        o |= ((word >> (8 * p + 4)) & 15u) << (16 + 4 * p);
-    }
+    for (int e = 0; e < 8; ++e) o |= ((word >> (4 * e)) & 15u) << (e < 4 ? 8 * e : 8 * (e - 4) + 4);
     dst[u] = o;
     if (kk == 0 && half == 0) {
         const size_t g = (size_t)row * kch + c;
