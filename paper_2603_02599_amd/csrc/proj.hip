@@ -376,7 +376,7 @@ void proj_w4_kernel(ProjArgs a) {
         const uint32_t szg = a.s_only ? (((sz >> (16 * (st & 1))) & 0xffffu) | 0x48000000u) : sz;
         const __half2 h2 = __builtin_bit_cast(__half2, szg);
         const float sc = __low2float(h2);
-        const int zi = (int)__high2float(h2);  // zero points are integer codes (Appendix A.1)
+        const int nzi = -(int)__high2float(h2);  // zero points are integer codes (Appendix A.1)
         const float* sxp = sx_lds[st & 3];
         const int* xsp = xs_lds[st & 3];
 #pragma unroll
@@ -388,7 +388,8 @@ void proj_w4_kernel(ProjArgs a) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int e = rr * 4 + q;
-                    const int tot = (ih[m][e] << 8) + il[m][e] - __mul24(zi, xs4[q]);
+                    int tot = (ih[m][e] << 8) + il[m][e];
+                    asm("v_mad_i32_i24 %0, %1, %2, %0" : "+v"(tot) : "v"(nzi), "v"(xs4[q]));  // tot -= Z * sum xi, one instruction
                     acc[m][e] = fmaf((float)tot, sc * sx4[q], acc[m][e]);
                 }
             }
