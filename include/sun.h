@@ -63,8 +63,12 @@ enum {
  * Decoder shape (pre-norm Llama-style block: RMSNorm, GQA attention with rotary
  * embedding in half-split pairing, SwiGLU, untied lm_head).  act_dtype selects the
  * arithmetic: SUN_F32 = fp32 weights and activations on the vector ALUs (parity
- * configuration), SUN_BF16 = bf16 weights, activations as two bf16 planes (value + remainder) into the matrix cores, fp32
- * accumulators / residual stream / softmax.  The KV pool is bf16 in both.
+ * configuration), SUN_BF16 = bf16 weights, activations as two bf16 planes (value +
+ * remainder) into the matrix cores, fp32 accumulators / residual stream / softmax;
+ * with 4-bit weights (sun_qweights_create) the projections run on the int8 matrix
+ * cores instead: the codes as integers, the activations as 16-bit fixed point with
+ * one scale per row and 128-wide group, exact int32 sums per group, scales applied
+ * in fp32.  The KV pool is bf16 in all of them.
  * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with ratio
  * <= 8; SUN_BF16 additionally needs hidden, ffn and n_q_heads*head_dim multiples
  * of 128 and vocab a multiple of 32.

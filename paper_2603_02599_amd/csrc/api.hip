@@ -104,7 +104,7 @@ struct Workspace {
     float* x;
     void *hA, *aA, *uA;         // bf16 tiled activations
     float *h32, *a32, *u32, *gu32, *qkv32, *o32;  // fp32 path
-    float* hs;
+    float* qs;           // 4-bit path: (scale, integer sum) of every row and 128-wide group of the current activations
     float* part;
     float* q;
     float* table;
@@ -136,7 +136,7 @@ static Workspace carve(const sun_model_cfg& c, int batch, int max_pages, char* b
         w.hA = take(atile_bytes(ATile{mb}, H));
         w.aA = take(atile_bytes(ATile{mb}, QD));
         w.uA = take(atile_bytes(ATile{mb}, F));
-        w.hs = (float*)take((size_t)(std::max(std::max(H, QD), F) / 128 + 1) * mb * 32 * 8);  // scale and integer sum per row and group
+        w.qs = (float*)take((size_t)(std::max(std::max(H, QD), F) / 128 + 1) * mb * 32 * 8);  // scale and integer sum per row and group
         w.part = (float*)take(std::max((size_t)kMaxSplits * batch * std::max(Nqkv, H), (size_t)kMaxSplitsWide * batch * 2 * F) * 4);
     } else {
         w.h32 = (float*)take((size_t)batch * H * 4);
@@ -687,12 +687,12 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
             {
                 ProfScope p(prof, 7, st);
                 SUN_HIP_CHECK(launch_residual_norm(c, ws.x, ws.part, down_parts, batch, L.g1, batch, nullptr, ws.hA,
-                                                   W.quant ? ws.hs : nullptr, st));
+                                                   W.quant ? ws.qs : nullptr, st));
             }
             const int sq = proj_pick_splits(L.qkv, batch, kMaxSplits);
             {
                 ProfScope p(prof, 2, st);
-                ProjLaunch pl{&L.qkv, ws.hA, ws.hs, batch, EPI_STORE, sq, ws.part, L.qkv.N, batch};
+                ProjLaunch pl{&L.qkv, ws.hA, ws.qs, batch, EPI_STORE, sq, ws.part, L.qkv.N, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             {
@@ -716,19 +716,19 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
         {
             ProfScope p(prof, 1, st);
             SUN_HIP_CHECK(launch_attn_combine(c, ws.plan, batch, bf ? nullptr : ws.a32, bf ? ws.aA : nullptr,
-                                              (bf && W.quant) ? ws.hs : nullptr, st));
+                                              (bf && W.quant) ? ws.qs : nullptr, st));
         }
         if (bf) {
             const int so = proj_pick_splits(L.o, batch, kMaxSplits);
             {
                 ProfScope p(prof, 3, st);
-                ProjLaunch pl{&L.o, ws.aA, ws.hs, batch, EPI_STORE, so, ws.part, H, batch};
+                ProjLaunch pl{&L.o, ws.aA, ws.qs, batch, EPI_STORE, so, ws.part, H, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             {
                 ProfScope p(prof, 7, st);
                 SUN_HIP_CHECK(launch_residual_norm(c, ws.x, ws.part, so, batch, L.g2, batch, nullptr, ws.hA,
-                                                   W.quant ? ws.hs : nullptr, st));
+                                                   W.quant ? ws.qs : nullptr, st));
             }
             if (!W.quant && batch > 64) {
                 // bf16 above 64 rows (no split-K there): SwiGLU in the epilogue, the down projection's tile as
@@ -741,18 +741,18 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
                 const int sg = proj_pick_splits(L.gu, batch, kMaxSplitsWide);
                 {
                     ProfScope p(prof, 4, st);
-                    ProjLaunch pl{&L.gu, ws.hA, ws.hs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch};
+                    ProjLaunch pl{&L.gu, ws.hA, ws.qs, batch, EPI_STORE, sg, ws.part, L.gu.N, batch};
                     SUN_HIP_CHECK(launch_proj(pl, st));
                 }
                 {
                     ProfScope p(prof, 7, st);
-                    SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, W.quant ? ws.hs : nullptr, st));
+                    SUN_HIP_CHECK(launch_swiglu_tile(ws.part, sg, batch, batch, c.ffn, ws.uA, W.quant ? ws.qs : nullptr, st));
                 }
             }
             const int sd = proj_pick_splits(L.down, batch, kMaxSplits);
             {
                 ProfScope p(prof, 5, st);
-                ProjLaunch pl{&L.down, ws.uA, ws.hs, batch, EPI_STORE, sd, ws.part, H, batch};
+                ProjLaunch pl{&L.down, ws.uA, ws.qs, batch, EPI_STORE, sd, ws.part, H, batch};
                 SUN_HIP_CHECK(launch_proj(pl, st));
             }
             down_parts = sd;
@@ -1104,14 +1104,14 @@ int sun_linear(const sun_weights* weights_, int layer, int mat, int batch, const
     // the tiled input goes to the buffer the step uses for this projection's input
     void* in = mat == 1 ? ws.aA : mat == 3 ? ws.uA : ws.hA;
     const bool w4 = M.kind == MAT_W4_PACKED;
-    SUN_HIP_CHECK(launch_tile_rows(x, batch, M.K, in, w4 ? ws.hs : nullptr, st));
+    SUN_HIP_CHECK(launch_tile_rows(x, batch, M.K, in, w4 ? ws.qs : nullptr, st));
     if (mat == 2) {
         if (!w4) {
             ProjLaunch pl{&M, in, nullptr, batch, EPI_SWIGLU, 1, (float*)ws.uA, M.N, batch};
             SUN_HIP_CHECK(launch_proj(pl, st));
         } else {
             const int s = proj_pick_splits(M, batch, kMaxSplitsWide);
-            ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch};
+            ProjLaunch pl{&M, in, ws.qs, batch, EPI_STORE, s, ws.part, M.N, batch};
             SUN_HIP_CHECK(launch_proj(pl, st));
             SUN_HIP_CHECK(launch_swiglu_tile(ws.part, s, batch, batch, c.ffn, ws.uA, nullptr, st));
         }
@@ -1121,7 +1121,7 @@ int sun_linear(const sun_weights* weights_, int layer, int mat, int batch, const
         SUN_HIP_CHECK(launch_proj(pl, st));
     } else {
         const int s = proj_pick_splits(M, batch, kMaxSplits);
-        ProjLaunch pl{&M, in, ws.hs, batch, EPI_STORE, s, ws.part, M.N, batch};
+        ProjLaunch pl{&M, in, ws.qs, batch, EPI_STORE, s, ws.part, M.N, batch};
         SUN_HIP_CHECK(launch_proj(pl, st));
         SUN_HIP_CHECK(launch_reduce_partials(ws.part, s, batch, batch, M.N, out, st));
     }

@@ -509,7 +509,7 @@ struct CombineArgs {
     const float* partial;
     float* out_f32;
     uint16_t* out_tiled;
-    float* hsum;
+    float* qscale;
     int Hq, D, batch, out_mb;
 };
 
@@ -548,13 +548,13 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
     }
     const float v = num / den;
     if (a.out_f32) a.out_f32[(size_t)b * a.Hq * a.D + col] = v;
-    if (a.out_tiled && !a.hsum) {
+    if (a.out_tiled && !a.qscale) {
         uint16_t lo;
         const uint16_t hi = split_bf16(v, lo);
         a.out_tiled[atile_elem(ATile{a.out_mb}, 0, b, col)] = hi;
         a.out_tiled[atile_elem(ATile{a.out_mb}, 1, b, col)] = lo;
     }
-    if (a.out_tiled && a.hsum) {
+    if (a.out_tiled && a.qscale) {
         // fixed-point tile of the 4-bit O projection: the workgroup's 128 columns are one group
         __shared__ float red_max[2];
         __shared__ int red_sum[2];
@@ -573,19 +573,19 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(CombineArgs a) {
         if ((threadIdx.x & 63) == 0) red_sum[threadIdx.x >> 6] = sum;
         __syncthreads();
         if (threadIdx.x == 0)
-            reinterpret_cast<float2*>(a.hsum)[(size_t)blockIdx.x * (a.out_mb * 32) + b] =
+            reinterpret_cast<float2*>(a.qscale)[(size_t)blockIdx.x * (a.out_mb * 32) + b] =
                 float2{am / kQMax, __int_as_float(red_sum[0] + red_sum[1])};
     }
 }
 
 hipError_t launch_attn_combine(const sun_model_cfg& cfg, const AttnPlan& plan, int batch, float* out_f32,
-                               void* out_tiled, float* hsum, hipStream_t st) {
+                               void* out_tiled, float* qscale, hipStream_t st) {
     CombineArgs a{};
     a.chunk_off = plan.chunk_off;
     a.partial = plan.partial;
     a.out_f32 = out_f32;
     a.out_tiled = (uint16_t*)out_tiled;
-    a.hsum = hsum;
+    a.qscale = qscale;
     a.Hq = cfg.n_q_heads;
     a.D = cfg.head_dim;
     a.batch = batch;

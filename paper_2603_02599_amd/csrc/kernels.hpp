@@ -14,7 +14,7 @@ enum ProjEpilogue {
 struct ProjLaunch {
     const Mat* W;
     const void* A;         // tiled bf16 activations [rows, K]
-    const float* hsum;     // W4 only: [K/128][MB*32] sums of the (rounded) activations per group
+    const float* qscale;   // W4 only: [K/128][MB*32] pairs (scale, sum of integers as int bits) of the fixed-point tile A
     int rows;              // valid rows (<= 256)
     int epilogue;
     int splits;            // split-K factor (EPI_STORE only); partial s is written at out + s*ld_rows*ldo
@@ -58,18 +58,20 @@ hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int l
 hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan, const float* q,
                              const int32_t* page_tables, int max_pages, const int32_t* n_or_len, int len_plus,
                              int batch, int total_chunks_hint, bool f32_exact, hipStream_t st);
-// out: fp32 row-major [batch, Hq*d] (out_f32) and/or tiled bf16 (+ per-128 group sums for W4).
+// out: fp32 row-major [batch, Hq*d] (out_f32) and/or the O projection's input: two-plane tiled bf16, or, with
+// qscale given, the fixed-point tile of a 4-bit projection and its (scale, integer sum) pairs.
 hipError_t launch_attn_combine(const sun_model_cfg& cfg, const AttnPlan& plan, int batch, float* out_f32,
-                               void* out_tiled, float* hsum, hipStream_t st);
+                               void* out_tiled, float* qscale, hipStream_t st);
 
 // ---------------- everything else (misc.hip) ----------------
 
 hipError_t launch_embed(const sun_model_cfg& cfg, const void* embed, const int32_t* tokens, int batch, float* x,
                         hipStream_t st);
 // x[b] += sum_s partial[s][b] (s ascending; nparts may be 0); then h = rmsnorm(x; g).
-// h_f32: row-major fp32 or NULL; h_tiled: tiled bf16 or NULL; hsum: group sums or NULL.
+// h_f32: row-major fp32 or NULL; h_tiled: tiled bf16 or NULL; with qscale given h_tiled is the fixed-point tile of a
+// 4-bit projection instead and qscale receives its (scale, integer sum) pairs.
 hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float* partial, int nparts, int ld_rows,
-                                const void* gain, int batch, float* h_f32, void* h_tiled, float* hsum, hipStream_t st);
+                                const void* gain, int batch, float* h_f32, void* h_tiled, float* qscale, hipStream_t st);
 // k_src, v_src: bf16 [n_layers][n_tokens][Hkv][d]; token t lands at position first_pos + t of the request whose
 // page-table row is given.
 hipError_t launch_kv_ingest(const KvPool& pool, const void* k_src, const void* v_src, int n_tokens, int first_pos,
@@ -100,15 +102,15 @@ hipError_t launch_rope_append(const KvPool& pool, int layer, const float* qkv, i
                               int batch, float* q_out, const void* q_norm, const void* k_norm, const void* bq, const void* bk,
                               const void* bv, hipStream_t st);
 hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipStream_t st);
-// gate/up partial sums (projection column order) -> silu(g)*u as two-plane tiled bf16 (+ group sums)
-hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,
+// gate/up partial sums (projection column order) -> silu(g)*u as two-plane tiled bf16, or as fixed-point tile + qscale
+hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* qscale,
                               hipStream_t st);
 constexpr int kArgmaxParts = 16;  // slices of a logits row searched by separate workgroups
 // part_val / part_idx: scratch [batch][kArgmaxParts]
 hipError_t launch_argmax(const float* logits, int batch, int vocab, float* part_val, int32_t* part_idx, int32_t* next,
                          hipStream_t st);
-// fp32 [rows, K] -> tiled bf16 (+ group sums)
-hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st);
+// fp32 [rows, K] -> two-plane tiled bf16, or fixed-point tile + qscale
+hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* qscale, hipStream_t st);
 // out[b][n] = sum_s partial[s][b][n]
 hipError_t launch_reduce_partials(const float* partial, int nparts, int ld_rows, int rows, int N, float* out,
                                   hipStream_t st);

@@ -147,14 +147,14 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(NormArgs a) {
 }
 
 hipError_t launch_residual_norm(const sun_model_cfg& cfg, float* x, const float* partial, int nparts, int ld_rows,
-                                const void* gain, int batch, float* h_f32, void* h_tiled, float* hsum, hipStream_t st) {
+                                const void* gain, int batch, float* h_f32, void* h_tiled, float* qscale, hipStream_t st) {
     NormArgs a{};
     a.x = x;
     a.partial = partial;
     a.gain = gain;
     a.h_f32 = h_f32;
     a.h_tiled = (uint16_t*)h_tiled;
-    a.qscale = (float2*)hsum;
+    a.qscale = (float2*)qscale;
     a.nparts = nparts;
     a.ld_rows = ld_rows;
     a.H = cfg.hidden;
@@ -342,10 +342,10 @@ hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipS
 // ---------------- SwiGLU over the gate/up projection's partial sums ----------------
 // part: [nparts][ld_rows][2*ffn] fp32 with the projection's column order (blocks of 16 gate
 // columns followed by their 16 up columns).  Writes u = silu(sum g) * (sum u) [rows, ffn] as the down
-// projection's input: two-plane tiled bf16, or (hsum given) the fixed-point tile of a 4-bit projection.
+// projection's input: two-plane tiled bf16, or (qscale given) the fixed-point tile of a 4-bit projection.
 __global__ __launch_bounds__(256) void swiglu_tile_kernel(const float* __restrict__ part, int nparts, int ld_rows,
                                                           int ffn, int mb, u32x4* __restrict__ tiled,
-                                                          float* __restrict__ hsum) {
+                                                          float* __restrict__ qscale) {
     const int b = blockIdx.y, u = blockIdx.x * 256 + threadIdx.x;  // unit = 8 consecutive u columns
     float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (u < ffn / 8) {
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(256) void swiglu_tile_kernel(const float* __restric
             y[e] = g0[e] / (1.f + __expf(-g0[e])) * u0[e];
             y[4 + e] = g1[e] / (1.f + __expf(-g1[e])) * u1[e];
         }
-        if (!hsum) {
+        if (!qscale) {
             u32x4 o, ol;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -375,15 +375,15 @@ __global__ __launch_bounds__(256) void swiglu_tile_kernel(const float* __restric
             tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
         }
     }
-    if (hsum) qtile_group16((uint8_t*)tiled, (float2*)hsum, ATile{mb}, b, u, u < ffn / 8, y);
+    if (qscale) qtile_group16((uint8_t*)tiled, (float2*)qscale, ATile{mb}, b, u, u < ffn / 8, y);
 }
 
-hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* hsum,
+hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* qscale,
                               hipStream_t st) {
     if (ffn % 128) return hipErrorInvalidValue;
     const int mb = atile_for_rows(rows).MB;
     hipLaunchKernelGGL(swiglu_tile_kernel, dim3((ffn / 8 + 255) / 256, rows), dim3(256), 0, st, part, nparts, ld_rows, ffn,
-                       mb, (u32x4*)tiled, hsum);
+                       mb, (u32x4*)tiled, qscale);
     return hipGetLastError();
 }
 
@@ -825,7 +825,7 @@ hipError_t launch_serve(const ServeArgs& a, const int32_t* next, int32_t* tokens
 
 // ---------------- layout helpers ----------------
 __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict__ x, int rows, int K, int mb,
-                                                        u32x4* __restrict__ tiled, float* __restrict__ hsum) {
+                                                        u32x4* __restrict__ tiled, float* __restrict__ qscale) {
     const int b = blockIdx.y;
     const int u = blockIdx.x * 256 + threadIdx.x;
     float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -833,7 +833,7 @@ __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict_
         const float* p = x + (size_t)b * K + u * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) y[e] = p[e];
-        if (!hsum) {
+        if (!qscale) {
             u32x4 o, ol;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -844,14 +844,14 @@ __global__ __launch_bounds__(256) void tile_rows_kernel(const float* __restrict_
             tiled[atile_unit(ATile{mb}, 1, b, u)] = ol;
         }
     }
-    if (hsum) qtile_group16((uint8_t*)tiled, (float2*)hsum, ATile{mb}, b, u, u < K / 8, y);
+    if (qscale) qtile_group16((uint8_t*)tiled, (float2*)qscale, ATile{mb}, b, u, u < K / 8, y);
 }
 
-hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* hsum, hipStream_t st) {
+hipError_t launch_tile_rows(const float* x, int rows, int K, void* tiled, float* qscale, hipStream_t st) {
     if (K % 128) return hipErrorInvalidValue;
     const int mb = atile_for_rows(rows).MB;
     hipLaunchKernelGGL(tile_rows_kernel, dim3((K / 8 + 255) / 256, rows), dim3(256), 0, st, x, rows, K, mb,
-                       (u32x4*)tiled, hsum);
+                       (u32x4*)tiled, qscale);
     return hipGetLastError();
 }
 

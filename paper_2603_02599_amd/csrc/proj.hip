@@ -29,7 +29,7 @@ struct ProjArgs {
     const uint32_t* SZ;
     int s_only;    // W4: SZ holds fp16 scales only, two 128-wide groups per dword; the zero point is 8 everywhere
     const u32x4* A;
-    const float* hsum;
+    const float* qscale;
     float* out;
     int rows, N, K;
     int n_stages, stages_per_split;
@@ -40,7 +40,7 @@ struct ProjArgs {
 // MB counts the 32-row operand blocks of the workgroup: MR = MB/2 blocks of rows, each present
 // as a hi and a lo bf16 plane (operand block m < MR is the hi plane of row block m, block MR+m
 // its lo plane); both are multiplied with the same weight fragment into the same accumulator.
-template <int MB, int KS, int NW, int EPI, bool W4, int NBUF>
+template <int MB, int KS, int NW, int EPI, int NBUF>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void proj_kernel(ProjArgs a) {
     constexpr int MR = MB / 2;
@@ -49,14 +49,9 @@ void proj_kernel(ProjArgs a) {
     constexpr int STAGE_UNITS = KK * MB * 64;  // 16-byte units of activations per stage
     constexpr int NT = NW * 64;
     constexpr int UPT = (STAGE_UNITS + NT - 1) / NT;  // the last round of a stage may be partial
-    constexpr int WREGS = W4 ? KK / 4 : KK;    // 16-byte weight loads per lane per stage
+    constexpr int WREGS = KK;                  // 16-byte weight loads per lane per stage
 
     __shared__ u32x4 lds[NBUF][STAGE_UNITS];  // ring of staged activation tiles (prefetch distance NBUF-1)
-    float* hs_lds = nullptr;  // W4: [4][MR*32] group sums of the activations, ring indexed by chunk
-    if constexpr (W4) {
-        __shared__ __attribute__((aligned(16))) float hs_store[4 * MR * 32];
-        hs_lds = hs_store;
-    }
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5;
     const int nb = blockIdx.x * NW + wave;
@@ -68,28 +63,19 @@ void proj_kernel(ProjArgs a) {
     const int kch = a.K / 128;
 
     // waves past the last column block work on block 0 and drop their result (keeps the loop branch-free)
-    const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * (W4 ? 2 : 8) * 64 + lane;
-    const uint32_t* SZl =
-        W4 ? a.SZ + ((size_t)(active ? nb : 0) * (a.s_only ? (kch + 1) >> 1 : kch)) * 32 + (lane & 31) : nullptr;
+    const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * 8 * 64 + lane;
 
     f32x16 acc[MR];
-    f32x16 accg[W4 ? MR : 1];
 #pragma unroll
     for (int m = 0; m < MR; ++m)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
 
     u32x4 w0[WREGS], w1[WREGS], w2[NBUF == 3 ? WREGS : 1], areg[UPT];
-    uint32_t sz0 = 0, sz1 = 0, sz2 = 0;
-    float hreg = 0.f;
 
-    auto load_w = [&](u32x4(&w)[WREGS], uint32_t& sz, int st) {
+    auto load_w = [&](u32x4(&w)[WREGS], int st) {
 #pragma unroll
         for (int j = 0; j < WREGS; ++j) w[j] = Wl[((size_t)st * WREGS + j) * 64];
-        if (W4) {
-            const int g = (st * KK) >> 3;
-            sz = SZl[(size_t)(a.s_only ? g >> 1 : g) * 32];
-        }
     };
     auto load_a = [&](int st) {
 #pragma unroll
@@ -100,18 +86,13 @@ void proj_kernel(ProjArgs a) {
             const int gb = m < MR ? mb_off + m : a.mb_rows + mb_off + (m - MR);
             areg[i] = a.A[((size_t)(st * KK + kk) * (2 * a.mb_rows) + gb) * 64 + (rem & 63)];
         }
-        if (W4 && ((st * KK) & 7) == 0 && tid < MR * 32)
-            hreg = a.hsum[(size_t)((st * KK) >> 3) * (a.mb_rows * 32) + mb_off * 32 + tid];
     };
-    auto store_a = [&](int buf, int st) {
+    auto store_a = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i)
             if (STAGE_UNITS % NT == 0 || i * NT + tid < STAGE_UNITS) lds[buf][i * NT + tid] = areg[i];
-        if (W4 && ((st * KK) & 7) == 0 && tid < MR * 32) hs_lds[(((st * KK) >> 3) & 3) * MR * 32 + tid] = hreg;
     };
-    auto compute = [&](int buf, const u32x4(&w)[WREGS], uint32_t sz, int st) {
-        const bool first = (KS == 128) || ((st & 1) == 0);
-        const bool last = (KS == 128) || ((st & 1) == 1);
+    auto compute = [&](int buf, const u32x4(&w)[WREGS]) {
         // A operands are read from LDS one k-step ahead of the MFMAs that use them; the 128-row
         // kernel reads them just in time instead: with the second fragment set it would not fit two
         // waves per SIMD, and the second wave hides more latency than the early read
@@ -133,49 +114,13 @@ void proj_kernel(ProjArgs a) {
                 for (int m = 0; m < MB; ++m) afr[0][m] = lds[buf][(kk * MB + m) * 64 + lane];
             }
             __builtin_amdgcn_sched_barrier(0);
-            bf16x8 bfrag;
-            if (W4) {
-                const uint32_t word = w[kk >> 2][kk & 3];
-                u32x4 t;
-#pragma unroll
-                for (int p = 0; p < 4; ++p) t[p] = ((word >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
-                bfrag = __builtin_bit_cast(bf16x8, t);
-            } else {
-                bfrag = __builtin_bit_cast(bf16x8, w[kk]);
-            }
+            const bf16x8 bfrag = __builtin_bit_cast(bf16x8, w[kk]);
 #pragma unroll
             for (int pl = 0; pl < 2; ++pl)  // hi plane, then lo plane, into the same accumulators
 #pragma unroll
                 for (int m = 0; m < MR; ++m) {
                     const bf16x8 afrag = __builtin_bit_cast(bf16x8, afr[kk & (AF - 1)][pl * MR + m]);
-                    if (W4) {
-                        if (first && kk == 0 && pl == 0) {
-                            f32x16 zero;
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-                            accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, zero, 0, 0, 0);
-                        } else {
-                            accg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, accg[m], 0, 0, 0);
-                        }
-                    } else {
-                        acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[m], 0, 0, 0);
-                    }
-                }
-        }
-        if (W4 && last) {
-            // scale-only layout: pick this group's half of the dword and put the constant zero point 8.0 beside it
-            const uint32_t szg = a.s_only ? (((sz >> (16 * (((st * KK) >> 3) & 1))) & 0xffffu) | 0x48000000u) : sz;
-            const __half2 h2 = __builtin_bit_cast(__half2, szg);
-            const float s = __low2float(h2), nzz = -(128.f + __high2float(h2));
-            const float* hs = hs_lds + (((st * KK) >> 3) & 3) * MR * 32;
-#pragma unroll
-            for (int m = 0; m < MR; ++m)
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const f32x4 h4 = *reinterpret_cast<const f32x4*>(hs + m * 32 + 8 * rr + 4 * half);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        acc[m][rr * 4 + q] = fmaf(s, fmaf(nzz, h4[q], accg[m][rr * 4 + q]), acc[m][rr * 4 + q]);
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[m], 0, 0, 0);
                 }
         }
     };
@@ -185,48 +130,47 @@ void proj_kernel(ProjArgs a) {
     // re-read and never used.
     if (s0 < s1) {
         if constexpr (NBUF == 3) {
-            auto phase = [&](const u32x4(&wc)[WREGS], uint32_t szc, u32x4(&wn)[WREGS], uint32_t& szn, int bufc, int bufn,
-                             int st) {
+            auto phase = [&](const u32x4(&wc)[WREGS], u32x4(&wn)[WREGS], int bufc, int bufn, int st) {
                 const int nx = min(st + 2, s1 - 1);
                 load_a(nx);  // before the weights: the LDS store below then waits for these only
-                load_w(wn, szn, nx);
-                compute(bufc, wc, szc, st);
-                store_a(bufn, nx);
+                load_w(wn, nx);
+                compute(bufc, wc);
+                store_a(bufn);
                 __syncthreads();
             };
             const int sA = min(s0 + 1, s1 - 1);
-            load_w(w0, sz0, s0);
+            load_w(w0, s0);
             load_a(s0);
-            store_a(0, s0);
-            load_w(w1, sz1, sA);
+            store_a(0);
+            load_w(w1, sA);
             load_a(sA);
-            store_a(1, sA);
+            store_a(1);
             __syncthreads();
             for (int st = s0; st < s1; st += 3) {
-                phase(w0, sz0, w2, sz2, 0, 2, st);
+                phase(w0, w2, 0, 2, st);
                 if (st + 1 >= s1) break;
-                phase(w1, sz1, w0, sz0, 1, 0, st + 1);
+                phase(w1, w0, 1, 0, st + 1);
                 if (st + 2 >= s1) break;
-                phase(w2, sz2, w1, sz1, 2, 1, st + 2);
+                phase(w2, w1, 2, 1, st + 2);
             }
         } else {
-            load_w(w0, sz0, s0);
+            load_w(w0, s0);
             load_a(s0);
-            store_a(0, s0);
+            store_a(0);
             __syncthreads();
             for (int st = s0; st < s1; st += 2) {
                 const int n1 = min(st + 1, s1 - 1);
                 load_a(n1);
-                load_w(w1, sz1, n1);
-                compute(0, w0, sz0, st);
-                store_a(1, n1);
+                load_w(w1, n1);
+                compute(0, w0);
+                store_a(1);
                 __syncthreads();
                 if (st + 1 >= s1) break;
                 const int n2 = min(st + 2, s1 - 1);
                 load_a(n2);
-                load_w(w0, sz0, n2);
-                compute(1, w1, sz1, st + 1);
-                store_a(0, n2);
+                load_w(w0, n2);
+                compute(1, w1);
+                store_a(0);
                 __syncthreads();
             }
         }
@@ -307,7 +251,7 @@ void proj_w4_kernel(ProjArgs a) {
     // waves past the last column block work on block 0 and drop their result (keeps the loop branch-free)
     const u32x4* Wl = a.W + ((size_t)(active ? nb : 0) * kch) * 2 * 64 + lane;
     const uint32_t* SZl = a.SZ + ((size_t)(active ? nb : 0) * (a.s_only ? (kch + 1) >> 1 : kch)) * 32 + (lane & 31);
-    const float2* QS = reinterpret_cast<const float2*>(a.hsum);
+    const float2* QS = reinterpret_cast<const float2*>(a.qscale);
 
     f32x16 acc[MR];
     i32x16 ih[MR], il[MR];
@@ -451,20 +395,17 @@ static hipError_t launch_proj_w4(const ProjArgs& a, int nw, int splits, int mtil
     return hipErrorInvalidValue;
 }
 
-template <int MB, int KS, bool W4, int NW = 4>
+template <int MB, int KS, int NW = 4>
 static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
     constexpr int NBUF = (MB * KS * 64 * 3 <= 49152) ? 3 : 2;  // LDS ring: 3 stages when they fit in 48 KB
     dim3 grid((a.N / 32 + NW - 1) / NW, splits, mtiles), block(NW * 64);
     if (epilogue == EPI_SWIGLU) {
-        if constexpr (!W4) {
-            if (splits != 1) return hipErrorInvalidValue;
-            hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, false, NBUF>), grid, block, 0, st, a);
-            return hipGetLastError();
-        }
-        return hipErrorInvalidValue;
+        if (splits != 1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_SWIGLU, NBUF>), grid, block, 0, st, a);
+        return hipGetLastError();
     }
     if (epilogue != EPI_STORE) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, W4, NBUF>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((proj_kernel<MB, KS, NW, EPI_STORE, NBUF>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 
@@ -537,13 +478,13 @@ static int proj_pick_waves(const Mat& W, int rows, int splits) {
     return best;
 }
 
-template <int MB, int KS, bool W4>
+template <int MB, int KS>
 static hipError_t launch_proj_nw(const ProjArgs& a, int nw, int epilogue, int splits, int mtiles, hipStream_t st) {
     switch (nw) {
-    case 4: return launch_proj_t<MB, KS, W4, 4>(a, epilogue, splits, mtiles, st);
-    case 5: return launch_proj_t<MB, KS, W4, 5>(a, epilogue, splits, mtiles, st);
-    case 6: return launch_proj_t<MB, KS, W4, 6>(a, epilogue, splits, mtiles, st);
-    case 7: return launch_proj_t<MB, KS, W4, 7>(a, epilogue, splits, mtiles, st);
+    case 4: return launch_proj_t<MB, KS, 4>(a, epilogue, splits, mtiles, st);
+    case 5: return launch_proj_t<MB, KS, 5>(a, epilogue, splits, mtiles, st);
+    case 6: return launch_proj_t<MB, KS, 6>(a, epilogue, splits, mtiles, st);
+    case 7: return launch_proj_t<MB, KS, 7>(a, epilogue, splits, mtiles, st);
     }
     return hipErrorInvalidValue;
 }
@@ -559,7 +500,7 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     a.SZ = (const uint32_t*)W.sz;
     a.s_only = W.s_only ? 1 : 0;
     a.A = (const u32x4*)p.A;
-    a.hsum = p.hsum;
+    a.qscale = p.qscale;
     a.out = p.out;
     a.rows = p.rows;
     a.N = W.N;
@@ -571,7 +512,7 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
     int splits = max(1, p.splits);
     const int cps = chunks_per_split(kch, splits);
     splits = (kch + cps - 1) / cps;
-    if (w4 && p.hsum == nullptr) return hipErrorInvalidValue;
+    if (w4 && p.qscale == nullptr) return hipErrorInvalidValue;
     const ProjTiling t = proj_tiling(W, p.rows);
     // Up to 64-row tiles a stage is a whole 128-wide group: three 16 KB stages in LDS for 32-row tiles,
     // two 32 KB stages for 64-row tiles (long stages amortise the workgroup barrier better than a
@@ -584,12 +525,12 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
             if (p.epilogue != EPI_STORE) return hipErrorInvalidValue;
             return t.mb == 2 ? launch_proj_w4<1>(a, nw, splits, t.mtiles, st) : launch_proj_w4<2>(a, nw, splits, t.mtiles, st);
         }
-        if (t.mb == 2) return launch_proj_nw<2, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
-        return launch_proj_nw<4, 128, false>(a, nw, p.epilogue, splits, t.mtiles, st);
+        if (t.mb == 2) return launch_proj_nw<2, 128>(a, nw, p.epilogue, splits, t.mtiles, st);
+        return launch_proj_nw<4, 128>(a, nw, p.epilogue, splits, t.mtiles, st);
     }
     a.n_stages = kch * 2;
     a.stages_per_split = cps * 2;
-    return launch_proj_t<8, 64, false>(a, p.epilogue, splits, t.mtiles, st);
+    return launch_proj_t<8, 64>(a, p.epilogue, splits, t.mtiles, st);
 }
 
 // ---------------------------------------------------------------------------------
