@@ -237,6 +237,49 @@ def test_linear_op_w4(H, batch):
         assert np.all(np.abs(got - want) <= tol), f"mat {mat}: max diff {np.abs(got - want).max():.3e}"
 
 
+def test_linear_op_w4_fixed_point_bound_with_outliers_and_empty_groups(H):
+    """The 4-bit projections take their input as 16-bit fixed point per row and 128-wide group.  Rows with
+    outliers 100x the rest, groups that are all zero, an all-zero row and a row of tiny values: the result stays
+    within the bound the format implies, sum over groups of (max|x| of the group / 32639 / 2) * sum|w_hat|, plus
+    fp32 rounding; rows and groups without outliers are not affected by the outliers elsewhere."""
+    from oracle import oracle as orc
+    shape = wl.SMALL128
+    H.say("linear W4 with outliers and empty groups")
+    cfg = sun.make_cfg(shape, "bf16")
+    w = wl.make_weights(shape, "bf16", H.DEV, 13, std=0.05)
+    quant = {k: [sun.sun_quantize_w4(m, 128, "asym") for m in w[k]] for k in sun.QUANT_KEYS}
+    W = sun.sun_qweights_create(cfg, w, quant)
+    batch = 40
+    ws = torch.empty(sun.sun_workspace_bytes(cfg, batch, 4), dtype=torch.uint8, device=H.DEV)
+    rng = np.random.default_rng(14)
+    for mat, key, K, N in ((1, "wo", 1024, 512), (3, "wd", 1024, 512)):
+        x = rng.standard_normal((batch, K)).astype(np.float32)
+        x[0, rng.integers(0, K, size=5)] *= 100.0          # outliers in a few groups of row 0
+        x[1, 128:384] = 0.0                                 # two empty groups
+        x[2, :] = 0.0                                       # an empty row
+        x[3, :] *= 1e-20                                    # tiny values: the scale is tiny, not zero
+        x[4, 5] = 3.0e4                                     # one huge value
+        xd = torch.from_numpy(x).to(H.DEV)
+        out = torch.full((batch, N), float("nan"), device=H.DEV)
+        sun.sun_linear(W, 0, mat, xd, out, ws)
+        torch.cuda.synchronize()
+        q, sc, z = (H.to_np(t) for t in quant[key][0])
+        what = orc.dequantize_w4(q, sc, z, K, 128).astype(np.float64)
+        want = orc.linear(orc.w4_mat(q, sc, z, K, 128), x.astype(np.float64))
+        got = out.double().cpu().numpy()
+        assert np.isfinite(got).all()
+        amax = np.abs(x.astype(np.float64)).reshape(batch, K // 128, 128).max(axis=2)              # [b, g]
+        wabs = np.abs(what).reshape(N, K // 128, 128).sum(axis=2)                                   # [n, g]
+        bound = (amax / 32639.0 / 2.0) @ wabs.T                                                     # [b, n]
+        slack = 4e-6 * (np.abs(x.astype(np.float64)) @ np.abs(what).T) + 1e-30                      # fp32 rounding of sums and scales
+        err = np.abs(got - want)
+        assert np.all(err <= 1.05 * bound + slack), f"mat {mat}: worst excess {(err - bound - slack).max():.3e}"
+        assert np.all(got[2] == 0.0)
+        H.say(f"   mat {mat}: max err / bound = {(err / (bound + slack)).max():.3f}; row 0 max err {err[0].max():.2e}, "
+              f"other rows {err[5:].max():.2e}")
+        assert err[5:].max() < 2e-4      # rows without outliers keep their usual accuracy
+
+
 # ------------------------------------------------------------------ bf16 and QSUN full steps, small shapes
 @pytest.mark.parametrize("batch", [8, 48, 100])
 def test_bf16_small_full_step(H, batch):
