@@ -7,7 +7,7 @@ Prints ONE JSON line: tokens/s (= batch / step time), TPOT (= step time), the ro
 dominant kernel (paged attention, HBM bound) measured with HIP events inside this run, and the
 CPU oracle timed on a bounded sample of the same workload on this machine's host cores.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5b] [--quant asym|sym|sym_noz]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg5a|cfg5b] [--quant asym|sym|sym_noz]
 """
 from __future__ import annotations
 
@@ -67,18 +67,13 @@ def build_workload(name: str):
     if name == "cfg3":
         return wl.make_workload("cfg3"), "8B-shaped shared decode, batch 256 over 8 Zipf(1.2) source models, log-normal L (median 1024, clip [64,16384])"
     if name == "cfg5b":
-        # 14B shape; requests admitted in draw order until ~200 GB of KV pool is full (no aliasing)
-        full = wl.make_workload("cfg5")
-        kv_tok = full.shape.kv_bytes_per_token()
-        keep, tot = 0, 0
-        for L in full.seq_lens:
-            pages = (int(L) + 16) // 16
-            if (tot + pages) * 16 * kv_tok > 200e9:
-                break
-            tot += pages
-            keep += 1
-        w = wl.make_workload("cfg5", batch=keep)
-        return w, f"14B-shaped shared decode, first {keep} of 128 Zipf(1.2) requests fitting a 200 GB pool, L~U[2048,32768]"
+        w = wl.make_workload("cfg5b")
+        return w, (f"14B-shaped shared decode, the first {w.batch} of 128 Zipf(1.2)-tagged requests, L~U[2048,32768], whose "
+                   "caches fit a 200 GB pool (no aliasing)")
+    if name == "cfg5a":
+        w = wl.make_workload("cfg5a")
+        return w, (f"14B-shaped shared decode, batch 128 over 16 Zipf(1.2) source models, L~U[2048,32768], over a "
+                   f"{w.n_pages}-page (206 GB) pool: own tail pages, history pages shared read-only")
     if name == "small":
         return (wl.make_workload("cfg2", shape=wl.SMALL128, batch=64, lo=64, hi=512, seed=7),
                 "small128 test shape, batch 64 (not a benchmark configuration)")
@@ -266,7 +261,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2",
-                    help="cfg2 (default, the headline configuration), cfg1 (tiny fp32), cfg3, cfg5b, small, or b<batch>x<len>")
+                    help="cfg2 (default, the headline configuration), cfg1 (tiny fp32), cfg3, cfg5a, cfg5b, small, or b<batch>x<len>")
     ap.add_argument("--quant", default=None, choices=[None, "asym", "sym", "sym_noz"],
                     help="4-bit group-128 decode weights: affine, symmetric, or symmetric without stored zero points")
     ap.add_argument("--cpu-sample", type=int, default=24, help="requests the oracle is timed on (0 = skip); 24 are about 10 s of CPU work")
@@ -311,7 +306,7 @@ def main():
 
     if args.ingest_tokens > 0:
         from paper_2603_02599_amd import workloads as wl
-        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
+        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5a": wl.QWEN_14B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
         n = args.ingest_tokens
         pages = (n + 15) // 16
         cfg = sun.make_cfg(shape, "bf16")
@@ -341,7 +336,7 @@ def main():
         return
     if args.prefill_tokens > 0:
         from paper_2603_02599_amd import workloads as wl
-        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
+        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5a": wl.QWEN_14B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
         n = args.prefill_tokens
         pages = n // 16 + 1
         cfg = sun.make_cfg(shape, "bf16")
@@ -372,7 +367,7 @@ def main():
         return
     if args.sweep_step_times:
         from paper_2603_02599_amd import workloads as wl
-        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
+        shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5a": wl.QWEN_14B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
         shared = H.DeviceWeights(shape, "bf16", 11, quant_mode=args.quant)
         fn = sun.sun_qdecode_step if args.quant else sun.sun_decode_step
         points = []

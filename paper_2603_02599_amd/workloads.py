@@ -74,6 +74,9 @@ SMALL_G5 = Shape("small_g5", 2, 1280, 10, 2, 128, 1024, 2048)
 LLAMA_8B = Shape("llama8b", 32, 4096, 32, 8, 128, 14336, 128256)
 QWEN_14B = Shape("qwen14b", 48, 5120, 40, 8, 128, 13824, 152064)
 
+CFG5A_PAGES = 65600          # pool pages of the aliased 14B workload (206 GB at 196 608 B per cached token)
+CFG5B_POOL_BYTES = 200e9     # pool budget of the unaliased 14B workload
+
 SHAPES = {s.name: s for s in (TINY, TINY_Q, TINY_QWEN, SMALL128, SMALL_LLAMA31, SMALL_G5, LLAMA_8B, QWEN_14B)}
 
 
@@ -182,7 +185,9 @@ def _torch_dtype(dtype: str):
 def make_weights(shape: Shape, dtype: str, device: str, seed: int,
                  std: float = 0.02, layers: Optional[int] = None) -> Dict[str, object]:
     """Random decoder weights: every matrix and the embedding ~ N(0, std^2),
-    rounded to `dtype`; all RMSNorm gains are 1.  Matrices are row-major
+    rounded to `dtype`; RMSNorm gains ~ 1 + N(0, 0.1^2) (centred on 1 so that the
+    activations keep their scale through the depth, spread so that a dropped,
+    swapped or mis-indexed gain shows in the logits).  Matrices are row-major
     [out_features, in_features].  Returns a dict with per-layer lists."""
     g = torch.Generator(device=device)
     g.manual_seed(seed)
@@ -194,29 +199,29 @@ def make_weights(shape: Shape, dtype: str, device: str, seed: int,
         w.normal_(0.0, std, generator=g)
         return w.to(dt)
 
+    def gain(n):
+        v = torch.empty(n, dtype=torch.float32, device=device).normal_(1.0, 0.1, generator=g)
+        return v.to(dt)
+
     w: Dict[str, object] = {"dtype": dtype, "shape": shape}
     w["embed"] = mat(shape.vocab, shape.hidden)
     for k in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd"):
         w[k] = []
     for _ in range(nl):
-        w["g1"].append(torch.ones(shape.hidden, dtype=dt, device=device))
+        w["g1"].append(gain(shape.hidden))
         w["wq"].append(mat(shape.q_dim, shape.hidden))
         w["wk"].append(mat(shape.kv_dim, shape.hidden))
         w["wv"].append(mat(shape.kv_dim, shape.hidden))
         w["wo"].append(mat(shape.hidden, shape.q_dim))
-        w["g2"].append(torch.ones(shape.hidden, dtype=dt, device=device))
+        w["g2"].append(gain(shape.hidden))
         w["wg"].append(mat(shape.ffn, shape.hidden))
         w["wu"].append(mat(shape.ffn, shape.hidden))
         w["wd"].append(mat(shape.hidden, shape.ffn))
-    w["gf"] = torch.ones(shape.hidden, dtype=dt, device=device)
+    w["gf"] = gain(shape.hidden)
     w["wlm"] = mat(shape.vocab, shape.hidden)
     if shape.qk_norm:  # head-norm gains: 1 + N(0, 0.1^2), so that a dropped or swapped gain shows
-        def head_gain():
-            g = torch.empty(shape.head_dim, dtype=torch.float32, device=device).normal_(1.0, 0.1, generator=g_)
-            return g.to(dt)
-        g_ = g
-        w["qn"] = [head_gain() for _ in range(nl)]
-        w["kn"] = [head_gain() for _ in range(nl)]
+        w["qn"] = [gain(shape.head_dim) for _ in range(nl)]
+        w["kn"] = [gain(shape.head_dim) for _ in range(nl)]
     if shape.qkv_bias:  # N(0, 0.5^2): large enough that a dropped or misplaced bias shows in the logits
         def bias(n):
             return torch.empty(n, dtype=torch.float32, device=device).normal_(0.0, 0.5, generator=g).to(dt)
@@ -267,10 +272,38 @@ def make_workload(name: str, **over) -> Workload:
     cfg2: 8B bf16, 64 requests even over 4 models, L ~ U[512,4096].
     cfg3: 8B bf16, 256 requests Zipf(1.2) over 8 models, log-normal lengths
           (median 1024, sigma 1, clipped to [64,16384]).
-    cfg5: 14B bf16, 128 requests Zipf(1.2) over 16 models, L ~ U[2048,32768],
-          pool capped (history pages aliased) unless n_pages is overridden.
+    cfg5: 14B bf16, 128 requests Zipf(1.2) over 16 models, L ~ U[2048,32768]; the
+          caches of that draw would take 438 GB, so it comes in two forms that fit:
+          cfg5a: all 128 requests over a pool of 65 600 pages (206 GB; more than
+                 2^31 elements per layer): every request's tail page is its own,
+                 its history pages are drawn with replacement from the rest of the
+                 pool (read-only aliasing: the bytes read and the addresses are those
+                 of the full batch, the memory is not);
+          cfg5b: the first requests of the same draw whose pages fit 200 GB, no
+                 aliasing (52 requests).
     Any field can be overridden (e.g. shape=SMALL128, batch=..., lo/hi=...).
     """
+    if name == "cfg5a":
+        over.setdefault("n_pages", CFG5A_PAGES)
+        w = make_workload("cfg5", **over)
+        w.name = "cfg5a"
+        return w
+    if name == "cfg5b":
+        full = make_workload("cfg5", **{**over, "n_pages": 1 << 20})   # the whole draw (its own tables are not used)
+        kv_tok = full.shape.kv_bytes_per_token()
+        keep, tot = 0, 0
+        for L in full.seq_lens:
+            pages = int(pages_needed(np.array([L]))[0])
+            if (tot + pages) * PAGE_TOKENS * kv_tok > CFG5B_POOL_BYTES:
+                break
+            tot += pages
+            keep += 1
+        n_pages = int(over.get("n_pages", CFG5B_POOL_BYTES // (PAGE_TOKENS * kv_tok)))   # the budget, whole pages
+        L = full.seq_lens[:keep].copy()
+        tables, n_pages = deal_page_tables(L, np.random.default_rng(full.seed + 1000), n_pages=n_pages)
+        return Workload(name="cfg5b", shape=full.shape, dtype=full.dtype, batch=keep, n_models=full.n_models,
+                        tokens=full.tokens[:keep].copy(), model_ids=full.model_ids[:keep].copy(), seq_lens=L,
+                        page_tables=tables, n_pages=n_pages, seed=full.seed, aliased=False)
     presets = {
         "cfg1": dict(num=1, shape=TINY, dtype="f32", batch=8, n_models=3, ids="present",
                      lens="uniform", lo=16, hi=128),

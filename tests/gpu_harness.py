@@ -167,13 +167,18 @@ def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
 
 
 def check_appended_kv(gpu_after: np.ndarray, orc_after: np.ndarray, before: np.ndarray, mask: np.ndarray, dtype: str,
-                      abs_tol: float = 2e-6):
-    """Eq. 4: only the predicted slots change.  fp32 path: values equal the oracle's bf16
-    rounding up to 1 bf16 ulp (an fp32 and an fp64 projection can round apart), or, for an element
-    that cancels to nearly zero, where one bf16 ulp is smaller than the fp32 accumulation error of
-    the projection that produced it, up to abs_tol absolute (2e-6 for one step over a given cache);
-    bf16 path: within the logits tolerance.
+                      abs_tol: float = None, max_off_frac: float = 0.15):
+    """Eq. 4: only the predicted slots change, and each stored value is the oracle's round-to-nearest-even
+    bf16 value, or its neighbour: the projections that produce it differ from the oracle's fp64 ones by much
+    less than a bf16 ulp, so the two roundings can fall apart by one ulp and no more.  An element that cancels
+    to nearly zero is the exception (one bf16 ulp there is smaller than the error the path is allowed before the
+    rounding); it is held to abs_tol absolute instead: 2e-6 for the fp32 path (its accumulation error), 2e-3 for
+    the bf16 / 4-bit paths (a tenth of the logit tolerance: what reaches a deep layer's projection input
+    through the layers before it).  A store that does not round to nearest (truncation) would still be within one ulp everywhere
+    but off by one in about half of the elements, so the fraction of elements that differ at all is bounded
+    too (max_off_frac; measured: a few per cent at 32 to 48 layers, 0 to 3 elements on the fp32 path).
     Returns (#elements off by one ulp or more, #elements written)."""
+    abs_tol = max(abs_tol or 0.0, 2e-6 if dtype == "f32" else 2e-3)   # a caller may widen the floor, not narrow it
     assert np.array_equal(gpu_after[~mask], before[~mask]), "GPU wrote outside the appended slots"
     assert np.array_equal(orc_after[~mask], before[~mask])
     a, b = gpu_after[mask].astype(np.int32), orc_after[mask].astype(np.int32)
@@ -183,10 +188,22 @@ def check_appended_kv(gpu_after: np.ndarray, orc_after: np.ndarray, before: np.n
 
     ulp = np.abs(ordered(a) - ordered(b))
     ga, oa = bf16_to_f64(gpu_after[mask]), bf16_to_f64(orc_after[mask])
-    if dtype == "f32":
-        bad = (ulp > 1) & (np.abs(ga - oa) > abs_tol)
-        assert not bad.any(), f"appended K/V differs by {ulp[bad].max()} bf16 ulps ({np.abs(ga - oa)[bad].max():.2e})"
-    else:
-        worst = float((np.abs(ga - oa) - (2e-2 + 1e-2 * np.abs(oa))).max())
-        assert worst <= 0, f"appended K/V exceeds the bf16 tolerance by {worst:.3e}"
-    return int((ulp >= 1).sum()), int(mask.sum())
+    bad = (ulp > 1) & (np.abs(ga - oa) > abs_tol)
+    assert not bad.any(), (f"appended K/V differs by {ulp[bad].max()} bf16 ulps ({np.abs(ga - oa)[bad].max():.2e} absolute) "
+                           f"in {int(bad.sum())} of {int(mask.sum())} elements")
+    off = int((ulp >= 1).sum())
+    assert off <= max_off_frac * max(int(mask.sum()), 1) + 3, \
+        f"{off} of {int(mask.sum())} appended K/V elements differ from the oracle's rounding: not round-to-nearest?"
+    return off, int(mask.sum())
+
+
+def appended_kv_stats(gpu_after: np.ndarray, orc_after: np.ndarray, mask: np.ndarray) -> Dict[str, float]:
+    """For the log: the largest difference (absolute, and in bf16 ulps) among the written elements."""
+    a, b = gpu_after[mask].astype(np.int32), orc_after[mask].astype(np.int32)
+    oa_, ob_ = np.where(a & 0x8000, -(a & 0x7FFF), a & 0x7FFF), np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    ulp = np.abs(oa_ - ob_)
+    d = np.abs(bf16_to_f64(gpu_after[mask]) - bf16_to_f64(orc_after[mask]))
+    multi = ulp > 1
+    return {"max_ulp": int(ulp.max()) if ulp.size else 0, "n_multi_ulp": int(multi.sum()),
+            "max_abs_where_multi_ulp": float(d[multi].max()) if multi.any() else 0.0,
+            "off_frac": float((ulp >= 1).mean()) if ulp.size else 0.0}

@@ -36,7 +36,10 @@ def _full_step_parity(H, case, rows=None, tol=None):
     st = H.layout_strides(case.lay)
     st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
     mask = H.appended_mask(work.shape, st, before_host.size, tabs, work.seq_lens[rows])
-    off, total = H.check_appended_kv(case.pool_pages_now(used), ref["pool_after"], before_host, mask, work.dtype)
+    after = case.pool_pages_now(used)
+    if work.dtype != "f32":
+        H.say(f"   appended K/V {H.appended_kv_stats(after, ref['pool_after'], mask)}")
+    off, total = H.check_appended_kv(after, ref["pool_after"], before_host, mask, work.dtype)
     H.say(f"   next-token near-ties {near}; appended K/V elements off by >=1 bf16 ulp: {off} of {total}")
     return rep
 
@@ -456,3 +459,28 @@ def test_tied_embeddings(H):
     w = wl.make_weights(wl.TINY, "f32", "cuda", 99)
     w["wlm"] = w["embed"]
     _full_step_parity(H, H.GpuCase(work, weights=w))
+
+
+@pytest.mark.parametrize("dtype,shape,quant", [("f32", wl.TINY, None), ("bf16", wl.SMALL128, None), ("bf16", wl.SMALL128, "asym")])
+def test_every_rmsnorm_gain_is_live(H, dtype, shape, quant):
+    """The gains of the two norms of every layer and of the final norm are drawn around 1, not equal to 1, so
+    the parity tests above already pin their wiring; here each one is shown to reach the logits on the GPU:
+    scaling one gain vector changes them."""
+    H.say(f"gains live {dtype} quant={quant}")
+    work = wl.make_workload("cfg1", shape=shape, dtype=dtype, batch=6, lo=1, hi=200, seed=120)
+    w = wl.make_weights(shape, dtype, "cuda", 121)
+    assert all((g.float() - 1).abs().max() > 0.05 for g in w["g1"] + w["g2"] + [w["gf"]])
+    base_case = H.GpuCase(work, weights=w, quant_mode=quant)
+    pool0 = base_case.pool_mem.clone()
+    base_case.step()
+    base = base_case.logits.clone()
+    for key, layer in (("g1", 0), ("g1", 1), ("g2", 0), ("g2", 1), ("gf", None)):
+        w2 = {k: (list(v) if isinstance(v, list) else v) for k, v in w.items()}
+        if layer is None:
+            w2[key] = (w[key].float() * 1.5).to(w[key].dtype)
+        else:
+            w2[key][layer] = (w[key][layer].float() * 1.5).to(w[key][layer].dtype)
+        c = H.GpuCase(work, weights=w2, quant_mode=quant)
+        c.pool_mem.copy_(pool0)
+        c.step()
+        assert (c.logits - base).abs().max() > 1e-3, f"{key}[{layer}] does not reach the logits"

@@ -1,6 +1,8 @@
 """GPU parity at the benchmark sizes, in the launch configuration bench.py times: the full
 8B-shaped step (batch 64 and 256, bf16 and QSUN) is run on the GPU and a sample of its
-requests is recomputed by the CPU oracle from exactly the bytes the GPU consumed."""
+requests is recomputed by the CPU oracle from exactly the bytes the GPU consumed.  The 14B-shaped
+configurations have a module of their own (test_gpu_parity_14b.py: their pools need the memory these
+fixtures hold)."""
 import numpy as np
 import pytest
 import torch
@@ -40,18 +42,18 @@ def quant8b(H):
     torch.cuda.empty_cache()
 
 
-def _sample_rows(work, k):
+def _sample_rows(work, k, must=()):
     order = np.argsort(work.seq_lens, kind="stable")
-    picks = {int(order[0]), int(order[-1])}
+    picks = {int(order[0]), int(order[-1])} | {int(r) for r in must}
     rng = np.random.default_rng(work.seed)
     while len(picks) < k:
         picks.add(int(rng.integers(0, work.batch)))
     return sorted(picks)
 
 
-def _sampled_parity(H, work, shared, k):
+def _sampled_parity(H, work, shared, k, must=()):
     case = H.GpuCase(work, shared=shared)
-    rows = _sample_rows(work, k)
+    rows = _sample_rows(work, k, must)
     H.say(f"{work.name} B={work.batch} quant={shared.quant is not None}: oracle on rows {rows} "
           f"(lengths {[int(work.seq_lens[r]) for r in rows]})")
     before_host, _, tabs, used = case.extract_pool(rows)
@@ -66,7 +68,9 @@ def _sampled_parity(H, work, shared, k):
     st = H.layout_strides(case.lay)
     st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
     mask = H.appended_mask(work.shape, st, before_host.size, tabs, work.seq_lens[rows])
-    off, total = H.check_appended_kv(case.pool_pages_now(used), ref["pool_after"], before_host, mask, "bf16")
+    after = case.pool_pages_now(used)
+    H.say(f"   appended K/V {H.appended_kv_stats(after, ref['pool_after'], mask)}")
+    off, total = H.check_appended_kv(after, ref["pool_after"], before_host, mask, "bf16")
     H.say(f"   near-tie rows {near}; appended K/V off by >=1 bf16 ulp: {off} of {total}")
     # every request's argmax equals the argmax of the GPU's own logits (lowest index on ties)
     all_logits = case.logits
@@ -90,23 +94,6 @@ def test_cfg4_qsun_batch64_sampled(H, quant8b):
 
 def test_cfg4_qsun_batch256_sampled(H, quant8b):
     _sampled_parity(H, wl.make_workload("cfg3"), quant8b, 4)
-
-
-def test_cfg5_14b_shape_sampled(H):
-    """14B shape (48 layers, 40 q / 8 kv heads, vocab 152064): the first 16 requests of the cfg5
-    draw (lengths up to 32768, ~50 GB of KV) in a pool without aliasing, dense and 4-bit; the
-    oracle recomputes 3 of them including the longest."""
-    work = wl.make_workload("cfg5", batch=16)
-    for quant in (None, "asym"):
-        H.say(f"building 14B-shaped weights quant={quant}")
-        sw = H.SharedWeights(wl.QWEN_14B, "bf16", wl.SEED_BASE + 105, quant_mode=quant)
-        if quant:
-            for k in sun.QUANT_KEYS:
-                sw.w[k] = None
-            torch.cuda.empty_cache()
-        case, rep = _sampled_parity(H, work, sw, 3)
-        del case, sw
-        torch.cuda.empty_cache()
 
 
 def test_cfg2_batch64_run_of_three_steps_sampled(H, dense8b):
@@ -301,5 +288,7 @@ def test_prefill_8b_shape(H, dense8b):
     H.orc.kv_ingest(expect, st, H.orc.bf16_bits(K), H.orc.bf16_bits(V), 0, tabs[0])
     probe = np.zeros(before.size, np.uint16)
     H.orc.kv_ingest(probe, st, np.ones(K.shape, np.uint16), np.ones(K.shape, np.uint16), 0, tabs[0])
-    off, total = H.check_appended_kv(case.pool_pages_now(used), expect, before, probe != 0, "bf16")
+    # entries of a position depend on the rounded entries of the positions before it: one-ulp differences feed
+    # forward, so the share of entries that differ is not bounded here the way it is for a single step
+    off, total = H.check_appended_kv(case.pool_pages_now(used), expect, before, probe != 0, "bf16", max_off_frac=0.6)
     H.say(f"   cache entries off by >=1 bf16 ulp: {off} of {total}")

@@ -59,4 +59,23 @@ def test_weights_are_seeded_and_shaped():
     w2 = wl.make_weights(wl.TINY, "f32", "cpu", 7)
     assert all((a == b).all() for a, b in zip(w["wg"], w2["wg"]))
     assert w["wg"][0].shape == (688, 256) and w["wd"][1].shape == (256, 688) and w["wlm"].shape == (1024, 256)
-    assert abs(float(w["wlm"].std()) - 0.02) < 2e-3 and float(w["g1"][0].min()) == 1.0
+    assert abs(float(w["wlm"].std()) - 0.02) < 2e-3
+    # gains are spread around 1 (a dropped or swapped gain must show), each vector its own draw
+    for g in w["g1"] + w["g2"] + [w["gf"]]:
+        assert abs(float(g.mean()) - 1.0) < 0.03 and 0.07 < float(g.std()) < 0.13
+    assert not (w["g1"][0] == w["g2"][0]).all() and not (w["g1"][0] == w["g1"][1]).all()
+
+
+def test_cfg5_forms_fit_one_gpu():
+    a, b = wl.make_workload("cfg5a"), wl.make_workload("cfg5b")
+    full = wl.make_workload("cfg5", n_pages=10 ** 6)
+    kv_tok = a.shape.kv_bytes_per_token()
+    assert a.batch == 128 and a.aliased and a.n_pages == wl.CFG5A_PAGES and np.array_equal(a.seq_lens, full.seq_lens)
+    assert a.n_pages * 2 * a.shape.kv_dim * 16 > 2 ** 31              # elements of one layer of the pool
+    need = wl.pages_needed(a.seq_lens)
+    tails = [int(a.page_tables[i, need[i] - 1]) for i in range(a.batch)]
+    hist = np.concatenate([a.page_tables[i, :need[i] - 1] for i in range(a.batch)])
+    assert len(set(tails)) == a.batch and not np.isin(tails, hist).any() and hist.min() >= 0 and hist.max() < a.n_pages
+    assert b.batch == 52 and not b.aliased and np.array_equal(b.seq_lens, full.seq_lens[:52])
+    assert b.n_pages * 16 * kv_tok <= wl.CFG5B_POOL_BYTES < (b.n_pages + 1) * 16 * kv_tok
+    assert int(wl.pages_needed(full.seq_lens[:53]).sum()) > b.n_pages >= int(need[:52].sum())
