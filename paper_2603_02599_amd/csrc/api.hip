@@ -628,16 +628,23 @@ static int validate_device_arrays(const KvPool& pool, int batch, const int32_t* 
     return SUN_OK;
 }
 
-static int total_chunks_from_host(const int32_t* host, int len_plus, int batch, int Hkv) {
-    if (!host) return -1;
-    long long tot = 0;
+// Chunk counts of the batch (all chunks; full chunks) from lengths the host knows, as the plan kernel computes
+// them on the device; -1 when the host has no lengths.
+struct ChunkHint {
+    int total, full;
+};
+static ChunkHint chunks_from_host(const int32_t* host, int len_plus, int batch, int max_pages, int Hkv) {
+    if (!host) return ChunkHint{-1, -1};
+    long long tot = 0, full = 0;
+    const long long cap = (long long)max_pages * kPageTokens;
     for (int b = 0; b < batch; ++b) {
-        const long long n = std::max<long long>((long long)host[b] + len_plus, 1);
+        const long long n = std::min(std::max<long long>((long long)host[b] + len_plus, 1), cap);
         int nf, ns, ch;
-        attn_chunking((int)std::min<long long>(n, 0x7fffffff), batch, Hkv, nf, ns, ch);
+        attn_chunking((int)n, batch, Hkv, nf, ns, ch);
         tot += nf + ns;
+        full += nf;
     }
-    return (int)std::min<long long>(tot, 0x7fffffff);
+    return ChunkHint{(int)std::min<long long>(tot, 0x7fffffff), (int)std::min<long long>(full, 0x7fffffff)};
 }
 
 static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_quant, int batch,
@@ -670,7 +677,7 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
     const bool prof = flags & SUN_PROFILE;
     const bool bf = c.act_dtype == SUN_BF16;
     const int H = c.hidden;
-    const int hint = total_chunks_from_host(seq_lens_host, 1, batch, c.n_kv_heads);
+    const ChunkHint hint = chunks_from_host(seq_lens_host, 1, batch, max_pages, c.n_kv_heads);
     float* logits = logits_out ? logits_out : ws.logits;
 
     {
@@ -710,8 +717,8 @@ static int step_impl(sun_kv_pool* pool_, const sun_weights* weights_, bool want_
         }
         {
             ProfScope p(prof, 0, st);
-            SUN_HIP_CHECK(launch_attn_split(pool, l, ws.plan, attn_q, page_tables, max_pages, seq_lens, 1, batch, hint,
-                                            !bf, st));
+            SUN_HIP_CHECK(launch_attn_split(pool, l, ws.plan, attn_q, page_tables, max_pages, seq_lens, 1, batch, hint.total,
+                                            hint.full, !bf, st));
         }
         {
             ProfScope p(prof, 1, st);
@@ -1071,9 +1078,9 @@ int sun_paged_attention(sun_kv_pool* pool_, int layer, int batch, const float* q
     const Workspace ws = carve(c, batch, max_pages, (char*)workspace);
     if (ws.bytes > workspace_bytes) return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, ws.bytes);
     hipStream_t st = (hipStream_t)stream;
-    const int hint = total_chunks_from_host(n_tokens_host, 0, batch, c.n_kv_heads);
+    const ChunkHint hint = chunks_from_host(n_tokens_host, 0, batch, max_pages, c.n_kv_heads);
     SUN_HIP_CHECK(launch_attn_plan(ws.plan, n_tokens, 0, batch, page_tables, max_pages, (int)pool.lay.n_pages, c.n_kv_heads, st));
-    SUN_HIP_CHECK(launch_attn_split(pool, layer, ws.plan, q, page_tables, max_pages, n_tokens, 0, batch, hint,
+    SUN_HIP_CHECK(launch_attn_split(pool, layer, ws.plan, q, page_tables, max_pages, n_tokens, 0, batch, hint.total, hint.full,
                                     c.act_dtype == SUN_F32, st));
     SUN_HIP_CHECK(launch_attn_combine(c, ws.plan, batch, out, nullptr, nullptr, st));
     return SUN_OK;

@@ -132,6 +132,7 @@ struct AttnArgs {
     const int32_t* records;
     float* partial;
     int len_plus, max_pages, batch, Hq, Hkv, n_pages;
+    int n_full_items, total_items;  // item counts when the host knows the lengths, else -1: read from the plan
     float qscale;           // log2(e) / sqrt(D)
 };
 
@@ -160,7 +161,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ int list_cursor;
     if (threadIdx.x == 0) list_cursor = 0;
     __syncthreads();
-    const int n_full = a.full_off[a.batch] * a.Hkv, total_items = a.chunk_off[a.batch] * a.Hkv;
+    const int n_full = a.n_full_items >= 0 ? a.n_full_items : a.full_off[a.batch] * a.Hkv;
+    const int total_items = a.total_items >= 0 ? a.total_items : a.chunk_off[a.batch] * a.Hkv;
     const int n_small = total_items - n_full;
     const int wg = blockIdx.x, nwg = gridDim.x;
     const int fq = n_full / nwg, fr = n_full % nwg;
@@ -457,7 +459,7 @@ static hipError_t launch_split_d(const AttnArgs& a, int G, int grid, hipStream_t
 
 hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan, const float* q,
                              const int32_t* page_tables, int max_pages, const int32_t* n_or_len, int len_plus,
-                             int batch, int total_chunks_hint, bool f32_exact, hipStream_t st) {
+                             int batch, int total_chunks_hint, int full_chunks_hint, bool f32_exact, hipStream_t st) {
     const sun_model_cfg& c = pool.cfg;
     const sun_kv_layout& L = pool.lay;
     const int D = c.head_dim, G = c.n_q_heads / c.n_kv_heads;
@@ -483,6 +485,7 @@ hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan
     a.Hkv = c.n_kv_heads;
     a.n_pages = (int)L.n_pages;
     a.qscale = kLog2e / sqrtf((float)D);
+    a.n_full_items = a.total_items = -1;
     const long long chunks = total_chunks_hint >= 0 ? total_chunks_hint : plan.max_chunks;
     const long long items = chunks * c.n_kv_heads;
     if (f32_exact) {
@@ -495,6 +498,12 @@ hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan
     }
     // persistent workgroups of 8 waves, one per compute unit (fewer only when there are fewer
     // items than waves)
+    // the item counts travel as kernel arguments when the host knows them: one dependent load less before a
+    // wave's first request for K and V
+    if (full_chunks_hint >= 0 && total_chunks_hint >= 0) {
+        a.n_full_items = full_chunks_hint * c.n_kv_heads;
+        a.total_items = total_chunks_hint * c.n_kv_heads;
+    }
     const int grid = (int)max(1LL, min((items + 7) / 8, 256LL));
     if (D == 64) return launch_split_d<64>(a, G, grid, st);
     if (D == 128) return launch_split_d<128>(a, G, grid, st);

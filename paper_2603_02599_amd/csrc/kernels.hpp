@@ -54,10 +54,11 @@ struct AttnPlan {           // device arrays inside the workspace
 size_t attn_max_chunks(int batch, int max_pages, int Hkv);
 hipError_t launch_attn_plan(const AttnPlan& plan, const int32_t* n_or_len, int len_plus, int batch,
                             const int32_t* page_tables, int max_pages, int n_pages, int Hkv, hipStream_t st);
-// n_tokens(i) = n_or_len[i] + len_plus.  q fp32 [batch, Hq*d].  total_chunks_hint < 0 if unknown.
+// n_tokens(i) = n_or_len[i] + len_plus.  q fp32 [batch, Hq*d].  The chunk counts of the batch (all chunks, full
+// chunks) when the host knows the lengths, else < 0.
 hipError_t launch_attn_split(const KvPool& pool, int layer, const AttnPlan& plan, const float* q,
                              const int32_t* page_tables, int max_pages, const int32_t* n_or_len, int len_plus,
-                             int batch, int total_chunks_hint, bool f32_exact, hipStream_t st);
+                             int batch, int total_chunks_hint, int full_chunks_hint, bool f32_exact, hipStream_t st);
 // out: fp32 row-major [batch, Hq*d] (out_f32) and/or the O projection's input: two-plane tiled bf16, or, with
 // qscale given, the fixed-point tile of a 4-bit projection and its (scale, integer sum) pairs.
 hipError_t launch_attn_combine(const sun_model_cfg& cfg, const AttnPlan& plan, int batch, float* out_f32,

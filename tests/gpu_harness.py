@@ -167,18 +167,24 @@ def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
 
 
 def check_appended_kv(gpu_after: np.ndarray, orc_after: np.ndarray, before: np.ndarray, mask: np.ndarray, dtype: str,
-                      abs_tol: float = None, max_off_frac: float = 0.15):
+                      abs_tol: float = None, max_off_frac: float = None, quant: bool = False):
     """Eq. 4: only the predicted slots change, and each stored value is the oracle's round-to-nearest-even
     bf16 value, or its neighbour: the projections that produce it differ from the oracle's fp64 ones by much
     less than a bf16 ulp, so the two roundings can fall apart by one ulp and no more.  An element that cancels
     to nearly zero is the exception (one bf16 ulp there is smaller than the error the path is allowed before the
-    rounding); it is held to abs_tol absolute instead: 2e-6 for the fp32 path (its accumulation error), 2e-3 for
-    the bf16 / 4-bit paths (a tenth of the logit tolerance: what reaches a deep layer's projection input
-    through the layers before it).  A store that does not round to nearest (truncation) would still be within one ulp everywhere
-    but off by one in about half of the elements, so the fraction of elements that differ at all is bounded
-    too (max_off_frac; measured: a few per cent at 32 to 48 layers, 0 to 3 elements on the fp32 path).
+    rounding); it is held to an absolute bound instead: 2e-6 for the fp32 path (its accumulation error); 2e-3
+    for the bf16 path (a tenth of the logit tolerance: what reaches a deep layer's projection input through the
+    layers before it; measured up to 1.1e-3 at 48 layers); 1e-2 + 5e-3|o| for the 4-bit path (half its logit
+    tolerance: there the projection inputs are rounded to 16-bit fixed point per group, and the measured
+    difference of a deep layer's entries reaches 8e-3, the same as its logits').  A store that does not round
+    to nearest (truncation) would still be within one ulp everywhere but off by one in about half of the
+    elements, so the fraction of elements that differ at all is bounded too (max_off_frac: 0.15, measured
+    0.4 to 3.5 per cent at 2 to 48 layers and 0 to 3 elements on the fp32 path; 0.3 for the 4-bit path, measured
+    up to 0.18 at 48 layers: the store is the same kernel on all three paths).
     Returns (#elements off by one ulp or more, #elements written)."""
     abs_tol = max(abs_tol or 0.0, 2e-6 if dtype == "f32" else 2e-3)   # a caller may widen the floor, not narrow it
+    if max_off_frac is None:
+        max_off_frac = 0.3 if quant else 0.15
     assert np.array_equal(gpu_after[~mask], before[~mask]), "GPU wrote outside the appended slots"
     assert np.array_equal(orc_after[~mask], before[~mask])
     a, b = gpu_after[mask].astype(np.int32), orc_after[mask].astype(np.int32)
@@ -188,7 +194,8 @@ def check_appended_kv(gpu_after: np.ndarray, orc_after: np.ndarray, before: np.n
 
     ulp = np.abs(ordered(a) - ordered(b))
     ga, oa = bf16_to_f64(gpu_after[mask]), bf16_to_f64(orc_after[mask])
-    bad = (ulp > 1) & (np.abs(ga - oa) > abs_tol)
+    bound = np.maximum(abs_tol, 1e-2 + 5e-3 * np.abs(oa)) if quant else abs_tol
+    bad = (ulp > 1) & (np.abs(ga - oa) > bound)
     assert not bad.any(), (f"appended K/V differs by {ulp[bad].max()} bf16 ulps ({np.abs(ga - oa)[bad].max():.2e} absolute) "
                            f"in {int(bad.sum())} of {int(mask.sum())} elements")
     off = int((ulp >= 1).sum())

@@ -39,7 +39,7 @@ def _full_step_parity(H, case, rows=None, tol=None):
     after = case.pool_pages_now(used)
     if work.dtype != "f32":
         H.say(f"   appended K/V {H.appended_kv_stats(after, ref['pool_after'], mask)}")
-    off, total = H.check_appended_kv(after, ref["pool_after"], before_host, mask, work.dtype)
+    off, total = H.check_appended_kv(after, ref["pool_after"], before_host, mask, work.dtype, quant=case.quant is not None)
     H.say(f"   next-token near-ties {near}; appended K/V elements off by >=1 bf16 ulp: {off} of {total}")
     return rep
 

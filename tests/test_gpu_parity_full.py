@@ -70,7 +70,7 @@ def _sampled_parity(H, work, shared, k, must=()):
     mask = H.appended_mask(work.shape, st, before_host.size, tabs, work.seq_lens[rows])
     after = case.pool_pages_now(used)
     H.say(f"   appended K/V {H.appended_kv_stats(after, ref['pool_after'], mask)}")
-    off, total = H.check_appended_kv(after, ref["pool_after"], before_host, mask, "bf16")
+    off, total = H.check_appended_kv(after, ref["pool_after"], before_host, mask, "bf16", quant=shared.quant is not None)
     H.say(f"   near-tie rows {near}; appended K/V off by >=1 bf16 ulp: {off} of {total}")
     # every request's argmax equals the argmax of the GPU's own logits (lowest index on ties)
     all_logits = case.logits

@@ -76,7 +76,7 @@ def _run_case(H, shape, dtype, lens, n_steps, quant=None, spare_pages=24, n_free
             nl = cur[i] + 1
             if nl // 16 < mp and final_tabs[i, nl // 16] >= 0 and nl <= ref["seq_lens"][i]:
                 cur[i] = nl
-    off, total = H.check_appended_kv(after, host, before, mask, dtype)
+    off, total = H.check_appended_kv(after, host, before, mask, dtype, quant=quant is not None)
     H.say(f"   run {dtype} quant={quant} steps={n_steps}: near-ties {near}; K/V off by one ulp: {off} of {total}; "
           f"pages taken {ref['free_head']}; status {ref['status']}")
     return ref, got

@@ -112,7 +112,7 @@ def _serve_and_compare(H, S, steps_per_call, eos=-1):
         H.orc.kv_ingest(probe, st, one, one, slot, np.array([page], np.int32))
         mask |= probe != 0
     assert not (mask & idle_elems).any()
-    off, n_written = H.check_appended_kv(after, host, S.before, mask, S.dtype, abs_tol=2e-5)
+    off, n_written = H.check_appended_kv(after, host, S.before, mask, S.dtype, abs_tol=2e-5, quant=S.quant is not None)
     H.say(f"   serve {S.dtype} quant={S.quant} eos={eos}: {cnt[6]} tokens, {cnt[5]} admitted, {cnt[4]} retired, status "
           f"{cnt[3]}; near-ties {near}; K/V off by one ulp: {off} of {n_written}")
     return got_t, got_r, ref
