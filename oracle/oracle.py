@@ -224,6 +224,32 @@ def decode_step(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_l
     return {"logits": logits, "next": nxt, "rowsums": rows, "attn": attn}
 
 
+def decode_step_peer(cfg: Cfg, params: Params, pool: Pool, peer: Pool, tokens, page_tables, seq_lens, model_ids,
+                     tol_abs: float, tol_rel: float = 0.0, mode: int = 0):
+    """One decode step next to another implementation's cache after the same step (`peer`, same page ids):
+    every new K/V value is computed and rounded here; where the peer's stored bf16 code is that rounding, its
+    neighbour, or within tol_abs + tol_rel |value| of it, the peer's code is what this step stores and attends
+    over (a stored code is a rounding decision that a correct fp32 implementation may take one step away),
+    otherwise its own.  Returns the dict of decode_step plus "peer": counts of entries (equal, adopted as
+    neighbour, adopted by value, kept own = peer rejected)."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    page_tables = np.ascontiguousarray(page_tables, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    model_ids = np.ascontiguousarray(model_ids, dtype=np.int32)
+    B = tokens.shape[0]
+    logits = np.empty((B, cfg.vocab), dtype=np.float64)
+    nxt = np.empty(B, dtype=np.int32)
+    stats = np.zeros(4, dtype=np.int64)
+    rc = lib().orc_decode_step_peer(C.byref(cfg), params.mats, C.byref(pool), C.c_int(B), _ptr(tokens),
+                                    _ptr(page_tables), C.c_int(page_tables.shape[1]), _ptr(seq_lens),
+                                    _ptr(model_ids), C.c_int(mode), _ptr(logits), _ptr(nxt), C.byref(peer),
+                                    C.c_double(tol_abs), C.c_double(tol_rel), _ptr(stats))
+    if rc != 0:
+        raise ValueError(f"orc_decode_step_peer failed with status {rc}")
+    return {"logits": logits, "next": nxt, "peer": {"equal": int(stats[0]), "neighbour": int(stats[1]),
+                                                    "by_value": int(stats[2]), "rejected": int(stats[3])}}
+
+
 def decode_run(cfg: Cfg, params: Params, pool: Pool, tokens, page_tables, seq_lens, model_ids, free_pages,
                free_head: int, n_steps: int, page_tokens: int = 16, mode: int = 0, forced_tokens=None,
                keep_logits: bool = False):

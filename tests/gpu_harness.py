@@ -214,3 +214,78 @@ def appended_kv_stats(gpu_after: np.ndarray, orc_after: np.ndarray, mask: np.nda
     return {"max_ulp": int(ulp.max()) if ulp.size else 0, "n_multi_ulp": int(multi.sum()),
             "max_abs_where_multi_ulp": float(d[multi].max()) if multi.any() else 0.0,
             "off_frac": float((ulp >= 1).mean()) if ulp.size else 0.0}
+
+
+def replay_steps_on_gpu_cache(case: DeviceCase, used: np.ndarray, after: np.ndarray, tabs: np.ndarray, lens0: np.ndarray,
+                              tokens_per_step, ids: np.ndarray, quant: bool = False):
+    """Several decode steps of the same requests, each compared on its own: step s of the oracle starts from the
+    cache the GPU holds (`after`: the compact copy of the used pages after all steps; step s reads positions
+    below lens0 + s only, which later steps do not touch), is fed the token the GPU was fed, computes position
+    lens0 + s next to the GPU's entry for it (decode_step_peer: see oracle_step_next_to_gpu_cache) and returns
+    its logits.  Each step is thereby held to the single-step bar.  tokens_per_step[s]: the tokens fed at
+    step s.  Returns (list of per-step logits, summed peer counts)."""
+    work = case.work
+    st = layout_strides(case.lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
+    ocfg, params = _orc().make_cfg(work.shape), case_oracle_params(case)
+    tol_abs, tol_rel, max_off = kv_bound(work.dtype, quant)
+    peer = _orc().make_pool(after, len(used), 16, st)
+    logits, tot = [], {"equal": 0, "neighbour": 0, "by_value": 0, "rejected": 0}
+    for s, toks in enumerate(tokens_per_step):
+        host = after.copy()
+        pool = _orc().make_pool(host, len(used), 16, st)
+        ln = (lens0 + s).astype(np.int32)
+        res = _orc().decode_step_peer(ocfg, params, pool, peer, np.asarray(toks, np.int32), tabs, ln, ids, tol_abs, tol_rel)
+        for k2, v in res["peer"].items():
+            tot[k2] += v
+        assert res["peer"]["rejected"] == 0, f"step {s}: {res['peer']}"
+        assert np.array_equal(host, after), "the oracle stored something else than the GPU's accepted entries"
+        logits.append(res["logits"])
+    n = sum(tot.values())
+    assert tot["neighbour"] + tot["by_value"] <= max_off * n + 3, f"{tot}: too many entries differ for a round-to-nearest store"
+    return logits, tot
+
+
+def kv_bound(dtype: str, quant: bool):
+    """(tol_abs, tol_rel, max share of entries that may differ at all) of the appended-K/V comparison: see
+    check_appended_kv."""
+    if dtype == "f32":
+        return 2e-6, 0.0, 0.15
+    return (1e-2, 5e-3, 0.3) if quant else (2e-3, 0.0, 0.15)
+
+
+def oracle_step_next_to_gpu_cache(case: DeviceCase, rows: Sequence[int], extracted, after: np.ndarray, tokens=None,
+                                  lens=None, ids=None, quant: bool = False):
+    """The oracle's step for the sampled requests, run after the GPU's from the cache as it was before
+    (`extracted` = case_extract_pool(case, rows) taken before the GPU step), next to the GPU's cache after its
+    step (`after`, the same pages): every new entry is computed and rounded by the oracle and compared with the
+    GPU's; a GPU entry that is that rounding, its neighbour, or within the bound is what the oracle then attends
+    over (a stored bf16 code is a rounding decision, and the fp32 path may legitimately take the other side of
+    a boundary; carried through 32 to 48 layers such a flip would otherwise show up in everything compared
+    after it, a request that puts much attention weight on its own new position being the worst case).  Asserts
+    that no entry is rejected, that the share of entries that differ at all stays under the bound (a store
+    that truncates instead of rounding would differ in half of them), and that nothing else in the cache
+    moved.  Returns the oracle's result dict (logits, next, peer counts)."""
+    work = case.work
+    rows = list(rows)
+    host, pool, tabs, used = extracted
+    before = host.copy()
+    st = layout_strides(case.lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(case.lay.k_page)
+    peer = _orc().make_pool(after, len(used), 16, st)
+    toks = (work.tokens if tokens is None else tokens)[rows]
+    ln = (work.seq_lens if lens is None else lens)[rows]
+    mi = (work.model_ids if ids is None else ids)[rows]
+    tol_abs, tol_rel, max_off = kv_bound(work.dtype, quant)
+    res = _orc().decode_step_peer(_orc().make_cfg(work.shape), case_oracle_params(case), pool, peer, toks, tabs, ln, mi,
+                                  tol_abs, tol_rel)
+    cnt = res["peer"]
+    total = sum(cnt.values())
+    mask = appended_mask(work.shape, st, after.size, tabs, ln)
+    assert total == int(mask.sum())
+    assert np.array_equal(after[~mask], before[~mask]), "GPU wrote outside the appended slots"
+    assert np.array_equal(host[~mask], before[~mask])
+    assert cnt["rejected"] == 0, f"{cnt['rejected']} of {total} appended K/V entries are neither the oracle's rounding, its neighbour, nor within the bound"
+    assert np.array_equal(host[mask], after[mask])
+    assert cnt["neighbour"] + cnt["by_value"] <= max_off * total + 3, f"{cnt} of {total}: too many entries differ for a round-to-nearest store"
+    return res

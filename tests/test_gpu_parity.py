@@ -484,3 +484,36 @@ def test_every_rmsnorm_gain_is_live(H, dtype, shape, quant):
         c.pool_mem.copy_(pool0)
         c.step()
         assert (c.logits - base).abs().max() > 1e-3, f"{key}[{layer}] does not reach the logits"
+
+
+@pytest.mark.parametrize("batch", [65, 100, 128, 129, 200, 256])
+def test_linear_op_bf16_above_64_rows_ragged_columns(H, batch):
+    """The projection kernel for more than 64 rows (a wave owns two 32-column strips, a workgroup up to four
+    such pairs) on widths that leave the last workgroup partly empty and the last wave with one strip only:
+    20 and 65 strips; every projection of the step, alone."""
+    from oracle import oracle as orc
+    shape = wl.Shape("ragged_cols", 2, 640, 5, 1, 128, 1152, 2080)
+    H.say(f"linear bf16 batch {batch}, ragged column counts")
+    cfg = sun.make_cfg(shape, "bf16")
+    w = wl.make_weights(shape, "bf16", H.DEV, 14, std=0.05)
+    W = sun.sun_weights_create(cfg, w)
+    ws = torch.empty(sun.sun_workspace_bytes(cfg, batch, 4), dtype=torch.uint8, device=H.DEV)
+    g = torch.Generator(device=H.DEV).manual_seed(1000 + batch)
+    wn = H.weights_to_np(w)
+    for mat, K, N in ((0, 640, 896), (1, 640, 640), (2, 640, 1152), (3, 1152, 640), (4, 640, 2080)):
+        x = torch.randn((batch, K), device=H.DEV, generator=g)
+        out = torch.full((batch, N), float("nan"), device=H.DEV)
+        sun.sun_linear(W, 1, mat, x, out, ws)
+        torch.cuda.synchronize()
+        xr = x.double().cpu().numpy()
+        lin = lambda key: orc.linear(orc.dense_mat(wn[key][1] if isinstance(wn[key], list) else wn[key]), xr)
+        if mat == 0:
+            want = np.concatenate([lin("wq"), lin("wk"), lin("wv")], axis=1)
+        elif mat == 2:
+            gate, up = lin("wg"), lin("wu")
+            want = gate / (1 + np.exp(-gate)) * up
+        else:
+            want = lin({1: "wo", 3: "wd", 4: "wlm"}[mat])
+        got = out.double().cpu().numpy()
+        tol = 1e-2 * np.abs(want) + 2e-3 if mat == 2 else 2e-4 + 1e-5 * np.abs(want)   # mat 2 output is bf16
+        assert np.all(np.abs(got - want) <= tol), f"mat {mat}: max diff {np.abs(got - want).max():.3e}"

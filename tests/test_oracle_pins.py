@@ -418,3 +418,73 @@ def test_bf16_and_f32_weights_are_read_at_stored_value(orc):
     X = rng.normal(size=(2, 8))
     want = X @ orc.bf16_values(bits).reshape(5, 8).T
     assert np.abs(orc.linear(orc.dense_mat(bits.reshape(5, 8)), X) - want).max() < 1e-14
+
+
+def test_step_next_to_a_peer_cache_adopts_valid_neighbours_only(orc):
+    """decode_step_peer: the step stores, and attends over, the peer's bf16 code where that code is its own
+    rounding, the neighbouring value, or within the given bound of it; its own rounding otherwise.
+    Pinned by (a) a peer that is the plain step's own cache (nothing changes, logits bit-identical),
+    (b) a one-layer model whose peer entries are nudged: the stored entries follow the rule element by
+    element, and the logits equal what the oracle's primitives (norm, projections, rotation, paged attention
+    over the pool as stored) give when chained by hand, i.e. attention really read the adopted entries."""
+    shape = MiniShape(n_layers=1)
+    rng = np.random.default_rng(61)
+    w = random_weights(shape, rng, dtype=np.float32)
+    cfg, params = orc.make_cfg(shape), orc.params_from_arrays(w)
+    lens = [0, 5, 16, 33]
+    b = _random_batch(orc, shape, rng, lens)
+    before = b["base"].copy()
+    plain = orc.decode_step(cfg, params, b["pool"], b["toks"], b["tables"], b["lens"], b["ids"])
+    own_after = b["base"].copy()
+    written = own_after != before
+    st = orc.default_strides(shape, b["n_pages"], PT)
+    # (a) the peer is the plain step's result
+    b["base"][:] = before
+    peer_base = own_after.copy()
+    peer = orc.make_pool(peer_base, b["n_pages"], PT, st)
+    r = orc.decode_step_peer(cfg, params, b["pool"], peer, b["toks"], b["tables"], b["lens"], b["ids"], tol_abs=0.0)
+    n_new = len(lens) * 2 * shape.n_kv_heads * shape.head_dim
+    assert r["peer"] == {"equal": n_new, "neighbour": 0, "by_value": 0, "rejected": 0}
+    assert np.array_equal(r["logits"], plain["logits"]) and np.array_equal(b["base"], own_after)
+    # (b) nudge the peer's new entries: +1 code (neighbour), +3 codes on a large value (rejected), +3 codes on a value
+    # tiny enough to be within tol_abs (adopted by value)
+    def ordered(u):
+        return np.where(u & 0x8000, -(u & 0x7FFF).astype(np.int64), (u & 0x7FFF).astype(np.int64))
+    def from_ordered(o):
+        return np.where(o < 0, 0x8000 | (-o), o).astype(np.uint16)
+    idx = np.flatnonzero(written)
+    vals = (own_after[idx].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    rng2 = np.random.default_rng(62)
+    pick = rng2.permutation(len(idx))
+    nb, far = pick[:40], pick[40:60]
+    peer_base[:] = own_after
+    peer_base[idx[nb]] = from_ordered(ordered(own_after[idx[nb]]) + rng2.choice([-1, 1], size=len(nb)))
+    peer_base[idx[far]] = from_ordered(ordered(own_after[idx[far]]) + 3 * rng2.choice([-1, 1], size=len(far)))
+    tol = 1e-3
+    far_vals = (peer_base[idx[far]].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    by_value = np.abs(far_vals - vals[far]) <= tol
+    assert by_value.any() and (~by_value).any(), "the draw should hold both kinds"
+    b["base"][:] = before
+    r = orc.decode_step_peer(cfg, params, b["pool"], peer, b["toks"], b["tables"], b["lens"], b["ids"], tol_abs=tol)
+    assert r["peer"] == {"equal": n_new - 60, "neighbour": 40, "by_value": int(by_value.sum()), "rejected": int((~by_value).sum())}
+    expect = peer_base.copy()
+    expect[idx[far[~by_value]]] = own_after[idx[far[~by_value]]]          # rejected: the step's own rounding stays
+    assert np.array_equal(b["base"], expect)
+    assert not np.array_equal(r["logits"], plain["logits"])
+    # the chain by hand over the pool as stored
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    for i, L in enumerate(lens):
+        x0 = f64(w["embed"][b["toks"][i]])
+        h = orc.rmsnorm(x0, f64(w["g1"][0]), shape.rms_eps)
+        q = orc.linear(orc.dense_mat(np.ascontiguousarray(w["wq"][0])), h[None])[0].reshape(shape.n_q_heads, shape.head_dim)
+        qr = np.concatenate([orc.rope(q[hh], L, shape.rope_base) for hh in range(shape.n_q_heads)])
+        a, _ = orc.attention_paged(cfg, b["pool"], 0, b["tables"][i], qr, L + 1)
+        x1 = x0 + orc.linear(orc.dense_mat(np.ascontiguousarray(w["wo"][0])), a[None])[0]
+        h2 = orc.rmsnorm(x1, f64(w["g2"][0]), shape.rms_eps)
+        gate = orc.linear(orc.dense_mat(np.ascontiguousarray(w["wg"][0])), h2[None])[0]
+        up = orc.linear(orc.dense_mat(np.ascontiguousarray(w["wu"][0])), h2[None])[0]
+        u = np.array([orc.silu(float(g)) for g in gate]) * up
+        x2 = x1 + orc.linear(orc.dense_mat(np.ascontiguousarray(w["wd"][0])), u[None])[0]
+        hf = orc.rmsnorm(x2, f64(w["gf"]), shape.rms_eps)
+        logits = orc.linear(orc.dense_mat(np.ascontiguousarray(w["wlm"])), hf[None])[0]
+        assert np.abs(logits - r["logits"][i]).max() < 1e-11
