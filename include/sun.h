@@ -465,6 +465,25 @@ int sun_paged_attention(sun_kv_pool* pool, int layer, int batch, const float* q,
                         size_t workspace_bytes, void* stream);
 
 /*
+ * sun_paged_attention for callers that cannot allocate or hand over device memory for a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * the workspace, same kernels, same result.  The plan arrays, item records and split partials live in an
+ * array inside the library instead (sun_paged_attention_static_limit() bytes, 16 MiB, one copy on every GPU
+ * the library runs on, held until the process ends); the call allocates nothing, on the host or the device.
+ *   sun_paged_attention_static_bytes(cfg, batch, max_pages): the scratch such a call needs; a call that needs
+ *   more than the limit fails with SUN_ERR_WORKSPACE before anything is enqueued (use sun_paged_attention).
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents (nothing in it has to be
+ * cleared: every entry a kernel reads has been written by an earlier kernel of the same call).  Two calls
+ * whose kernels overlap on one GPU (different streams, no ordering) race on it; calls on one stream are safe.
+ * Errors: SUN_ERR_NULL, SUN_ERR_SHAPE, SUN_ERR_WORKSPACE (over the limit), SUN_ERR_HIP.
+ */
+size_t sun_paged_attention_static_limit(void);
+size_t sun_paged_attention_static_bytes(const sun_model_cfg* cfg, int batch, int max_pages);
+int sun_paged_attention_static(sun_kv_pool* pool, int layer, int batch, const float* q,
+                               const int32_t* page_tables, int max_pages, const int32_t* n_tokens,
+                               const int32_t* n_tokens_host, float* out, void* stream);
+
+/*
  * out[b, n] = sum_k W[n, k] x[b, k]  through the projection kernels of the step.
  *   mat: index into the projection list of layer `layer`: 0 = [Wq;Wk;Wv] stacked,
  *        1 = Wo, 2 = fused silu(Wg x) * (Wu x) (out has ffn columns), 3 = Wd, 4 = lm_head

@@ -27,7 +27,8 @@ EXPORTS = [
     "sun_qweights_pack_bytes", "sun_qweights_create", "sun_quantize_w4",
     "sun_workspace_bytes", "sun_decode_step", "sun_qdecode_step", "sun_decode_run",
     "sun_prefill_workspace_bytes", "sun_prefill", "sun_serve_workspace_bytes", "sun_decode_serve",
-    "sun_paged_attention", "sun_linear",
+    "sun_paged_attention", "sun_paged_attention_static", "sun_paged_attention_static_bytes",
+    "sun_paged_attention_static_limit", "sun_linear",
     "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
 ]
 
@@ -95,7 +96,8 @@ def lib() -> C.CDLL:
         L.sun_last_error.restype = C.c_char_p
         L.sun_version.restype = C.c_char_p
         for f in ("sun_kv_pool_bytes", "sun_weights_pack_bytes", "sun_qweights_pack_bytes", "sun_workspace_bytes",
-                  "sun_prefill_workspace_bytes", "sun_serve_workspace_bytes"):
+                  "sun_prefill_workspace_bytes", "sun_serve_workspace_bytes", "sun_paged_attention_static_bytes",
+                  "sun_paged_attention_static_limit"):
             getattr(L, f).restype = C.c_size_t
         L.sun_kv_pool_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int64, C.c_int]
         L.sun_kv_pool_create.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_size_t, C.c_int, C.c_int,
@@ -132,6 +134,10 @@ def lib() -> C.CDLL:
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint]
         L.sun_paged_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sun_paged_attention_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sun_paged_attention_static_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int]
+        L.sun_paged_attention_static_limit.argtypes = []
         L.sun_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
         L.sun_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -438,6 +444,21 @@ def sun_paged_attention(pool, layer: int, q, page_tables, n_tokens, out, workspa
     _check(lib().sun_paged_attention(pool.handle, layer, batch, _p(q), _p(page_tables), max_pages, _p(n_tokens),
                                      host_ptr, _p(out), _p(workspace), workspace.numel() * workspace.element_size(),
                                      _stream(stream)))
+
+
+def sun_paged_attention_static(pool, layer: int, q, page_tables, n_tokens, out, n_tokens_host=None, stream=None):
+    batch, max_pages = page_tables.shape
+    keep, host_ptr = _host_i32(n_tokens_host)
+    _check(lib().sun_paged_attention_static(pool.handle, layer, batch, _p(q), _p(page_tables), max_pages, _p(n_tokens),
+                                            host_ptr, _p(out), _stream(stream)))
+
+
+def sun_paged_attention_static_bytes(cfg, batch: int, max_pages: int) -> int:
+    return int(lib().sun_paged_attention_static_bytes(C.byref(cfg), batch, max_pages))
+
+
+def sun_paged_attention_static_limit() -> int:
+    return int(lib().sun_paged_attention_static_limit())
 
 
 def sun_linear(weights, layer: int, mat: int, x, out, workspace, stream=None):

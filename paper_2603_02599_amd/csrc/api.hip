@@ -198,6 +198,33 @@ struct ProfScope {
 
 using namespace sun;
 
+// ---------------------------------------------------------------- library-owned scratch
+// Scratch of sun_paged_attention_static: the plan arrays, item records and split partials that
+// sun_paged_attention takes from the caller's workspace.  One copy per GPU, held until the process ends.
+// In host code the array's name is only a stand-in for the symbol; the device address comes from
+// hipGetSymbolAddress, once per device, and is what the kernels and carve() are given.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_static_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_static_scratch_mu;
+
+// device address of this GPU's copy of the scratch array (looked up on the first call on each device)
+static int static_scratch(void** out) {
+    int dev = -1;
+    SUN_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return sun::set_error("device %d outside [0, %d)", dev, kMaxDevices), SUN_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_static_scratch_mu);
+    if (!g_static_scratch_ptr[dev]) {
+        void* p = nullptr;
+        SUN_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+        if (!p || (uintptr_t)p % 256) return sun::set_error("scratch symbol has no usable device address"), SUN_ERR_HIP;
+        g_static_scratch_ptr[dev] = p;
+    }
+    *out = g_static_scratch_ptr[dev];
+    return SUN_OK;
+}
+
 extern "C" {
 
 const char* sun_last_error(void) { return g_err; }
@@ -1079,6 +1106,59 @@ int sun_paged_attention(sun_kv_pool* pool_, int layer, int batch, const float* q
     if (ws.bytes > workspace_bytes) return fail(SUN_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, ws.bytes);
     hipStream_t st = (hipStream_t)stream;
     const ChunkHint hint = chunks_from_host(n_tokens_host, 0, batch, max_pages, c.n_kv_heads);
+    SUN_HIP_CHECK(launch_attn_plan(ws.plan, n_tokens, 0, batch, page_tables, max_pages, (int)pool.lay.n_pages, c.n_kv_heads, st));
+    SUN_HIP_CHECK(launch_attn_split(pool, layer, ws.plan, q, page_tables, max_pages, n_tokens, 0, batch, hint.total, hint.full,
+                                    c.act_dtype == SUN_F32, st));
+    SUN_HIP_CHECK(launch_attn_combine(c, ws.plan, batch, out, nullptr, nullptr, st));
+    return SUN_OK;
+}
+
+// The part of the workspace the attention sub-step uses: plan arrays, item records, split partials.
+static Workspace carve_attention(const sun_model_cfg& c, int batch, int max_pages, char* base) {
+    Workspace w{};
+    size_t off = 0;
+    auto take = [&](size_t n) {
+        char* p = base ? base + off : nullptr;
+        off += align_up(n);
+        return (void*)p;
+    };
+    const size_t mc = attn_max_chunks(batch, max_pages, c.n_kv_heads);
+    w.plan.max_chunks = (int)std::min<size_t>(mc, 0x7fffffff);
+    w.plan.chunk_off = (int32_t*)take((size_t)(batch + 1) * 4);
+    w.plan.full_off = (int32_t*)take((size_t)(batch + 1) * 4);
+    w.plan.small_off = (int32_t*)take((size_t)(batch + 1) * 4);
+    w.plan.records = (int32_t*)take(mc * c.n_kv_heads * 24 * 4);
+    w.plan.partial = (float*)take(mc * c.n_q_heads * (c.head_dim + 2) * 4);
+    w.bytes = off;
+    return w;
+}
+
+size_t sun_paged_attention_static_limit(void) { return kStaticScratchBytes; }
+
+size_t sun_paged_attention_static_bytes(const sun_model_cfg* cfg, int batch, int max_pages) {
+    if (!cfg || batch < 1 || max_pages < 1 || check_cfg(cfg) != SUN_OK) return 0;
+    return carve_attention(*cfg, batch, max_pages, nullptr).bytes;
+}
+
+int sun_paged_attention_static(sun_kv_pool* pool_, int layer, int batch, const float* q, const int32_t* page_tables,
+                               int max_pages, const int32_t* n_tokens, const int32_t* n_tokens_host, float* out,
+                               void* stream) {
+    if (!pool_ || !q || !page_tables || !n_tokens || !out) return fail(SUN_ERR_NULL, "NULL argument");
+    KvPool& pool = *(KvPool*)pool_;
+    const sun_model_cfg& c = pool.cfg;
+    if (layer < 0 || layer >= c.n_layers) return fail(SUN_ERR_SHAPE, "layer out of range");
+    if (batch < 1 || batch > 1024 || max_pages < 1) return fail(SUN_ERR_SHAPE, "batch must be in [1,1024], max_pages >= 1");
+    const size_t need = carve_attention(c, batch, max_pages, nullptr).bytes;
+    if (need > kStaticScratchBytes)
+        return fail(SUN_ERR_WORKSPACE, "batch %d x %d pages needs %zu bytes of scratch, the library's array holds %zu: "
+                    "use sun_paged_attention with a workspace", batch, max_pages, need, kStaticScratchBytes);
+    void* base = nullptr;
+    if (int rc = static_scratch(&base)) return rc;
+    const Workspace ws = carve_attention(c, batch, max_pages, (char*)base);
+    hipStream_t st = (hipStream_t)stream;
+    const ChunkHint hint = chunks_from_host(n_tokens_host, 0, batch, max_pages, c.n_kv_heads);
+    // nothing in the scratch has to start at zero: the plan kernels write every prefix sum and every record the
+    // split kernel reads, the split kernel every partial the combine kernel reads
     SUN_HIP_CHECK(launch_attn_plan(ws.plan, n_tokens, 0, batch, page_tables, max_pages, (int)pool.lay.n_pages, c.n_kv_heads, st));
     SUN_HIP_CHECK(launch_attn_split(pool, layer, ws.plan, q, page_tables, max_pages, n_tokens, 0, batch, hint.total, hint.full,
                                     c.act_dtype == SUN_F32, st));
