@@ -24,15 +24,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "int8": 5000.0}   # dense matrix-core peaks of the MI355X
 
-# HBM bytes per attention launch from two counter runs (FETCH_SIZE, then WRITE_SIZE) of this script under
-# the profiler, each scaled by what the same counter reads for a plain 1 GiB copy (--copy-calibration):
-# FETCH_SIZE reports 0.5 of the bytes read, WRITE_SIZE 1.0 of the bytes written.  Keyed by workload; the
-# summaries with the commands are under profiles/.  Workloads that were not counted report null.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2": (298542.9 / 0.5 + 14060.5 / 1.0) * 1024.0,
-    "cfg3": (960163.0 / 0.5 + 49223.1 / 1.0) * 1024.0,
-}
+
+def measured_traffic_bytes(workload: str, quant):
+    """HBM bytes per attention launch from the counter summaries under profiles/ (two rocprofv3 --pmc runs of
+    this script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy:
+    --copy-calibration).  The summary of a workload carries a line `traffic_bytes_per_launch: <bytes>`; a
+    workload (or weight format) that was not counted reports null.  Not a reading of this run."""
+    name = f"attn_split_{workload}{'_qsun' if quant else ''}_hbm_traffic_pmc.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def w4_bytes_per_weight(quant) -> float:
@@ -81,21 +89,43 @@ def build_workload(name: str):
 
 
 def cpu_baseline(case, work, n_sample: int):
-    """Times the oracle (as it stands) on n_sample requests spread over the length distribution."""
-    tests = os.path.join(ROOT, "tests")
-    if tests not in sys.path:
-        sys.path.insert(0, tests)
-    import gpu_harness as H   # the tests' oracle mirrors: the only leg of bench.py that touches the oracle
+    """Times the oracle (as it stands) on n_sample requests spread over the length distribution.  The only
+    part of this script that touches the oracle: it hands it host copies of the weights and of the sampled
+    requests' cache pages."""
+    import torch
     from oracle import oracle as orc
+    from paper_2603_02599_amd.device_case import layout_strides, to_np, weights_to_np
     order = np.argsort(work.seq_lens)
     rows = sorted({int(order[int(round(q * (work.batch - 1)))]) for q in np.linspace(0, 1, n_sample)})
-    params = H.case_oracle_params(case)
-    host, pool, tabs, used = H.case_extract_pool(case, rows)
+    wnp = weights_to_np(case.w)
+    qnp = None
+    if case.quant is not None:
+        def triple(t):
+            q, sc, z = t
+            scn = to_np(sc)
+            return to_np(q), scn, (to_np(z) if z is not None else np.full(scn.shape, 0x4800, np.uint16))
+        qnp = {k: [triple(t) for t in v] for k, v in case.quant.items()}
+        for k, v in qnp.items():        # the dense sources of the quantised matrices have left the device
+            if k not in wnp:
+                wnp[k] = [np.empty((0, 2 * t[0].shape[1]), np.float32) for t in v]
+    params = orc.params_from_arrays(wnp, qnp)
+    # compact host copy of the pages the sampled requests reference, same in-page layout
+    lay = case.lay
+    tabs = work.page_tables[rows]
+    used = np.unique(tabs[tabs >= 0])
+    remap = np.full(int(lay.n_pages), -1, np.int64)
+    remap[used] = np.arange(len(used))
+    new_tabs = np.where(tabs >= 0, remap[np.maximum(tabs, 0)], -1).astype(np.int32)
+    view = case.pool_mem.view(work.shape.n_layers, int(lay.n_pages), int(lay.k_page))
+    host = to_np(view.index_select(1, torch.from_numpy(used.astype(np.int64)).to(view.device)).contiguous()).reshape(-1).copy()
+    st = layout_strides(lay)
+    st["k_layer"] = st["v_layer"] = len(used) * int(lay.k_page)
+    pool = orc.make_pool(host, len(used), 16, st)
     ocfg = orc.make_cfg(work.shape)
 
     def timed():
         t0 = time.perf_counter()
-        orc.decode_step(ocfg, params, pool, work.tokens[rows], tabs, work.seq_lens[rows], work.model_ids[rows])
+        orc.decode_step(ocfg, params, pool, work.tokens[rows], new_tabs, work.seq_lens[rows], work.model_ids[rows])
         return time.perf_counter() - t0
 
     dt = timed()
@@ -260,8 +290,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2",
-                    help="cfg2 (default, the headline configuration), cfg1 (tiny fp32), cfg3, cfg5a, cfg5b, small, or b<batch>x<len>")
+    ap.add_argument("--workload", default=None,
+                    help="one workload only: cfg2 (the headline configuration), cfg1 (tiny fp32), cfg3, cfg5a, cfg5b, small, or "
+                         "b<batch>x<len>.  Default (step mode): cfg2 and cfg3, each with bf16 and with 4-bit weights, in one "
+                         "process; the JSON line is cfg2/bf16 and carries the other three under \"legs\"")
     ap.add_argument("--quant", default=None, choices=[None, "asym", "sym", "sym_noz"],
                     help="4-bit group-128 decode weights: affine, symmetric, or symmetric without stored zero points")
     ap.add_argument("--cpu-sample", type=int, default=24, help="requests the oracle is timed on (0 = skip); 24 are about 10 s of CPU work")
@@ -283,6 +315,9 @@ def main():
                     help="instead of one workload: time the decode step of the --workload shape over a grid of batch "
                          "sizes and cache lengths (all requests of a point equally long) and print one JSON table; "
                          "this is the input of paper_2603_02599_amd/placement.py")
+    ap.add_argument("--hbm-read-probe", action="store_true",
+                    help="only time a kernel that reads 8 GiB and does nothing else (address order, shuffled 4 KiB blocks): the "
+                         "practical ceiling the HBM-bound kernels are compared with")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (known size) to calibrate FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -290,10 +325,47 @@ def main():
         import torch
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(5):
             dst.copy_(src)
+        e1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
+        ms = e0.elapsed_time(e1) / 5
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 6, "ms_per_copy": ms,
+                          "read_plus_write_GBps": 2.0 * (1 << 30) / (ms * 1e-3) / 1e9}))
+        return
+    if args.hbm_read_probe:
+        # the yardstick: what a kernel that only reads reaches on this device (sun_hbm_read_probe), over buffers far
+        # larger than the 256 MB memory-side cache, in address order and in shuffled 4 KiB blocks (the size of one
+        # (page, head) K or V block of the pool)
+        import torch
+        from paper_2603_02599_amd import binding as sun
+        sun.lib()
+        nbytes = 8 << 30
+        src = torch.empty(nbytes // 4, dtype=torch.int32, device="cuda")
+        src.random_(0, 1 << 30)
+        perm = torch.randperm(nbytes // 4096, device="cuda").to(torch.int32)
+        out = {"what": "read-only streaming kernel", "bytes": nbytes, "hbm_peak_GBps": HBM_PEAK_GBS, "runs": []}
+        for block, order, wgs in ((4096, None, 2048), (4096, perm, 2048), (4096, perm, 1024), (4096, perm, 4096),
+                                  (65536, None, 2048)):
+            sink = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
+            p = order if block == 4096 else None
+            for _ in range(2):
+                sun.sun_hbm_read_probe(src, block, p, wgs, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                sun.sun_hbm_read_probe(src, block, p, wgs, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            out["runs"].append({"block_bytes": block, "order": "shuffled" if p is not None else "address", "workgroups": wgs,
+                                "ms": ms, "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        print(json.dumps(out))
         return
     if args.gpus != 1:
         raise SystemExit("bench.py: this build measures one GPU only (one decode worker holds a full copy of the "
@@ -304,6 +376,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     from paper_2603_02599_amd import device_case as H   # device buffers and handles; nothing of the oracle
 
+    all_legs = (args.workload is None and args.mode == "step" and not args.ingest_tokens and not args.prefill_tokens
+                and not args.sweep_step_times)
+    if not all_legs and args.workload is None:
+        args.workload = "cfg2"
     if args.ingest_tokens > 0:
         from paper_2603_02599_amd import workloads as wl
         shape = {"cfg2": wl.LLAMA_8B, "cfg3": wl.LLAMA_8B, "cfg5a": wl.QWEN_14B, "cfg5b": wl.QWEN_14B, "small": wl.SMALL128}[args.workload]
@@ -397,37 +473,88 @@ def main():
         return
     if args.mode == "serve":
         return bench_serve(args, sun, H)
-    work, desc = build_workload(args.workload)
-    shape = work.shape
     if args.mode == "run":
-        # room in the page tables for the tokens generated during warm-up and the timed run
-        grow = args.steps + args.warmup + 8  # + a short per-kernel timing pass after the timed run
-        cols = (int(work.seq_lens.max()) + grow) // 16 + 1
-        wide = np.full((work.batch, cols), -1, np.int32)
-        wide[:, :work.max_pages] = work.page_tables
-        referenced = np.zeros(work.n_pages, bool)
-        referenced[work.page_tables[work.page_tables >= 0]] = True
-        free_list = np.flatnonzero(~referenced).astype(np.int32)
-        assert len(free_list) >= work.batch * (grow // 16 + 1), "pool has too few spare pages for this output length"
-        work.page_tables = wide
+        return bench_run_setup(args, sun, H)
+    if args.workload is not None:
+        print(json.dumps(step_leg(args, sun, H, args.workload, args.quant, None, args.cpu_sample)))
+        return
+    # Default: the whole metric in one process.  The headline line is cfg2 with bf16 weights; the same step with
+    # 4-bit weights, and both at batch 256 (cfg3), ride along under "legs", each with its own roofline.  The
+    # two weight sets are built once and shared by the workloads.
+    from paper_2603_02599_amd import workloads as wl
+    legs = {}
+    head = None
+    for quant in (None, args.quant or "asym"):
+        shared = H.DeviceWeights(wl.LLAMA_8B, "bf16", wl.SEED_BASE + 3, quant_mode=quant)
+        if quant:
+            for k in sun.QUANT_KEYS:
+                shared.w[k] = None
+            torch.cuda.empty_cache()
+        for name in ("cfg2", "cfg3"):
+            first = name == "cfg2" and quant is None
+            leg = step_leg(args, sun, H, name, quant, shared, args.cpu_sample if first else 0)
+            if first:
+                head = leg
+            else:
+                legs[f"{name}_{'qsun' if quant else 'bf16'}"] = {k: leg[k] for k in (
+                    "value", "unit", "ms_per_step", "step_ms_p10_p50_p90", "dtype", "config", "algorithmic_GB_per_step",
+                    "step_GBps", "step_frac_of_hbm_peak", "roofline", "kernels")}
+        del shared
+        torch.cuda.empty_cache()
+    b16, q4 = head["ms_per_step"], legs["cfg2_qsun"]["ms_per_step"]
+    head["legs"] = legs
+    head["qsun_step_time_gain"] = {"cfg2": 1.0 - q4 / b16, "cfg3": 1.0 - legs["cfg3_qsun"]["ms_per_step"] / legs["cfg3_bf16"]["ms_per_step"]}
+    print(json.dumps(head))
+
+
+def projection_figures(shape, work, quant, kernels):
+    """Per projection: weight bytes per second, and the method's arithmetic (2 N K per row: the second activation
+    plane of the kernels is not counted) per second against the matrix-core peak of the operand type the kernel
+    multiplies in; `bound` names the larger of the two floors (weights once from HBM at 8 TB/s, arithmetic at
+    the matrix-core peak)."""
+    el = 4.0 if work.dtype == "f32" else 2.0
+    b_w = w4_bytes_per_weight(quant) if quant else el
+    H_, QD, KD, F = shape.hidden, shape.q_dim, shape.kv_dim, shape.ffn
+    mats = {"qkv_proj": ((QD + 2 * KD), H_, b_w, quant), "o_proj": (H_, QD, b_w, quant), "gate_up_proj": (2 * F, H_, b_w, quant),
+            "down_proj": (H_, F, b_w, quant), "lm_head": (shape.vocab, H_, el, None)}
+    for k, (N, K, bpw, q) in mats.items():
+        if k not in kernels:
+            continue
+        t = kernels[k]["avg_us"] * 1e-6
+        nbytes, flops = N * K * bpw, 2.0 * work.batch * N * K
+        peak = MFMA_PEAK_TFLOPS["int8" if q else "bf16"]
+        kernels[k]["weight_GBps"] = nbytes / t / 1e9
+        kernels[k]["frac_of_hbm_peak"] = nbytes / t / 1e9 / HBM_PEAK_GBS
+        if work.dtype != "f32":
+            kernels[k]["TFLOPs"] = flops / t / 1e12
+            kernels[k]["mfma_operands"] = "int8" if q else "bf16"
+            kernels[k]["frac_of_mfma_peak"] = flops / t / 1e12 / peak
+            kernels[k]["bound"] = "mfma" if flops / (peak * 1e12) > nbytes / (HBM_PEAK_GBS * 1e9) else "hbm"
+
+
+def step_leg(args, sun, H, workload, quant, shared, cpu_sample):
+    """Times K independent calls of the decode step on one resident workload; returns the JSON object."""
+    import torch
+    work, desc = build_workload(workload)
+    shape = work.shape
     t_setup = time.perf_counter()
-    case = H.DeviceCase(work, quant_mode=args.quant)
-    if args.quant:  # the dense projection sources are no longer needed on the device
-        for k in sun.QUANT_KEYS:
-            case.w[k] = None
+    if shared is not None:
+        case = H.DeviceCase(work, shared=shared)
+    else:
+        case = H.DeviceCase(work, quant_mode=quant)
+        if quant:  # the dense projection sources are no longer needed on the device
+            for k in sun.QUANT_KEYS:
+                case.w[k] = None
     torch.cuda.synchronize()
-    print(f"[bench] setup {time.perf_counter() - t_setup:.1f} s; pool {work.n_pages} pages, "
+    print(f"[bench] {workload} quant={quant}: setup {time.perf_counter() - t_setup:.1f} s; pool {work.n_pages} pages, "
           f"{work.kv_tokens_read} KV tokens read per layer-step", file=sys.stderr, flush=True)
     host_lens = work.seq_lens.copy()
-    fn = sun.sun_qdecode_step if args.quant else sun.sun_decode_step
+    fn = sun.sun_qdecode_step if quant else sun.sun_decode_step
 
     def one_step(flags=0):
         # seq_lens is held fixed so every step overwrites the same slot and moves identical bytes
         fn(case.pool, case.weights, case.tokens, case.tables, case.lens, case.ids, case.logits, case.next, case.ws,
            seq_lens_host=host_lens, flags=flags)
-
-    if args.mode == "run":
-        return bench_run(args, sun, case, work, shape, desc, free_list)
 
     graph = None
     if args.graph:
@@ -454,9 +581,10 @@ def main():
     per_step = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)])
     ms_per_step = wall * 1e3 / args.steps
 
-    alg = algorithmic_bytes(shape, work, args.quant)
+    alg = algorithmic_bytes(shape, work, quant)
     roof = None
     kernels = {}
+    launches_per_step = None
     if not args.no_profile:
         sun.sun_profile_reset()
         for _ in range(args.steps):
@@ -468,25 +596,20 @@ def main():
             if v["launches"]:
                 kernels[k] = {"avg_us": 1e3 * v["ms"] / v["launches"], "launches_per_step": v["launches"] // args.steps,
                               "ms_per_step": v["ms"] / args.steps}
+        launches_per_step = sum(v["launches_per_step"] for v in kernels.values())
         att = prof["attn_split"]
         # one launch = one layer: K and V of every cached position of every request, once
         per_launch = float(work.kv_tokens_read) * 2 * shape.n_kv_heads * shape.head_dim * 2
         avg_s = att["ms"] / att["launches"] * 1e-3
         roof = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": per_launch / avg_s / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": per_launch / avg_s / 1e9 / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
-        el = 4.0 if work.dtype == "f32" else 2.0
-        b_w = w4_bytes_per_weight(args.quant) if args.quant else el
-        H_, QD, KD, F = shape.hidden, shape.q_dim, shape.kv_dim, shape.ffn
-        sizes = {"qkv_proj": (QD + 2 * KD) * H_ * b_w, "o_proj": H_ * QD * b_w, "gate_up_proj": 2 * F * H_ * b_w,
-                 "down_proj": H_ * F * b_w, "lm_head": shape.vocab * H_ * el}
-        for k, nbytes in sizes.items():
-            if k in kernels:
-                kernels[k]["weight_GBps"] = nbytes / (kernels[k]["avg_us"] * 1e-6) / 1e9
+                "traffic": measured_traffic_bytes(workload, quant), "traffic_source": "profiles/ (counter runs of this command, not this run)",
+                "bytes_per_launch": per_launch, "avg_launch_us": avg_s * 1e6}
+        projection_figures(shape, work, quant, kernels)
 
     cpu = None
-    if args.cpu_sample > 0:
-        cpu = cpu_baseline(case, work, args.cpu_sample)
+    if cpu_sample > 0:
+        cpu = cpu_baseline(case, work, cpu_sample)
 
     out = {
         "metric": "shared-decode tokens/sec",
@@ -501,18 +624,45 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": ("f32" if work.dtype == "f32" else "bf16") if not args.quant else "bf16 activations, 4-bit group-128 weights",
+        "dtype": ("f32" if work.dtype == "f32" else "bf16") if not quant else "bf16 activations, 4-bit group-128 weights",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "shape": shape.name, "batch": work.batch,
-                   "quant": args.quant, "kv_tokens": work.kv_tokens_read, "graph": bool(args.graph)},
+        "config": {"workload": f"{workload}: {desc}", "shape": shape.name, "batch": work.batch,
+                   "quant": quant, "kv_tokens": work.kv_tokens_read, "graph": bool(args.graph)},
         "algorithmic_GB_per_step": alg["total"] / 1e9,
         "step_GBps": alg["total"] / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": alg["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "launches_per_step": launches_per_step,
         "roofline": roof,
         "kernels": kernels,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(out))
+    del case
+    torch.cuda.empty_cache()
+    return out
+
+
+def bench_run_setup(args, sun, H):
+    """--mode run: widen the page tables for the tokens the run generates, then time it."""
+    import torch
+    workload = args.workload or "cfg2"
+    work, desc = build_workload(workload)
+    shape = work.shape
+    grow = args.steps + args.warmup + 8  # + a short per-kernel timing pass after the timed run
+    cols = (int(work.seq_lens.max()) + grow) // 16 + 1
+    wide = np.full((work.batch, cols), -1, np.int32)
+    wide[:, :work.max_pages] = work.page_tables
+    referenced = np.zeros(work.n_pages, bool)
+    referenced[work.page_tables[work.page_tables >= 0]] = True
+    free_list = np.flatnonzero(~referenced).astype(np.int32)
+    assert len(free_list) >= work.batch * (grow // 16 + 1), "pool has too few spare pages for this output length"
+    work.page_tables = wide
+    case = H.DeviceCase(work, quant_mode=args.quant)
+    if args.quant:
+        for k in sun.QUANT_KEYS:
+            case.w[k] = None
+    torch.cuda.synchronize()
+    args.workload = workload
+    return bench_run(args, sun, case, work, shape, desc, free_list)
 
 
 if __name__ == "__main__":

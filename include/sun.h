@@ -19,8 +19,15 @@
  *    pointers are ordinary host memory.  The library never allocates or frees
  *    device memory and never synchronises unless stated; work is enqueued on the
  *    caller's hipStream_t (passed as void*; NULL = the null stream).
- *  - Every function returns a status (SUN_OK = 0).  On error nothing has been
- *    enqueued and sun_last_error() describes the problem (thread-local).
+ *  - Every function returns a status (SUN_OK = 0) and sun_last_error() describes
+ *    a failure (thread-local).  Every check of arguments and, under SUN_VALIDATE,
+ *    of device arrays happens before the first launch: such an error enqueues
+ *    nothing.  SUN_ERR_HIP is the exception: a launch the runtime refuses in the
+ *    middle of a step leaves the earlier kernels of that step enqueued, and the
+ *    workspace, the outputs and the positions of the pool the step writes are
+ *    then undefined; the multi-step calls (sun_decode_run, sun_decode_serve,
+ *    sun_prefill) may in that case have completed earlier steps, which have
+ *    updated token ids, lengths, page tables and the pool.
  *  - All matrices are row-major [out_features, in_features].
  *  - A process uses the library from one thread per stream; calls that share a
  *    workspace or a pool must not overlap.
@@ -306,9 +313,12 @@ int sun_qdecode_step(sun_kv_pool* pool, const sun_weights* weights, int batch,
  * the position the request writes next opens a page (seq_lens[i] % 16 == 0) that its table
  * does not have (entry < 0), the entry is set to free_pages[*free_head] and *free_head
  * advances; within a step requests are served in index order.  A request that finds the free
- * list empty, or whose table has no column left, keeps its length (it decodes the same position
- * again in the following steps, which is harmless) and bit 0 (list empty) or bit 1 (table full)
- * of *run_status is set; *run_status is cleared at the start of the run.
+ * list empty, or whose table has no column left, keeps its length: nothing is ever written through a
+ * missing page, but its fed-back token is still replaced, so from that step on it decodes every new
+ * token at the same position, over its own earlier entry there, and the tokens it produces are not a
+ * continuation of its sequence; bit 0 (list empty) or bit 1 (table full) of *run_status is set and the
+ * caller must discard that request's outputs from the step it was starved in (sun_decode_serve avoids
+ * the situation by reserving pages at admission).  *run_status is cleared at the start of the run.
  *
  *   token_ids   dev int32 [batch]             in: y_{t-1}; out: the last generated token
  *   page_tables dev int32 [batch, max_pages]  in/out
@@ -495,6 +505,18 @@ int sun_linear(const sun_weights* weights, int layer, int mat, int batch, const 
                void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------ misc */
+
+/*
+ * Measurement only (the yardstick the step's HBM-bound kernels are held against; Section 2.1: decode "must read
+ * ... a growing KV cache with little compute per byte"): a kernel that does nothing but read `bytes` of device
+ * memory at src in blocks of block_bytes (a multiple of 1024; 4096 = one (page, kv head) block of K or of V),
+ * 16 bytes per lane and load, one block per wave and turn, in address order or in the order perm gives
+ * (dev int32 [bytes / block_bytes], a permutation of the block indices), on `workgroups` workgroups of 256
+ * threads.  sink: dev, workgroups * 1024 bytes, receives one folded word per thread.  Asynchronous on stream.
+ * Errors: SUN_ERR_NULL, SUN_ERR_SHAPE, SUN_ERR_HIP.
+ */
+int sun_hbm_read_probe(const void* src, size_t bytes, int block_bytes, const int32_t* perm, int workgroups,
+                       void* sink, void* stream);
 
 /*
  * With SUN_PROFILE the step brackets each kernel class with HIP events.  After the

@@ -29,7 +29,7 @@ EXPORTS = [
     "sun_prefill_workspace_bytes", "sun_prefill", "sun_serve_workspace_bytes", "sun_decode_serve",
     "sun_paged_attention", "sun_paged_attention_static", "sun_paged_attention_static_bytes",
     "sun_paged_attention_static_limit", "sun_linear",
-    "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
+    "sun_hbm_read_probe", "sun_profile_read", "sun_profile_reset", "sun_last_error", "sun_version",
 ]
 
 
@@ -140,6 +140,7 @@ def lib() -> C.CDLL:
         L.sun_paged_attention_static_limit.argtypes = []
         L.sun_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
+        L.sun_hbm_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.sun_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.sun_profile_reset.restype = None
         _lib = L
@@ -464,6 +465,11 @@ def sun_paged_attention_static_limit() -> int:
 def sun_linear(weights, layer: int, mat: int, x, out, workspace, stream=None):
     _check(lib().sun_linear(weights.handle, layer, mat, x.shape[0], _p(x), _p(out), _p(workspace),
                             workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def sun_hbm_read_probe(src, block_bytes: int, perm, workgroups: int, sink, stream=None):
+    _check(lib().sun_hbm_read_probe(_p(src), src.numel() * src.element_size(), block_bytes, _p(perm) if perm is not None else None,
+                                    workgroups, _p(sink), _stream(stream)))
 
 
 def sun_profile_reset():

@@ -27,10 +27,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int CH = kAttnChunk;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kRecInts = 24;  // ints per item record
-#ifndef SUN_ATTN_TOPUP
-#define SUN_ATTN_TOPUP (CH / kAttnSmall)
-#endif
-constexpr int kTopUp = SUN_ATTN_TOPUP;  // small chunks that stand for one full chunk in a wave's item list
+constexpr int kTopUp = CH / kAttnSmall;  // small chunks that stand for one full chunk in a wave's item list
 
 size_t attn_max_chunks(int batch, int max_pages, int Hkv) {
     // An upper bound for every batch size up to `batch` (a workspace sized for a larger batch serves a smaller

@@ -15,14 +15,8 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kWave = 64;
 constexpr int kPageTokens = 16;     // tokens per KV page
-#ifndef SUN_ATTN_CHUNK
-#define SUN_ATTN_CHUNK 256
-#endif
-#ifndef SUN_ATTN_SMALL
-#define SUN_ATTN_SMALL 64
-#endif
-constexpr int kAttnChunk = SUN_ATTN_CHUNK;  // tokens per full split-K work item
-constexpr int kAttnSmall = SUN_ATTN_SMALL;  // tokens per small work item at the end of a request
+constexpr int kAttnChunk = 256;  // tokens per full split-K work item
+constexpr int kAttnSmall = 64;   // tokens per small work item at the end of a request
 // Length of a request's full chunks.  From 64 requests up it is kAttnChunk.  A smaller batch has too few
 // chunks of that length to occupy the chip (and one wave walks a chunk step by step, a memory latency per
 // step), so there the length is the power of two in [kAttnSmall, kAttnChunk] that gives about 2048 items over

@@ -1,4 +1,4 @@
-"""Host-side simulator of decode-worker placement in multi-model disaggregated serving (Section 3.2.2,
+"""Host-side simulator of decode-worker placement in multi-model disaggregated serving (Section 3.2.3,
 Appendix A.2): N task-specific models, each with its own prefill worker, and decode workers that are either
 isolated per model (the baseline, one decode worker per model) or pooled and model-agnostic (SUN: any of K
 workers can decode any request, because all tasks share the one frozen decode module).
