@@ -223,6 +223,218 @@ void proj_kernel(ProjArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------
+// bf16 weights, more than 64 rows
+// ---------------------------------------------------------------------------------
+// Above 64 rows the projection is bound by the matrix cores, and the workgroup shape above would
+// be bound by LDS just as much: there every operand fragment read from LDS feeds one matrix
+// instruction (1 KiB per 32 cycles and SIMD = the 128 bytes per cycle the LDS delivers).  Here a
+// wave owns 64 columns (two strips), so a fragment of the activations feeds two instructions.
+// A workgroup is eight waves, two per SIMD, and covers 256 columns and 64 * MRW rows: wave (c, h)
+// owns column pair c and row group h (MRW row blocks of 32; 2 in every launch: 128-row
+// workgroups).  The two row groups of a column pair request the same weights (HBM sees them once).
+// The activation stage is 64 wide (four k-steps) and shared by all waves.
+// Used above 128 rows.  Up to 128 rows the strip kernel stays (measured on the 14B shape at batch
+// 128: gate/up 103 against 119 us, the rest equal).  A variant with four waves of 128 rows x 64
+// columns, one per SIMD with its accumulators in the upper half of the register file, requests no
+// weight twice but was 10 to 90 % slower: one wave per SIMD cannot cover its own waits.
+template <int MRW, int EPI>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void proj_tall_kernel(ProjArgs a) {
+    constexpr int RH = 2, NWC = 4;             // row groups and column pairs of a workgroup
+    constexpr int MRT = RH * MRW;              // row blocks of the workgroup
+    constexpr int MB = 2 * MRT;                // operand blocks of a k-step in LDS: hi planes, then lo planes
+    constexpr int KK = 4;                      // k-steps per stage (64 of k)
+    constexpr int STAGE_UNITS = KK * MB * 64;
+    constexpr int NT = RH * NWC * 64;
+    constexpr int NBUF = (MRT <= 2) ? 3 : 2;   // a third weight stage in registers does not fit beside 64 + 64 accumulators
+    constexpr int UPT = (STAGE_UNITS + NT - 1) / NT;
+    static_assert(STAGE_UNITS % NT == 0, "every thread stages the same number of units");
+    __shared__ u32x4 lds_all[NBUF * STAGE_UNITS];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5;
+    const int wc = wave % NWC, rh = wave / NWC;
+    const int cp = blockIdx.x * NWC + wc;      // column pair: strips 2 cp and 2 cp + 1
+    const int n_strips = a.N / 32;
+    const bool act0 = 2 * cp < n_strips, act1 = 2 * cp + 1 < n_strips;
+    const int split = blockIdx.y;
+    const int mb_off = blockIdx.z * MRT;       // first row block of this workgroup
+    const int s0 = split * a.stages_per_split;
+    const int s1 = min(a.n_stages, s0 + a.stages_per_split);
+    const int kch = a.K / 128;
+
+    // a stage is half a 128-wide chunk of the packed weights: four of its eight k-steps
+    const u32x4* Wl0 = a.W + ((size_t)(act0 ? 2 * cp : 0) * kch) * 8 * 64 + lane;
+    const u32x4* Wl1 = a.W + ((size_t)(act1 ? 2 * cp + 1 : 0) * kch) * 8 * 64 + lane;
+
+    f32x16 acc[2][MRW];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int m = 0; m < MRW; ++m)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[s][m][r] = 0.f;
+
+    u32x4 w0[2][KK], w1[2][KK], w2[NBUF == 3 ? 2 : 1][NBUF == 3 ? KK : 1], areg[UPT];
+
+    auto load_w = [&](u32x4(&w)[2][KK], int st) {
+        const size_t off = ((size_t)st * KK) * 64;   // in k-steps of 64 lanes
+#pragma unroll
+        for (int j = 0; j < KK; ++j) {
+            w[0][j] = Wl0[off + (size_t)j * 64];
+            w[1][j] = Wl1[off + (size_t)j * 64];
+        }
+    };
+    auto load_a = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) {
+            const int u = i * NT + tid;
+            const int kk = u / (MB * 64), rem = u % (MB * 64);
+            const int m = rem >> 6;  // operand block: hi plane of row block m, or lo plane of row block m - MRT
+            const int gb = m < MRT ? mb_off + m : a.mb_rows + mb_off + (m - MRT);
+            areg[i] = a.A[((size_t)(st * KK + kk) * (2 * a.mb_rows) + gb) * 64 + (rem & 63)];
+        }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < UPT; ++i) lds_all[buf * STAGE_UNITS + i * NT + tid] = areg[i];
+    };
+    auto compute = [&](int buf, const u32x4(&w)[2][KK]) {
+        // this wave's operand blocks of a k-step: hi and lo plane of its MRW row blocks
+        const u32x4* src = lds_all + buf * STAGE_UNITS + lane;
+        u32x4 afr[2][2 * MRW];
+        auto read_a = [&](int kk, u32x4(&dst)[2 * MRW]) {
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+                for (int m = 0; m < MRW; ++m) dst[pl * MRW + m] = src[(kk * MB + pl * MRT + rh * MRW + m) * 64];
+        };
+        read_a(0, afr[0]);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk + 1 < KK) read_a(kk + 1, afr[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bf16x8 bfrag = __builtin_bit_cast(bf16x8, w[s][kk]);
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl)  // hi plane, then lo plane, into the same accumulators
+#pragma unroll
+                    for (int m = 0; m < MRW; ++m) {
+                        const bf16x8 afrag = __builtin_bit_cast(bf16x8, afr[kk & 1][pl * MRW + m]);
+                        acc[s][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag, acc[s][m], 0, 0, 0);
+                    }
+            }
+        }
+    };
+
+    if (s0 < s1) {
+        if constexpr (NBUF == 3) {
+            auto phase = [&](const u32x4(&wcur)[2][KK], u32x4(&wn)[2][KK], int bufc, int bufn, int st) {
+                const int nx = min(st + 2, s1 - 1);
+                load_a(nx);  // before the weights: the LDS store below then waits for these only
+                load_w(wn, nx);
+                compute(bufc, wcur);
+                store_a(bufn);
+                __syncthreads();
+            };
+            const int sA = min(s0 + 1, s1 - 1);
+            load_w(w0, s0);
+            load_a(s0);
+            store_a(0);
+            load_w(w1, sA);
+            load_a(sA);
+            store_a(1);
+            __syncthreads();
+            for (int st = s0; st < s1; st += 3) {
+                phase(w0, w2, 0, 2, st);
+                if (st + 1 >= s1) break;
+                phase(w1, w0, 1, 0, st + 1);
+                if (st + 2 >= s1) break;
+                phase(w2, w1, 2, 1, st + 2);
+            }
+        } else {
+            load_w(w0, s0);
+            load_a(s0);
+            store_a(0);
+            __syncthreads();
+            for (int st = s0; st < s1; st += 2) {
+                const int n1 = min(st + 1, s1 - 1);
+                load_a(n1);
+                load_w(w1, n1);
+                compute(0, w0);
+                store_a(1);
+                __syncthreads();
+                if (st + 1 >= s1) break;
+                const int n2 = min(st + 2, s1 - 1);
+                load_a(n2);
+                load_w(w0, n2);
+                compute(1, w1);
+                store_a(0);
+                __syncthreads();
+            }
+        }
+    }
+
+    const int col = lane & 31;
+    if constexpr (EPI == EPI_SWIGLU) {
+        // A strip's 32 columns are 16 gate columns followed by the 16 up columns of the same u columns (the
+        // packing order of the pair): lane c < 16 fetches its up value from lane c + 16 and owns u column
+        // strip*16 + c.  The results leave as the tile the down projection reads: hi and lo plane, 16-byte units
+        // of 8 consecutive u columns of one row, gathered through the wave's own piece of the (now idle)
+        // activation ring.  Every wave has passed the barrier that follows the last stage.
+        uint16_t* sw = reinterpret_cast<uint16_t*>(lds_all) + (size_t)wave * (MRW * 32 * 16 * 2);
+        u32x4* tile = reinterpret_cast<u32x4*>(a.out);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int nb = 2 * cp + s;
+#pragma unroll
+            for (int m = 0; m < MRW; ++m)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float g = acc[s][m][r];
+                    const float up = __shfl_xor(g, 16);
+                    const float y = g / (1.f + __expf(-g)) * up;
+                    const uint16_t hi = f32_to_bf16_bits(y);
+                    const uint16_t lo = f32_to_bf16_bits(y - bf16_bits_to_f32(hi));
+                    const int rl = m * 32 + 8 * (r >> 2) + 4 * half + (r & 3);  // row inside the wave's rows
+                    if (col < 16) {
+                        sw[(0 * MRW * 32 + rl) * 16 + col] = hi;
+                        sw[(1 * MRW * 32 + rl) * 16 + col] = lo;
+                    }
+                }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's LDS writes have landed (no other wave reads them)
+            __builtin_amdgcn_wave_barrier();
+            if (nb < n_strips) {
+#pragma unroll
+                for (int i = 0; i < MRW * 2; ++i) {       // MRW*32 rows x 2 units x 2 planes = MRW*128 units, 64 lanes
+                    const int idx = i * 64 + lane;
+                    const int plane = idx / (MRW * 64), rem = idx % (MRW * 64), rl = rem >> 1, un = rem & 1;
+                    const int b = (mb_off + rh * MRW) * 32 + rl;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(sw + ((size_t)plane * MRW * 32 + rl) * 16 + un * 8);
+                    if (b < a.rows) tile[atile_unit(ATile{a.mb_rows}, plane, b, nb * 2 + un)] = v;
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // the reads are done before the second strip overwrites the piece
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int nb = 2 * cp + s;
+            if (nb >= n_strips) continue;
+            float* o = a.out + (size_t)split * a.ld_rows * a.ldo + nb * 32 + col;
+#pragma unroll
+            for (int m = 0; m < MRW; ++m)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int b = (mb_off + rh * MRW + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (b < a.rows) o[(size_t)b * a.ldo] = acc[s][m][r];
+                }
+        }
+    }
+}
+
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 
@@ -409,6 +621,35 @@ static hipError_t launch_proj_t(const ProjArgs& a, int epilogue, int splits, int
     return hipGetLastError();
 }
 
+static hipError_t launch_proj_tall(const ProjArgs& a, int epilogue, int splits, int mtiles, hipStream_t st) {
+    const int pairs = (a.N / 32 + 1) / 2;
+    dim3 grid((pairs + 3) / 4, splits, mtiles);
+    if (epilogue == EPI_SWIGLU) {
+        if (splits != 1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((proj_tall_kernel<2, EPI_SWIGLU>), grid, dim3(512), 0, st, a);
+        return hipGetLastError();
+    }
+    if (epilogue != EPI_STORE) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((proj_tall_kernel<2, EPI_STORE>), grid, dim3(512), 0, st, a);
+    return hipGetLastError();
+}
+
+// Split-K factor of the launch above 128 rows (bf16; workgroups of 128 rows x 256 columns).  All workgroups do
+// equal work and one round of at most 256 of them is wanted: the largest split that stays within the round
+// (each split costs a slab of partial sums, but the matrix-core time of a workgroup goes with its stages;
+// measured on the 8B shape at 256 rows: qkv 5 splits 32.7 us against 37.7 with 4, down 8 against 4: 64 / 125).
+static int tall_pick_splits(const Mat& W, int rows, int max_splits) {
+    const int pairs = (W.N / 32 + 1) / 2, stages = W.K / 64, colwgs = (pairs + 3) / 4;
+    const int mtiles = (atile_for_rows(rows).MB + 3) / 4;
+    int best = 1;
+    for (int s = 1; s <= max(1, min(max_splits, stages / 4)); ++s) {
+        const int sps = (stages + s - 1) / s;
+        if ((stages + sps - 1) / sps != s) continue;
+        if ((long long)colwgs * mtiles * s <= 256) best = s;
+    }
+    return best;
+}
+
 static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / splits; }
 
 // Waves per workgroup (each wave owns 32 columns) and split-K factor.  A compute unit's share of
@@ -459,7 +700,16 @@ static ProjShape proj_pick(const Mat& W, int rows, int max_splits) {
     return best;
 }
 
-int proj_pick_splits(const Mat& W, int rows, int max_splits) { return proj_pick(W, rows, max_splits).splits; }
+static bool use_tall(const Mat& W, int rows) {
+    // the wide vocabulary projection runs several rounds of workgroups, two of the strip kernel's on a compute unit
+    // at a time: measured faster there than one of these
+    return W.kind == MAT_BF16_PACKED && rows > 128 && (W.N / 32 + 7) / 8 <= 256;
+}
+
+int proj_pick_splits(const Mat& W, int rows, int max_splits) {
+    if (use_tall(W, rows)) return tall_pick_splits(W, rows, max_splits);
+    return proj_pick(W, rows, max_splits).splits;
+}
 
 // the wave count that goes with a given split factor
 static int proj_pick_waves(const Mat& W, int rows, int splits) {
@@ -527,6 +777,13 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
         }
         if (t.mb == 2) return launch_proj_nw<2, 128>(a, nw, p.epilogue, splits, t.mtiles, st);
         return launch_proj_nw<4, 128>(a, nw, p.epilogue, splits, t.mtiles, st);
+    }
+    if (use_tall(W, p.rows)) {
+        const int want = p.epilogue == EPI_SWIGLU ? 1 : max(1, p.splits);
+        const int stg = kch * 2, per = (stg + want - 1) / want, real_s = (stg + per - 1) / per;
+        a.n_stages = stg;
+        a.stages_per_split = per;
+        return launch_proj_tall(a, p.epilogue, real_s, (at.MB + 3) / 4, st);
     }
     a.n_stages = kch * 2;
     a.stages_per_split = cps * 2;
