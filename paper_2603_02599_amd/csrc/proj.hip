@@ -441,7 +441,7 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 // 4-bit weights: MR 32-row blocks per workgroup (all rows up to 64; 64-row tiles above), one stage =
 // one 128-wide group = four int8 MFMA k-steps, three stages of activations in the LDS ring.
 template <int MR, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, MR == 1 ? 4 : 2)))
 void proj_w4_kernel(ProjArgs a) {
     constexpr int STEPS = 4;
     constexpr int STAGE_UNITS = STEPS * 2 * MR * 64;  // 16-byte units of activations per stage (two planes)
@@ -662,17 +662,21 @@ struct ProjShape {
     int nw, splits;
 };
 // Row tiling: operand blocks per workgroup (2 planes x 32-row blocks) and row tiles per launch.
-// Up to 64 rows one tile holds all rows.  Above, bf16 weights use 128-row tiles (every tile streams
-// the weights from HBM again); 4-bit weights are a quarter of the bytes and their kernel is bound by
-// the matrix cores, so they keep the 64-row tile, which fits two waves per SIMD with its group
-// accumulators.
+// bf16 weights: up to 64 rows one tile holds all rows; above, 128-row tiles (every tile streams the
+// weights from HBM again).  4-bit weights: 32-row tiles at every batch size.  Their kernel is bound by
+// its vector-ALU epilogue and by the wait for the matrix cores between epilogues, not by the weight
+// stream (a quarter of the bytes, and the row tiles of a column strip run side by side and share
+// their fetches); with one row block a wave needs 128 registers instead of 230, four waves share a
+// SIMD instead of two and cover each other's waits (8B shape, qkv / o / gate-up / down in us: batch 64
+// 16.2 / 11.9 / 32.7 / 21.6 -> 15.0 / 11.1 / 30.0 / 20.5; batch 256 30.9 / 22.7 / 104.6 / 60.2 -> 27.8 / 20.6 /
+// 90.9 / 50.7; results bit-identical).
 struct ProjTiling {
     int mb, mtiles;
 };
 static ProjTiling proj_tiling(const Mat& W, int rows) {
     const int mbr = atile_for_rows(rows).MB;  // 32-row blocks of the activation tiling: 1, 2, 4 or 8
+    if (W.kind == MAT_W4_PACKED) return ProjTiling{2, mbr};
     if (mbr <= 2) return ProjTiling{2 * mbr, 1};
-    if (W.kind == MAT_W4_PACKED) return ProjTiling{4, mbr / 2};
     return ProjTiling{8, mbr / 4};
 }
 static long long proj_cost(int strips, int kch, int mtiles, int nw, int s) {
@@ -681,10 +685,32 @@ static long long proj_cost(int strips, int kch, int mtiles, int nw, int s) {
     const long long rounds = (wgs + 255) / 256;
     return rounds * ((long long)nw * cps + 6) * 16 + real_s;  // ties: fewer splits
 }
+// 4-bit weights with more than one 32-row tile: several workgroups share a compute unit (16 waves at 128
+// registers), so the launch wants two to four times 256 workgroups rather than exactly 256.  Four waves per
+// workgroup (seven for a matrix of 512 strips or more while there are only two row tiles), and the smallest
+// split that gives at least 512 workgroups without leaving a workgroup more than 32 stages.  Measured on the 8B
+// shape (us, best of the shapes tried): batch 64 qkv 4 x 8: 13.5 (6 x 8: 14.7, 4 x 4: 15.3), o 4 x 8: 10.8
+// (4 x 4: 12.0, 4 x 16: 12.6), gate/up 7 x 2: 30.0 (4 x 2: 31.8, 7 x 1: 35.6), down 4 x 8: 19.7 (4 x 4: 26.8);
+// batch 256 qkv 4 x 2: 25.8 (4 x 4: 27.5, 4 x 8: 30.3), o 4 x 4: 20.4, gate/up 4 x 1: 92.4 (4 x 2: 95.4, 4 x 4: 105),
+// down 4 x 4: 49.4 (4 x 2: 52.4, 4 x 8: 51.3).
+static ProjShape w4_tiles_pick(const Mat& W, int mtiles, int max_splits) {
+    const int strips = W.N / 32, kch = W.K / 128;
+    const int nw = (strips >= 512 && mtiles <= 2) ? 7 : 4;
+    const long long colwgs = (strips + nw - 1) / nw;
+    ProjShape best{nw, 1};
+    for (int s = 1; s <= max(1, min(max_splits, kch / 2)); ++s) {
+        const int cps = chunks_per_split(kch, s), real_s = (kch + cps - 1) / cps;
+        if (real_s != s) continue;
+        best = ProjShape{nw, s};
+        if (colwgs * mtiles * s >= 512 && cps <= 32) break;
+    }
+    return best;
+}
 static ProjShape proj_pick(const Mat& W, int rows, int max_splits) {
     const int strips = W.N / 32, kch = W.K / 128;
     const ProjTiling t = proj_tiling(W, rows);
     const int mtiles = t.mtiles;
+    if (W.kind == MAT_W4_PACKED && mtiles >= 2) return w4_tiles_pick(W, mtiles, max_splits);
     const int smax = max(1, min(max_splits, kch / 2));
     ProjShape best{4, 1};
     long long best_cost = -1;
@@ -716,6 +742,7 @@ static int proj_pick_waves(const Mat& W, int rows, int splits) {
     const int strips = W.N / 32, kch = W.K / 128;
     const ProjTiling t = proj_tiling(W, rows);
     const int mtiles = t.mtiles;
+    if (W.kind == MAT_W4_PACKED && mtiles >= 2) return W.N / 32 >= 512 && mtiles <= 2 ? 7 : 4;
     int best = 4;
     long long best_cost = -1;
     for (int nw = 4; nw <= (t.mb <= 4 ? 7 : 4); ++nw) {
@@ -773,7 +800,7 @@ hipError_t launch_proj(const ProjLaunch& p, hipStream_t st) {
         const int nw = proj_pick_waves(W, p.rows, splits);
         if (w4) {
             if (p.epilogue != EPI_STORE) return hipErrorInvalidValue;
-            return t.mb == 2 ? launch_proj_w4<1>(a, nw, splits, t.mtiles, st) : launch_proj_w4<2>(a, nw, splits, t.mtiles, st);
+            return launch_proj_w4<1>(a, nw, splits, t.mtiles, st);
         }
         if (t.mb == 2) return launch_proj_nw<2, 128>(a, nw, p.epilogue, splits, t.mtiles, st);
         return launch_proj_nw<4, 128>(a, nw, p.epilogue, splits, t.mtiles, st);
