@@ -688,7 +688,7 @@ static long long proj_cost(int strips, int kch, int mtiles, int nw, int s) {
 // 4-bit weights with more than one 32-row tile: several workgroups share a compute unit (16 waves at 128
 // registers), so the launch wants two to four times 256 workgroups rather than exactly 256.  Four waves per
 // workgroup (seven for a matrix of 512 strips or more while there are only two row tiles), and the smallest
-// split that gives at least 512 workgroups without leaving a workgroup more than 32 stages.  Measured on the 8B
+// split into equal shares that gives at least 512 workgroups without leaving a workgroup more than 32 stages.  Measured on the 8B
 // shape (us, best of the shapes tried): batch 64 qkv 4 x 8: 13.5 (6 x 8: 14.7, 4 x 4: 15.3), o 4 x 8: 10.8
 // (4 x 4: 12.0, 4 x 16: 12.6), gate/up 7 x 2: 30.0 (4 x 2: 31.8, 7 x 1: 35.6), down 4 x 8: 19.7 (4 x 4: 26.8);
 // batch 256 qkv 4 x 2: 25.8 (4 x 4: 27.5, 4 x 8: 30.3), o 4 x 4: 20.4, gate/up 4 x 1: 92.4 (4 x 2: 95.4, 4 x 4: 105),
@@ -699,10 +699,9 @@ static ProjShape w4_tiles_pick(const Mat& W, int mtiles, int max_splits) {
     const long long colwgs = (strips + nw - 1) / nw;
     ProjShape best{nw, 1};
     for (int s = 1; s <= max(1, min(max_splits, kch / 2)); ++s) {
-        const int cps = chunks_per_split(kch, s), real_s = (kch + cps - 1) / cps;
-        if (real_s != s) continue;
+        if (kch % s) continue;  // equal shares only: the launch ends with its longest workgroup
         best = ProjShape{nw, s};
-        if (colwgs * mtiles * s >= 512 && cps <= 32) break;
+        if (colwgs * mtiles * s >= 448 && kch / s <= 32) break;  // "at least 512", with a little give
     }
     return best;
 }
