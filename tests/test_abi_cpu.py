@@ -226,6 +226,22 @@ def test_single_op_argument_checks(lib):
     assert lib.sun_paged_attention(pool, 5, 1, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == 2
     assert lib.sun_paged_attention(pool, 0, 1, None, FAKE, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == 1
     assert lib.sun_paged_attention(pool, 0, 1, FAKE, FAKE, 4, FAKE, None, FAKE, FAKE, 16, None) == 4
+    # the attention entry point that allocates nothing: same checks, and the size limit before any launch
+    st = lib.sun_paged_attention_static
+    assert st(None, 0, 1, FAKE, FAKE, 4, FAKE, None, FAKE, None) == 1 and st(pool, 0, 1, None, FAKE, 4, FAKE, None, FAKE, None) == 1
+    assert st(pool, 5, 1, FAKE, FAKE, 4, FAKE, None, FAKE, None) == 2 and st(pool, 0, 0, FAKE, FAKE, 4, FAKE, None, FAKE, None) == 2
+    limit = lib.sun_paged_attention_static_limit()
+    assert limit == 16 << 20 and 0 < lib.sun_paged_attention_static_bytes(C.byref(cfg), 8, 8) < limit
+    assert lib.sun_paged_attention_static_bytes(C.byref(cfg), 1024, 1 << 16) > limit
+    assert lib.sun_paged_attention_static_bytes(None, 8, 8) == 0 and lib.sun_paged_attention_static_bytes(C.byref(cfg), 0, 8) == 0
+    assert st(pool, 0, 1024, FAKE, FAKE, 1 << 16, FAKE, None, FAKE, None) == 4
+    assert b"scratch" in lib.sun_last_error()
+    # the read probe
+    pr = lib.sun_hbm_read_probe
+    assert pr(None, 1 << 20, 4096, None, 256, FAKE, None) == 1 and pr(FAKE, 1 << 20, 4096, None, 256, None, None) == 1
+    assert pr(FAKE, 1 << 20, 1000, None, 256, FAKE, None) == 2 and pr(FAKE, 1 << 20, 0, None, 256, FAKE, None) == 2
+    assert pr(FAKE, 1024, 4096, None, 256, FAKE, None) == 2 and pr(FAKE, 1 << 20, 4096, None, 0, FAKE, None) == 2
+    assert pr(FAKE + 8, 1 << 20, 4096, None, 256, FAKE, None) == 2
     assert lib.sun_quantize_w4(FAKE, 0, 4, 256, 64, 0, FAKE, FAKE, FAKE, None) == 2
     assert lib.sun_quantize_w4(FAKE, 0, 4, 200, 128, 0, FAKE, FAKE, FAKE, None) == 2
     assert lib.sun_quantize_w4(None, 0, 4, 256, 128, 0, FAKE, FAKE, FAKE, None) == 1

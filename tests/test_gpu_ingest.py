@@ -149,3 +149,27 @@ def test_shared_decode_over_caches_from_different_prefill_models(H):
     _, K0, _ = H.orc.full_forward(ocfg, prefill_params[0][1], p, round_kv=True, want_kv=True)
     _, K1, _ = H.orc.full_forward(ocfg, prefill_params[1][1], p, round_kv=True, want_kv=True)
     assert np.abs(K0 - K1).max() > 1e-3
+
+
+def test_read_probe_reads_every_block_once(H):
+    """The measurement kernel behind bench.py --hbm-read-probe: whatever the order of the blocks, every 16-byte
+    unit is read exactly once.  Each thread folds fixed components of its units into one word, so the fold of
+    all threads' words equals the fold of those components over the whole buffer, in address order and in any
+    shuffled order."""
+    H.say("hbm read probe")
+    n_blocks, block = 777, 4096
+    g = torch.Generator(device=H.DEV).manual_seed(5)
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (n_blocks * block // 4,), dtype=torch.int32, device=H.DEV, generator=g)
+    a = src.cpu().numpy().view(np.uint32).reshape(n_blocks, block // 16, 4)
+    comp = {0: (0, 3), 1: (1, 2), 2: (0, 2), 3: (1, 3)}      # which dwords of a unit are folded, by the unit's quarter of the block
+    want = np.uint32(0)
+    for quarter, (c0, c1) in comp.items():
+        part = a[:, quarter * 64:(quarter + 1) * 64]
+        want ^= np.bitwise_xor.reduce(part[..., c0].ravel()) ^ np.bitwise_xor.reduce(part[..., c1].ravel())
+    perm = torch.randperm(n_blocks, device=H.DEV, generator=g).to(torch.int32)
+    for order, wgs in ((None, 64), (perm, 64), (perm, 300)):
+        sink = torch.full((wgs * 256,), 12345, dtype=torch.int32, device=H.DEV)
+        sun.sun_hbm_read_probe(src, block, order, wgs, sink)
+        torch.cuda.synchronize()
+        got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+        assert got == want, f"fold {got:#x} != {want:#x} (order {'shuffled' if order is not None else 'address'}, {wgs} workgroups)"
