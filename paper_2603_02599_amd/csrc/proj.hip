@@ -224,9 +224,9 @@ void proj_kernel(ProjArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
-// bf16 weights, more than 64 rows
+// bf16 weights, more than 128 rows
 // ---------------------------------------------------------------------------------
-// Above 64 rows the projection is bound by the matrix cores, and the workgroup shape above would
+// Above 64 rows the projection is no longer bound by the weight stream, and the workgroup shape above would
 // be bound by LDS just as much: there every operand fragment read from LDS feeds one matrix
 // instruction (1 KiB per 32 cycles and SIMD = the 128 bytes per cycle the LDS delivers).  Here a
 // wave owns 64 columns (two strips), so a fragment of the activations feeds two instructions.
@@ -438,8 +438,8 @@ void proj_tall_kernel(ProjArgs a) {
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 
-// 4-bit weights: MR 32-row blocks per workgroup (all rows up to 64; 64-row tiles above), one stage =
-// one 128-wide group = four int8 MFMA k-steps, three stages of activations in the LDS ring.
+// 4-bit weights: MR 32-row blocks per workgroup (the launches use MR = 1: 32-row tiles, see proj_tiling), one
+// stage = one 128-wide group = four int8 MFMA k-steps, three stages of activations in the LDS ring.
 template <int MR, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, MR == 1 ? 4 : 2)))
 void proj_w4_kernel(ProjArgs a) {
@@ -657,7 +657,8 @@ static int chunks_per_split(int kch, int splits) { return (kch + splits - 1) / s
 // as fast as the most loaded unit: the pair is chosen to spread the weight bytes evenly over the
 // 256 compute units (N = 6144 -> 6 waves x 8 splits, N = 28672 -> 7 waves x 2 splits, ...), with a
 // fixed charge per workgroup for filling and draining its pipeline.  Depends on the matrix and the
-// row-count class only.  Above 64 rows the kernels are bound by the matrix cores and keep 4 waves.
+// row-count class only.  The bf16 kernel above 64 rows keeps 4 waves; 4-bit launches of several row tiles have
+// a rule of their own (w4_tiles_pick).
 struct ProjShape {
     int nw, splits;
 };
