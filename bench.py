@@ -349,21 +349,23 @@ def main():
         src.random_(0, 1 << 30)
         perm = torch.randperm(nbytes // 4096, device="cuda").to(torch.int32)
         out = {"what": "read-only streaming kernel", "bytes": nbytes, "hbm_peak_GBps": HBM_PEAK_GBS, "runs": []}
-        for block, order, wgs in ((4096, None, 2048), (4096, perm, 2048), (4096, perm, 1024), (4096, perm, 4096),
-                                  (65536, None, 2048)):
+        for block, order, wgs, streaming in ((4096, None, 2048, False), (4096, perm, 2048, False), (4096, perm, 1024, False),
+                                             (4096, perm, 4096, False), (65536, None, 2048, False), (4096, None, 2048, True),
+                                             (4096, perm, 2048, True), (4096, perm, 512, True), (4096, perm, 8192, True)):
             sink = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
             p = order if block == 4096 else None
             for _ in range(2):
-                sun.sun_hbm_read_probe(src, block, p, wgs, sink)
+                sun.sun_hbm_read_probe(src, block, p, wgs, sink, streaming_loads=streaming)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(5):
-                sun.sun_hbm_read_probe(src, block, p, wgs, sink)
+                sun.sun_hbm_read_probe(src, block, p, wgs, sink, streaming_loads=streaming)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 5
             out["runs"].append({"block_bytes": block, "order": "shuffled" if p is not None else "address", "workgroups": wgs,
+                                "loads": "streaming" if streaming else "plain",
                                 "ms": ms, "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
         print(json.dumps(out))
         return

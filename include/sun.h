@@ -512,11 +512,12 @@ int sun_linear(const sun_weights* weights, int layer, int mat, int batch, const 
  * memory at src in blocks of block_bytes (a multiple of 1024; 4096 = one (page, kv head) block of K or of V),
  * 16 bytes per lane and load, one block per wave and turn, in address order or in the order perm gives
  * (dev int32 [bytes / block_bytes], a permutation of the block indices), on `workgroups` workgroups of 256
- * threads.  sink: dev, workgroups * 1024 bytes, receives one folded word per thread.  Asynchronous on stream.
- * Errors: SUN_ERR_NULL, SUN_ERR_SHAPE, SUN_ERR_HIP.
+ * threads; streaming_loads != 0: with the loads that pass the caches by, which the attention kernel uses for K
+ * and V, else plain loads.  sink: dev, workgroups * 1024 bytes, receives one folded word per thread.
+ * Asynchronous on stream.  Errors: SUN_ERR_NULL, SUN_ERR_SHAPE, SUN_ERR_HIP.
  */
 int sun_hbm_read_probe(const void* src, size_t bytes, int block_bytes, const int32_t* perm, int workgroups,
-                       void* sink, void* stream);
+                       int streaming_loads, void* sink, void* stream);
 
 /*
  * With SUN_PROFILE the step brackets each kernel class with HIP events.  After the

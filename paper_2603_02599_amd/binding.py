@@ -140,7 +140,7 @@ def lib() -> C.CDLL:
         L.sun_paged_attention_static_limit.argtypes = []
         L.sun_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
-        L.sun_hbm_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.sun_hbm_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.sun_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.sun_profile_reset.restype = None
         _lib = L
@@ -467,9 +467,9 @@ def sun_linear(weights, layer: int, mat: int, x, out, workspace, stream=None):
                             workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def sun_hbm_read_probe(src, block_bytes: int, perm, workgroups: int, sink, stream=None):
+def sun_hbm_read_probe(src, block_bytes: int, perm, workgroups: int, sink, streaming_loads: bool = False, stream=None):
     _check(lib().sun_hbm_read_probe(_p(src), src.numel() * src.element_size(), block_bytes, _p(perm) if perm is not None else None,
-                                    workgroups, _p(sink), _stream(stream)))
+                                    workgroups, 1 if streaming_loads else 0, _p(sink), _stream(stream)))
 
 
 def sun_profile_reset():

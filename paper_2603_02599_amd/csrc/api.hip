@@ -239,14 +239,14 @@ void sun_profile_reset(void) {
     g_prof.clear();
 }
 
-int sun_hbm_read_probe(const void* src, size_t bytes, int block_bytes, const int32_t* perm, int workgroups, void* sink,
-                       void* stream) {
+int sun_hbm_read_probe(const void* src, size_t bytes, int block_bytes, const int32_t* perm, int workgroups,
+                       int streaming_loads, void* sink, void* stream) {
     if (!src || !sink) return fail(SUN_ERR_NULL, "NULL argument");
     if (block_bytes < 1024 || block_bytes % 1024 || bytes < (size_t)block_bytes || workgroups < 1 || workgroups > 65536)
         return fail(SUN_ERR_SHAPE, "block_bytes must be a multiple of 1024, bytes at least one block, workgroups in [1, 65536]");
     if ((uintptr_t)src % 16) return fail(SUN_ERR_SHAPE, "src must be 16-byte aligned");
     SUN_HIP_CHECK(launch_hbm_read_probe(src, (long long)(bytes / block_bytes), block_bytes / 16, perm, workgroups,
-                                        (uint32_t*)sink, (hipStream_t)stream));
+                                        streaming_loads != 0, (uint32_t*)sink, (hipStream_t)stream));
     return SUN_OK;
 }
 

@@ -124,6 +124,12 @@ __device__ __forceinline__ int qtile_store8(uint8_t* tile, ATile t, int b, int k
 // 1 / sx for a group whose largest magnitude is amax (an all-zero group maps to zeros with sx = 0)
 __device__ __forceinline__ float qtile_inv(float amax) { return amax > 0.f ? kQMax / amax : 0.f; }
 
+// 16-byte load of data that is read once and never again by this launch (the cached V of the attention kernel):
+// streamed past the caches (the "nt" form of the load), which also leaves what the neighbouring kernels exchange
+// in place.  Pays where an instruction reads long contiguous runs; see the attention kernel.
+typedef uint32_t u32x4_s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_s load_stream(const u32x4_s* p) { return __builtin_nontemporal_load(p); }
+
 // ---- wave reductions (all lanes receive the result; fixed order => deterministic) ----
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

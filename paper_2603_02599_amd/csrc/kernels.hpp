@@ -106,9 +106,10 @@ hipError_t launch_swiglu_f32(const float* gu, int batch, int ffn, float* u, hipS
 // gate/up partial sums (projection column order) -> silu(g)*u as two-plane tiled bf16, or as fixed-point tile + qscale
 hipError_t launch_swiglu_tile(const float* part, int nparts, int ld_rows, int rows, int ffn, void* tiled, float* qscale,
                               hipStream_t st);
-// measurement only: stream n_blocks blocks of block_units 16-byte units (order given by perm, or address order)
+// measurement only: read n_blocks blocks of block_units 16-byte units (order given by perm, or address order),
+// with plain loads or with the streaming loads the attention kernel uses for K and V
 hipError_t launch_hbm_read_probe(const void* src, long long n_blocks, int block_units, const int32_t* perm, int grid,
-                                 uint32_t* sink, hipStream_t st);
+                                 bool stream, uint32_t* sink, hipStream_t st);
 constexpr int kArgmaxParts = 16;  // slices of a logits row searched by separate workgroups
 // part_val / part_idx: scratch [batch][kArgmaxParts]
 hipError_t launch_argmax(const float* logits, int batch, int vocab, float* part_val, int32_t* part_idx, int32_t* next,

@@ -827,9 +827,11 @@ hipError_t launch_serve(const ServeArgs& a, const int32_t* next, int32_t* tokens
 // Reads `n_blocks` blocks of `block_units` 16-byte units each, in the order perm gives (or in address order),
 // and does nothing with them but fold them into one word per thread: what a kernel that only streams from HBM
 // reaches on this device, contiguous or in scattered blocks the size of one (page, head) K or V block.
+template <int STREAM>
 __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const u32x4* __restrict__ src, long long n_blocks,
                                                              int block_units, const int32_t* __restrict__ perm,
                                                              uint32_t* __restrict__ sink) {
+    auto ld = [](const u32x4* p) { return STREAM ? load_stream(p) : *p; };
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const long long gw = (long long)blockIdx.x * 4 + wave, nw = (long long)gridDim.x * 4;
     uint32_t acc = 0;
@@ -837,8 +839,8 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const u32x4* __rest
         const long long blk = perm ? perm[b] : b;
         const u32x4* p = src + blk * block_units;
         for (int u = lane; u < block_units; u += 256) {
-            const u32x4 v0 = p[u], v1 = p[min(u + 64, block_units - 1)], v2 = p[min(u + 128, block_units - 1)],
-                        v3 = p[min(u + 192, block_units - 1)];
+            const u32x4 v0 = ld(p + u), v1 = ld(p + min(u + 64, block_units - 1)), v2 = ld(p + min(u + 128, block_units - 1)),
+                        v3 = ld(p + min(u + 192, block_units - 1));
             acc ^= v0[0] ^ v0[3] ^ v1[1] ^ v1[2] ^ v2[0] ^ v2[2] ^ v3[1] ^ v3[3];
         }
     }
@@ -846,9 +848,9 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const u32x4* __rest
 }
 
 hipError_t launch_hbm_read_probe(const void* src, long long n_blocks, int block_units, const int32_t* perm, int grid,
-                                 uint32_t* sink, hipStream_t st) {
-    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(grid), dim3(256), 0, st, (const u32x4*)src, n_blocks, block_units, perm,
-                       sink);
+                                 bool stream, uint32_t* sink, hipStream_t st) {
+    if (stream) hipLaunchKernelGGL(hbm_read_probe_kernel<1>, dim3(grid), dim3(256), 0, st, (const u32x4*)src, n_blocks, block_units, perm, sink);
+    else hipLaunchKernelGGL(hbm_read_probe_kernel<0>, dim3(grid), dim3(256), 0, st, (const u32x4*)src, n_blocks, block_units, perm, sink);
     return hipGetLastError();
 }
 

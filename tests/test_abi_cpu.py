@@ -238,10 +238,10 @@ def test_single_op_argument_checks(lib):
     assert b"scratch" in lib.sun_last_error()
     # the read probe
     pr = lib.sun_hbm_read_probe
-    assert pr(None, 1 << 20, 4096, None, 256, FAKE, None) == 1 and pr(FAKE, 1 << 20, 4096, None, 256, None, None) == 1
-    assert pr(FAKE, 1 << 20, 1000, None, 256, FAKE, None) == 2 and pr(FAKE, 1 << 20, 0, None, 256, FAKE, None) == 2
-    assert pr(FAKE, 1024, 4096, None, 256, FAKE, None) == 2 and pr(FAKE, 1 << 20, 4096, None, 0, FAKE, None) == 2
-    assert pr(FAKE + 8, 1 << 20, 4096, None, 256, FAKE, None) == 2
+    assert pr(None, 1 << 20, 4096, None, 256, 0, FAKE, None) == 1 and pr(FAKE, 1 << 20, 4096, None, 256, 1, None, None) == 1
+    assert pr(FAKE, 1 << 20, 1000, None, 256, 0, FAKE, None) == 2 and pr(FAKE, 1 << 20, 0, None, 256, 0, FAKE, None) == 2
+    assert pr(FAKE, 1024, 4096, None, 256, 0, FAKE, None) == 2 and pr(FAKE, 1 << 20, 4096, None, 0, 0, FAKE, None) == 2
+    assert pr(FAKE + 8, 1 << 20, 4096, None, 256, 1, FAKE, None) == 2
     assert lib.sun_quantize_w4(FAKE, 0, 4, 256, 64, 0, FAKE, FAKE, FAKE, None) == 2
     assert lib.sun_quantize_w4(FAKE, 0, 4, 200, 128, 0, FAKE, FAKE, FAKE, None) == 2
     assert lib.sun_quantize_w4(None, 0, 4, 256, 128, 0, FAKE, FAKE, FAKE, None) == 1

@@ -167,9 +167,9 @@ def test_read_probe_reads_every_block_once(H):
         part = a[:, quarter * 64:(quarter + 1) * 64]
         want ^= np.bitwise_xor.reduce(part[..., c0].ravel()) ^ np.bitwise_xor.reduce(part[..., c1].ravel())
     perm = torch.randperm(n_blocks, device=H.DEV, generator=g).to(torch.int32)
-    for order, wgs in ((None, 64), (perm, 64), (perm, 300)):
+    for order, wgs, streaming in ((None, 64, False), (perm, 64, False), (perm, 300, True), (None, 64, True)):
         sink = torch.full((wgs * 256,), 12345, dtype=torch.int32, device=H.DEV)
-        sun.sun_hbm_read_probe(src, block, order, wgs, sink)
+        sun.sun_hbm_read_probe(src, block, order, wgs, sink, streaming_loads=streaming)
         torch.cuda.synchronize()
         got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
         assert got == want, f"fold {got:#x} != {want:#x} (order {'shuffled' if order is not None else 'address'}, {wgs} workgroups)"
